@@ -1,0 +1,140 @@
+"""CPU oracle for the segmented-operation hot path.  TEST INFRASTRUCTURE ONLY.
+
+Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of
+``bench.py`` may import this package.  It shares no code with the HIP library
+and never imports it.
+
+``oracle.mmvseg_oracle.c`` holds the sequential definitions (Problem 2.1 of
+Sec. 2 for the segmented scan, the "last element of every segment" definition
+of the segmented sum, and y = A x for SpMV); this module compiles that file
+with gcc and exposes it through ctypes on numpy arrays.  ``oracle.formulations``
+holds the paper's other routes to the same results (SCD, SSCR, the
+block-recursive algorithm, the REVSPEC lemma) in plain numpy / Python, used
+to pin the definitions against each other.
+
+Pins (tests/test_oracle_pins.py, tests/test_formulations.py): the worked
+example printed in Sec. 2, closed forms (all-ones values give segment lengths,
+arithmetic series), library special cases (numpy.cumsum, numpy.add.reduceat,
+reshape-sum, scipy.sparse), invariants, brute force over every flag pattern
+for n <= 12 against an O(n^2) definitional form in Python integers, and the
+paper's SCD / SSCR / block-recursive formulations for several s.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "mmvseg_oracle.c")
+_LIB = os.path.join(_HERE, "libmmvseg_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle (-O2, no fast-math, single thread)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-Wall", "-Wextra", "-fPIC", "-shared",
+                               "-fno-fast-math", "-o", tmp, _SRC])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        u64, vp = ctypes.c_uint64, ctypes.c_void_p
+        lib.oracle_segscan_i8.argtypes = [vp, vp, u64, vp]
+        lib.oracle_segscan_i8.restype = None
+        lib.oracle_segsum_i8.argtypes = [vp, vp, u64, vp]
+        lib.oracle_segsum_i8.restype = u64
+        lib.oracle_segscan_f64.argtypes = [vp, vp, u64, vp]
+        lib.oracle_segscan_f64.restype = None
+        lib.oracle_segscan_f32in.argtypes = [vp, vp, u64, vp]
+        lib.oracle_segscan_f32in.restype = None
+        lib.oracle_segsum_f64.argtypes = [vp, vp, u64, vp]
+        lib.oracle_segsum_f64.restype = u64
+        lib.oracle_spmv_coo.argtypes = [u64, u64, u64, vp, vp, vp, vp, vp]
+        lib.oracle_spmv_coo.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def _ptr(a: np.ndarray) -> int:
+    return a.ctypes.data
+
+
+def _flags_u8(f, n: int) -> np.ndarray:
+    """Flags as one byte per element (non-zero = segment start)."""
+    f = np.asarray(f)
+    if f.shape != (n,):
+        raise ValueError("flags must have the same length as the values")
+    return np.ascontiguousarray(f != 0, dtype=np.uint8)
+
+
+def segscan(x, f) -> np.ndarray:
+    """Segmented inclusive scan (Problem 2.1).
+
+    int8 values -> int32 result with wrap-around; float16/float32/float64
+    values -> float64 result accumulated in float64.
+    """
+    x = np.ascontiguousarray(x)
+    n = x.shape[0]
+    f = _flags_u8(f, n)
+    lib = _load()
+    if x.dtype == np.int8:
+        z = np.empty(n, dtype=np.int32)
+        lib.oracle_segscan_i8(_ptr(x), _ptr(f), n, _ptr(z))
+        return z
+    if x.dtype == np.float32:
+        z = np.empty(n, dtype=np.float64)
+        lib.oracle_segscan_f32in(_ptr(x), _ptr(f), n, _ptr(z))
+        return z
+    if x.dtype in (np.float16, np.float64):
+        xd = np.ascontiguousarray(x, dtype=np.float64)  # exact widening
+        z = np.empty(n, dtype=np.float64)
+        lib.oracle_segscan_f64(_ptr(xd), _ptr(f), n, _ptr(z))
+        return z
+    raise TypeError("unsupported value dtype %s" % x.dtype)
+
+
+def segsum(x, f) -> np.ndarray:
+    """Segmented sum: one value per segment, in segment order (Sec. 2)."""
+    x = np.ascontiguousarray(x)
+    n = x.shape[0]
+    f = _flags_u8(f, n)
+    lib = _load()
+    if n == 0:
+        return np.empty(0, dtype=np.int32 if x.dtype == np.int8 else np.float64)
+    # room for the worst case (every element its own segment); the C loop tests
+    # i == n-1 before it looks at f[i+1], so nothing past the end is read.
+    if x.dtype == np.int8:
+        out = np.empty(n, dtype=np.int32)
+        k = lib.oracle_segsum_i8(_ptr(x), _ptr(f), n, _ptr(out))
+        return out[:k].copy()
+    if x.dtype in (np.float16, np.float32, np.float64):
+        xd = np.ascontiguousarray(x, dtype=np.float64)
+        out = np.empty(n, dtype=np.float64)
+        k = lib.oracle_segsum_f64(_ptr(xd), _ptr(f), n, _ptr(out))
+        return out[:k].copy()
+    raise TypeError("unsupported value dtype %s" % x.dtype)
+
+
+def spmv_coo(n_rows: int, n_cols: int, row, col, val, x) -> np.ndarray:
+    """y = A x in float64 from (row, col, val) triples in any order."""
+    row = np.ascontiguousarray(row, dtype=np.int32)
+    col = np.ascontiguousarray(col, dtype=np.int32)
+    val = np.ascontiguousarray(val, dtype=np.float32)
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    if not (row.shape == col.shape == val.shape) or x.shape != (n_cols,):
+        raise ValueError("shape mismatch")
+    y = np.empty(n_rows, dtype=np.float64)
+    bad = _load().oracle_spmv_coo(n_rows, n_cols, row.shape[0], _ptr(row), _ptr(col), _ptr(val),
+                                  _ptr(x), _ptr(y))
+    if bad:
+        raise ValueError("row or column index out of range")
+    return y
