@@ -1,0 +1,139 @@
+/*
+ * libmmvseg - segmented inclusive scan, segmented sum and COO SpMV on AMD
+ * MI355X (gfx950), computed as small matrix products (tile times triangular
+ * all-ones matrix) on the matrix cores plus vector masking and carry steps,
+ * after "Segmented Operations using Matrix Multiplications" (MMV-RAM).
+ *
+ * Conventions shared by every call
+ * --------------------------------
+ *  - Every pointer whose name starts with d_ is DEVICE memory owned by the
+ *    caller.  The library allocates nothing and keeps no state between calls.
+ *  - Work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL =
+ *    the default stream).  Calls return as soon as the kernels are enqueued;
+ *    results are valid once the caller has synchronised that stream.
+ *  - `d_ws` is scratch of at least mmv_workspace_bytes(...) bytes, 256-byte
+ *    aligned.  The library resets what it needs on every call (inside the
+ *    stream, by a small fill kernel); contents are undefined afterwards, except
+ *    for the status word read by mmv_workspace_status().  Two calls that share
+ *    a workspace must not overlap in time.
+ *  - Value, flag, index and output pointers must be 16-byte aligned.
+ *  - Errors are returned as mmv_status; nothing aborts or throws.  Argument
+ *    errors are detected on the host before anything is launched.
+ *  - Position 0 always opens a segment, whatever its flag says (Problem 2.1 of
+ *    Sec. 2: "if i = 0 or f(i) = 1").
+ *  - n == 0 (nnz == 0) is valid: nothing is read, *d_nseg = 0, y is zero filled.
+ */
+#ifndef MMVSEG_H
+#define MMVSEG_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MMV_OK = 0,
+    MMV_ERR_INVALID_ARG = 1, /* bad enum value, misaligned pointer, size out of range */
+    MMV_ERR_NULL = 2,        /* a required pointer is NULL */
+    MMV_ERR_UNSUPPORTED = 3, /* valid but not implemented combination */
+    MMV_ERR_WORKSPACE = 4,   /* workspace too small or misaligned */
+    MMV_ERR_HIP = 5          /* a HIP launch failed */
+} mmv_status;
+
+/* Input element type / accumulator-and-output type (appendix "Implementation of
+ * operators": fp16 in, fp32 out; int8 in, int32 out; fp32 added for SpMV). */
+typedef enum {
+    MMV_F32_F32 = 0,
+    MMV_F16_F32 = 1,
+    MMV_BF16_F32 = 2,
+    MMV_I8_I32 = 3 /* 32-bit two's complement, wraps (Z/2^32 is a group, Sec. 2) */
+} mmv_dtype;
+
+/* Segment-start flags f of Problem 2.1. */
+typedef enum {
+    MMV_FLAGS_U8 = 0,      /* one byte per element, non-zero = segment start */
+    MMV_FLAGS_PACKED32 = 1 /* bit (i mod 32) of 32-bit word floor(i/32), LSB first;
+                              ceil(n/32) words, bits beyond n ignored */
+} mmv_flag_fmt;
+
+/* How the speculative s-block scans x-bar = MATMUL(x, U_s) (Sec. 1.1, first line
+ * of BlockSegScan in the block-recursive algorithm) are computed. */
+typedef enum {
+    MMV_VARIANT_MFMA = 0,   /* matrix cores: tile times triangular ones matrix, s = 32 */
+    MMV_VARIANT_SHUFFLE = 1 /* ablation: same rows scanned with vector adds and lane shuffles */
+} mmv_variant;
+
+typedef enum { MMV_OP_SEGSCAN = 0, MMV_OP_SEGSUM = 1, MMV_OP_SPMV_COO = 2 } mmv_op;
+
+/* Bytes of scratch needed for one call.  `n` is the vector length (nnz for
+ * SpMV).  Pure host function; returns 0 for invalid arguments. */
+size_t mmv_workspace_bytes(mmv_op op, mmv_dtype dt, mmv_flag_fmt ff, uint64_t n);
+
+/* Segmented inclusive scan (Problem 2.1, Sec. 2):
+ *   z(i) = x(i) if i == 0 or f(i) == 1, else z(i-1) + x(i).
+ * Computed by the block-recursive scheme of Sec. 4.2 (steps 1-6): speculative
+ * scans of rows of s = 32 elements as a matrix product with U_s, REVSPEC to undo
+ * the mis-speculation inside a row, a segmented scan of the row aggregates
+ * (registers, LDS, then decoupled look-back between workgroups instead of the
+ * paper's recursion passes) and the first-segment carry update.
+ *   d_x      n input values of the type `dt` names
+ *   d_flags  n flags in format `ff`
+ *   d_z      n outputs (fp32 or int32); may alias d_x only for MMV_F32_F32
+ * Float results differ from the sequential definition by rounding only. */
+mmv_status mmv_segscan(const void *d_x, const void *d_flags, uint64_t n, void *d_z,
+                       mmv_dtype dt, mmv_flag_fmt ff, mmv_variant v,
+                       void *d_ws, size_t ws_bytes, void *hip_stream);
+
+/* Segmented sum (Sec. 2): the last element of every segment of the segmented
+ * scan, in segment order; equals Algorithm SCD (Sec. 4.1) with the compress
+ * step fused (output index = number of segment ends before the element).
+ *   d_out         room for `out_capacity` sums (fp32 or int32)
+ *   d_nseg        device uint64: receives the true number of segments,
+ *                 1 + #{i >= 1 : f(i) = 1} for n >= 1
+ * Sums with index >= out_capacity are not written (d_nseg still holds the true
+ * count); pass out_capacity = n to be safe. */
+mmv_status mmv_segsum(const void *d_x, const void *d_flags, uint64_t n,
+                      void *d_out, uint64_t out_capacity, uint64_t *d_nseg,
+                      mmv_dtype dt, mmv_flag_fmt ff, mmv_variant v,
+                      void *d_ws, size_t ws_bytes, void *hip_stream);
+
+/* y = A x for a row-sorted COO matrix through the segmented sum (Algorithm
+ * "MMV-RAM CSR SpMV", Sec. 4.3: gather x by column, multiply by the values,
+ * segmented sum over rows; the row indices play the part of the flags:
+ * f(i) = [i == 0 or row(i) != row(i-1)]).
+ *   d_row, d_col  nnz int32 indices, rows non-decreasing (otherwise the result
+ *                 is undefined), 0 <= row < n_rows, 0 <= col < n_cols (not checked)
+ *   d_val, d_x    fp32; d_y  n_rows fp32, fully written: rows without entries
+ *                 are exactly 0 (appendix "SpMV implementation"); duplicate
+ *                 (row, col) pairs add up.
+ * n_rows, n_cols < 2^31. */
+mmv_status mmv_spmv_coo(uint64_t n_rows, uint64_t n_cols, uint64_t nnz,
+                        const int32_t *d_row, const int32_t *d_col, const float *d_val,
+                        const float *d_x, float *d_y, mmv_variant v,
+                        void *d_ws, size_t ws_bytes, void *hip_stream);
+
+/* Reads the status word the last call on this workspace left behind: 0 = fine,
+ * non-zero = a workgroup gave up waiting for a predecessor tile's carry (should
+ * never happen; the result of that call is then invalid).  Synchronises
+ * `hip_stream`.  *h_status is HOST memory. */
+mmv_status mmv_workspace_status(const void *d_ws, void *hip_stream, uint32_t *h_status);
+
+/* Streaming reference for the roofline (the paper compares every primitive with
+ * a memcopy operator, Sec. 5.2.2): reads `in_bytes` from d_src and writes
+ * `out_bytes` to d_dst with 128-bit accesses, each output chunk derived from the
+ * input chunk at the same relative position.  Both sizes must be multiples of
+ * 16; either may be 0. */
+mmv_status mmv_stream_copy(const void *d_src, size_t in_bytes, void *d_dst, size_t out_bytes,
+                           void *hip_stream);
+
+const char *mmv_status_string(mmv_status s);
+
+/* Elements per workgroup tile (for tests that want to straddle tile borders). */
+uint32_t mmv_tile_elems(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MMVSEG_H */

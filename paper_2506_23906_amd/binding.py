@@ -1,0 +1,172 @@
+"""ctypes binding of libmmvseg.so: argument marshalling only.
+
+Every function here has the name of the C entry point it calls
+(include/mmvseg.h) and takes torch tensors that live on the GPU; torch only
+provides the device memory and the HIP stream.  No step of the computation
+runs in Python or in torch, and there is no fallback: if the library has not
+been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch  # imported before the library so that both share one HIP runtime
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmmvseg.so")
+
+MMV_OK = 0
+MMV_F32_F32, MMV_F16_F32, MMV_BF16_F32, MMV_I8_I32 = 0, 1, 2, 3
+MMV_FLAGS_U8, MMV_FLAGS_PACKED32 = 0, 1
+MMV_VARIANT_MFMA, MMV_VARIANT_SHUFFLE = 0, 1
+MMV_OP_SEGSCAN, MMV_OP_SEGSUM, MMV_OP_SPMV_COO = 0, 1, 2
+
+EXPORTS = [
+    "mmv_workspace_bytes", "mmv_segscan", "mmv_segsum", "mmv_spmv_coo", "mmv_workspace_status",
+    "mmv_stream_copy", "mmv_status_string", "mmv_tile_elems",
+]
+
+_DTYPES = {torch.float32: MMV_F32_F32, torch.float16: MMV_F16_F32, torch.bfloat16: MMV_BF16_F32,
+           torch.int8: MMV_I8_I32}
+_OUT_DTYPE = {MMV_F32_F32: torch.float32, MMV_F16_F32: torch.float32, MMV_BF16_F32: torch.float32,
+              MMV_I8_I32: torch.int32}
+_VARIANTS = {"mfma": MMV_VARIANT_MFMA, "shuffle": MMV_VARIANT_SHUFFLE}
+
+_lib = None
+
+
+class MmvError(RuntimeError):
+    pass
+
+
+def load() -> ctypes.CDLL:
+    """Loads libmmvseg.so; raises if it has not been built (there is no fallback path)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise MmvError("libmmvseg.so is not built: run `python -m paper_2506_23906_amd.build` "
+                       "(or __graft_entry__.build()) first")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, u64, sz, i32 = ctypes.c_void_p, ctypes.c_uint64, ctypes.c_size_t, ctypes.c_int
+    lib.mmv_workspace_bytes.argtypes = [i32, i32, i32, u64]
+    lib.mmv_workspace_bytes.restype = sz
+    lib.mmv_segscan.argtypes = [vp, vp, u64, vp, i32, i32, i32, vp, sz, vp]
+    lib.mmv_segscan.restype = i32
+    lib.mmv_segsum.argtypes = [vp, vp, u64, vp, u64, vp, i32, i32, i32, vp, sz, vp]
+    lib.mmv_segsum.restype = i32
+    lib.mmv_spmv_coo.argtypes = [u64, u64, u64, vp, vp, vp, vp, vp, i32, vp, sz, vp]
+    lib.mmv_spmv_coo.restype = i32
+    lib.mmv_workspace_status.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_uint32)]
+    lib.mmv_workspace_status.restype = i32
+    lib.mmv_stream_copy.argtypes = [vp, sz, vp, sz, vp]
+    lib.mmv_stream_copy.restype = i32
+    lib.mmv_status_string.argtypes = [i32]
+    lib.mmv_status_string.restype = ctypes.c_char_p
+    lib.mmv_tile_elems.argtypes = []
+    lib.mmv_tile_elems.restype = ctypes.c_uint32
+    _lib = lib
+    return lib
+
+
+def _check(status: int, what: str) -> None:
+    if status != MMV_OK:
+        raise MmvError("%s failed: %s (status %d)" % (what, load().mmv_status_string(status).decode(), status))
+
+
+def _stream_ptr(stream) -> int:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return int(s.cuda_stream)
+
+
+def _dev(t: torch.Tensor, name: str) -> int:
+    if not t.is_cuda or not t.is_contiguous():
+        raise MmvError("%s must be a contiguous tensor in GPU memory" % name)
+    return t.data_ptr()
+
+
+def _flag_fmt(flags: torch.Tensor) -> int:
+    if flags.dtype == torch.uint8:
+        return MMV_FLAGS_U8
+    if flags.dtype == torch.int32:
+        return MMV_FLAGS_PACKED32
+    raise MmvError("flags must be uint8 (one byte per element) or int32 (bit-packed words)")
+
+
+def mmv_tile_elems() -> int:
+    return int(load().mmv_tile_elems())
+
+
+def mmv_workspace_bytes(op: int, dt: int, ff: int, n: int) -> int:
+    return int(load().mmv_workspace_bytes(op, dt, ff, n))
+
+
+def new_workspace(op: int, dt: int, ff: int, n: int, device=None) -> torch.Tensor:
+    nbytes = max(256, mmv_workspace_bytes(op, dt, ff, n))
+    return torch.empty(nbytes, dtype=torch.uint8, device=device or "cuda")
+
+
+def mmv_segscan(x: torch.Tensor, flags: torch.Tensor, n: int | None = None, z: torch.Tensor | None = None,
+                variant: str = "mfma", ws: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+    """Segmented inclusive scan of x under segment-start flags; returns z (fp32 or int32)."""
+    lib = load()
+    n = x.numel() if n is None else n
+    dt, ff = _DTYPES[x.dtype], _flag_fmt(flags)
+    if z is None:
+        z = torch.empty(n, dtype=_OUT_DTYPE[dt], device=x.device)
+    if ws is None:
+        ws = new_workspace(MMV_OP_SEGSCAN, dt, ff, n, x.device)
+    st = lib.mmv_segscan(_dev(x, "x"), _dev(flags, "flags"), n, _dev(z, "z"), dt, ff, _VARIANTS[variant],
+                         _dev(ws, "ws"), ws.numel(), _stream_ptr(stream))
+    _check(st, "mmv_segscan")
+    return z
+
+
+def mmv_segsum(x: torch.Tensor, flags: torch.Tensor, n: int | None = None, out: torch.Tensor | None = None,
+               nseg: torch.Tensor | None = None, variant: str = "mfma", ws: torch.Tensor | None = None,
+               stream=None):
+    """Segmented sum; returns (out, nseg) where nseg is a one-element int64 device tensor."""
+    lib = load()
+    n = x.numel() if n is None else n
+    dt, ff = _DTYPES[x.dtype], _flag_fmt(flags)
+    if out is None:
+        out = torch.empty(max(n, 1), dtype=_OUT_DTYPE[dt], device=x.device)
+    if nseg is None:
+        nseg = torch.empty(1, dtype=torch.int64, device=x.device)
+    if ws is None:
+        ws = new_workspace(MMV_OP_SEGSUM, dt, ff, n, x.device)
+    st = lib.mmv_segsum(_dev(x, "x"), _dev(flags, "flags"), n, _dev(out, "out"), out.numel(), _dev(nseg, "nseg"),
+                        dt, ff, _VARIANTS[variant], _dev(ws, "ws"), ws.numel(), _stream_ptr(stream))
+    _check(st, "mmv_segsum")
+    return out, nseg
+
+
+def mmv_spmv_coo(n_rows: int, n_cols: int, row: torch.Tensor, col: torch.Tensor, val: torch.Tensor,
+                 x: torch.Tensor, y: torch.Tensor | None = None, variant: str = "mfma",
+                 ws: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+    """y = A x for a row-sorted COO matrix (int32 indices, fp32 values)."""
+    lib = load()
+    nnz = val.numel()
+    if y is None:
+        y = torch.empty(n_rows, dtype=torch.float32, device=val.device)
+    if ws is None:
+        ws = new_workspace(MMV_OP_SPMV_COO, MMV_F32_F32, MMV_FLAGS_PACKED32, nnz, val.device)
+    st = lib.mmv_spmv_coo(n_rows, n_cols, nnz, _dev(row, "row"), _dev(col, "col"), _dev(val, "val"), _dev(x, "x"),
+                          _dev(y, "y"), _VARIANTS[variant], _dev(ws, "ws"), ws.numel(), _stream_ptr(stream))
+    _check(st, "mmv_spmv_coo")
+    return y
+
+
+def mmv_workspace_status(ws: torch.Tensor, stream=None) -> int:
+    h = ctypes.c_uint32(0)
+    _check(load().mmv_workspace_status(_dev(ws, "ws"), _stream_ptr(stream), ctypes.byref(h)), "mmv_workspace_status")
+    return int(h.value)
+
+
+def mmv_stream_copy(src: torch.Tensor, dst: torch.Tensor, in_bytes: int | None = None,
+                    out_bytes: int | None = None, stream=None) -> None:
+    ib = src.numel() * src.element_size() if in_bytes is None else in_bytes
+    ob = dst.numel() * dst.element_size() if out_bytes is None else out_bytes
+    _check(load().mmv_stream_copy(_dev(src, "src"), ib, _dev(dst, "dst"), ob, _stream_ptr(stream)),
+           "mmv_stream_copy")

@@ -28,3 +28,12 @@ def read_golden(name):
 @pytest.fixture(scope="session")
 def golden_sec2():
     return read_golden("worked_example_sec2.txt")
+
+
+@pytest.fixture(scope="session")
+def libmmvseg_path():
+    """Path of the built C-ABI library; builds it only if nothing is there."""
+    from paper_2506_23906_amd import binding, build
+    if not os.path.exists(binding.LIB_PATH):
+        build.build()
+    return binding.LIB_PATH

@@ -1,0 +1,82 @@
+"""Host-only checks of the C-ABI boundary: the library loads, exports every
+symbol the header declares, and rejects bad arguments before launching anything."""
+import ctypes
+import os
+import re
+
+from conftest import ROOT
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "mmvseg.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(mmv_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_and_binding_agree():
+    from paper_2506_23906_amd import binding
+    assert _declared_symbols() == sorted(binding.EXPORTS)
+
+
+def test_library_exports_every_declared_symbol(libmmvseg_path):
+    lib = ctypes.CDLL(libmmvseg_path)
+    for name in _declared_symbols():
+        assert hasattr(lib, name), name
+
+
+def test_host_only_entry_points(libmmvseg_path):
+    from paper_2506_23906_amd import binding as B
+    lib = B.load()
+    tile = B.mmv_tile_elems()
+    assert tile == 8192
+    assert lib.mmv_status_string(0) == b"ok"
+    assert lib.mmv_status_string(4).startswith(b"workspace")
+    # header + one 8-byte descriptor per tile, rounded to 256 bytes
+    assert B.mmv_workspace_bytes(B.MMV_OP_SEGSCAN, B.MMV_I8_I32, B.MMV_FLAGS_PACKED32, 1) == 512
+    n = 1 << 28
+    scan = B.mmv_workspace_bytes(B.MMV_OP_SEGSCAN, B.MMV_I8_I32, B.MMV_FLAGS_PACKED32, n)
+    assert scan == 256 + (n // tile) * 8
+    assert B.mmv_workspace_bytes(B.MMV_OP_SEGSUM, B.MMV_F16_F32, B.MMV_FLAGS_PACKED32, n) == 256 + 2 * (n // tile) * 8
+    assert B.mmv_workspace_bytes(B.MMV_OP_SEGSCAN, B.MMV_I8_I32, B.MMV_FLAGS_U8, n) == scan + n // 8
+    assert B.mmv_workspace_bytes(B.MMV_OP_SEGSCAN, 7, B.MMV_FLAGS_U8, n) == 0      # bad dtype
+    assert B.mmv_workspace_bytes(5, B.MMV_I8_I32, B.MMV_FLAGS_U8, n) == 0          # bad op
+
+
+def test_argument_errors_are_caught_on_the_host(libmmvseg_path):
+    """None of these reaches a kernel launch, so they run without a GPU."""
+    from paper_2506_23906_amd import binding as B
+    lib = B.load()
+    OK, INVALID, NULL, WORKSPACE = 0, 1, 2, 4
+    a16 = 0x10000   # fake, aligned, never dereferenced on these paths
+    # n == 0 is a valid no-op
+    assert lib.mmv_segscan(None, None, 0, None, B.MMV_I8_I32, B.MMV_FLAGS_U8, 0, None, 0, None) == OK
+    assert lib.mmv_segscan(None, None, 0, None, 9, B.MMV_FLAGS_U8, 0, None, 0, None) == INVALID
+    assert lib.mmv_spmv_coo(0, 0, 0, None, None, None, None, None, 0, None, 0, None) == OK
+    # null pointers
+    assert lib.mmv_segscan(None, a16, 10, a16, B.MMV_I8_I32, B.MMV_FLAGS_U8, 0, a16 << 4, 4096, None) == NULL
+    assert lib.mmv_segscan(a16, a16, 10, None, B.MMV_I8_I32, B.MMV_FLAGS_U8, 0, a16 << 4, 4096, None) == NULL
+    assert lib.mmv_segscan(a16, a16, 10, a16 * 2, B.MMV_I8_I32, B.MMV_FLAGS_U8, 0, None, 4096, None) == NULL
+    assert lib.mmv_segsum(a16, a16, 10, a16, 10, None, B.MMV_I8_I32, B.MMV_FLAGS_U8, 0, a16 << 4, 4096, None) == NULL
+    # misaligned pointers, bad enums
+    assert lib.mmv_segscan(a16 + 4, a16, 10, a16 * 2, B.MMV_I8_I32, B.MMV_FLAGS_U8, 0, a16 << 4, 4096, None) == INVALID
+    assert lib.mmv_segscan(a16, a16, 10, a16 * 2, 4, B.MMV_FLAGS_U8, 0, a16 << 4, 4096, None) == INVALID
+    assert lib.mmv_segscan(a16, a16, 10, a16 * 2, B.MMV_I8_I32, 2, 0, a16 << 4, 4096, None) == INVALID
+    assert lib.mmv_segscan(a16, a16, 10, a16 * 2, B.MMV_I8_I32, B.MMV_FLAGS_U8, 2, a16 << 4, 4096, None) == INVALID
+    # output may alias the input only when both are fp32
+    assert lib.mmv_segscan(a16, a16 * 2, 10, a16, B.MMV_I8_I32, B.MMV_FLAGS_U8, 0, a16 << 4, 4096, None) == INVALID
+    # workspace too small / misaligned
+    assert lib.mmv_segscan(a16, a16, 10, a16 * 2, B.MMV_I8_I32, B.MMV_FLAGS_U8, 0, a16 << 4, 16, None) == WORKSPACE
+    assert lib.mmv_segscan(a16, a16, 10, a16 * 2, B.MMV_I8_I32, B.MMV_FLAGS_U8, 0, (a16 << 4) + 16, 4096, None) == WORKSPACE
+    assert lib.mmv_spmv_coo(1 << 31, 4, 4, a16, a16, a16, a16, a16, 0, a16 << 4, 4096, None) == INVALID
+    assert lib.mmv_spmv_coo(4, 4, 4, a16, None, a16, a16, a16, 0, a16 << 4, 4096, None) == NULL
+    assert lib.mmv_stream_copy(a16, 24, a16, 32, None) == INVALID
+    assert lib.mmv_workspace_status(None, None, None) == NULL
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    from paper_2506_23906_amd import binding as B
+    import pytest
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "libmmvseg.so"))
+    with pytest.raises(B.MmvError):
+        B.load()

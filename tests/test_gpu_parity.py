@@ -1,0 +1,229 @@
+"""GPU parity: the HIP path, called through the C-ABI, against the CPU oracle."""
+import itertools
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2506_23906_amd import binding as B
+from paper_2506_23906_amd import workloads as W
+from parity_util import (check_scan, check_sum, dev, packed_dev, random_values, run_segscan, run_segsum)
+
+pytestmark = pytest.mark.gpu
+
+DTYPES = [np.int8, np.float16, np.float32]
+VARIANTS = ["mfma", "shuffle"]
+TILE = 8192
+SIZES = [1, 2, 31, 32, 33, 63, 64, 65, 1023, 1024, 1025, 2047, 2048, 2049, TILE - 1, TILE, TILE + 1,
+         3 * TILE + 77, 16 * TILE + 5]
+
+
+def test_worked_example_on_gpu(golden_sec2):
+    g = golden_sec2
+    f = np.array(g["f"], dtype=np.uint8)
+    for dtype in DTYPES:
+        x = np.array(g["x"], dtype=dtype)
+        for variant in VARIANTS:
+            assert run_segscan(x, f, variant).tolist() == g["segscan"]
+            out, nseg = run_segsum(x, f, variant)
+            assert nseg == 3 and out[:3].tolist() == g["segsum"]
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_sizes_and_densities(dtype, variant):
+    rng = np.random.default_rng(1234)
+    for n in SIZES:
+        for density in (0.0, 0.002, 0.05, 0.5, 1.0):
+            x = random_values(rng, n, dtype)
+            f = W.uniform_density_flags(n, density, seed=n + int(density * 1000))
+            print("segscan/segsum", dtype.__name__, variant, "n=%d density=%g" % (n, density), flush=True)
+            check_scan(run_segscan(x, f, variant), x, f)
+            out, nseg = run_segsum(x, f, variant)
+            check_sum(out, nseg, x, f)
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_every_flag_pattern_n10(variant):
+    """All 2^n flag patterns, n <= 10, laid end to end (each pattern starts a segment)."""
+    for n in (3, 7, 10):
+        pats = np.array(list(itertools.product((0, 1), repeat=n)), dtype=np.uint8)
+        pats[:, 0] = 1
+        f = pats.reshape(-1)
+        x = np.tile(np.arange(1, n + 1, dtype=np.int8) * 5 - 17, len(pats))
+        print("patterns", variant, n, flush=True)
+        check_scan(run_segscan(x, f, variant), x, f)
+        out, nseg = run_segsum(x, f, variant)
+        check_sum(out, nseg, x, f)
+        xf = x.astype(np.float32)
+        assert np.array_equal(run_segscan(xf, f, variant), oracle.segscan(xf, f).astype(np.float32))
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_shift_invariance(dtype):
+    """Prepending k single-element segments moves every row and tile border."""
+    rng = np.random.default_rng(99)
+    n = 2 * TILE + 100
+    x = random_values(rng, n, dtype)
+    f = W.uniform_density_flags(n, 0.01, seed=5)
+    for k in (1, 3, 31, 32, 33, 64, 2047, 2049):
+        xs = np.concatenate([random_values(rng, k, dtype), x])
+        fs = np.concatenate([np.ones(k, dtype=np.uint8), f])
+        print("shift", dtype.__name__, k, flush=True)
+        check_scan(run_segscan(xs, fs), xs, fs)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_u8_flags_equal_packed_flags(dtype):
+    rng = np.random.default_rng(7)
+    for n in (1, 37, 5000, 3 * TILE + 19):
+        x = random_values(rng, n, dtype)
+        f = W.uniform_density_flags(n, 0.03, seed=n)
+        f[f != 0] = rng.integers(1, 256, size=int(f.sum()))      # any non-zero byte is a flag
+        a = run_segscan(x, f, packed=True)
+        b = run_segscan(x, f, packed=False)
+        assert np.array_equal(a, b)
+        check_scan(b, x, f)
+        out, nseg = run_segsum(x, f, packed=False)
+        check_sum(out, nseg, x, f)
+
+
+def test_flag_zero_is_ignored_and_bits_beyond_n_too():
+    x = np.arange(1, 41, dtype=np.int8)
+    f = np.zeros(40, dtype=np.uint8)
+    f[[5, 17]] = 1
+    want = oracle.segscan(x, f)
+    words = W.pack_flags(f).copy()
+    words[1] |= 0xFFFFFF00                       # garbage beyond n = 40
+    ft = torch.from_numpy(words.view(np.int32).copy()).cuda()
+    z = B.mmv_segscan(dev(x), ft, n=40)
+    assert np.array_equal(z.cpu().numpy(), want)
+    out, nseg = B.mmv_segsum(dev(x), ft, n=40)
+    assert int(nseg.item()) == 3
+    assert np.array_equal(out.cpu().numpy()[:3], oracle.segsum(x, f))
+
+
+def test_int32_wraps():
+    n = 17_500_000
+    x = np.full(n, 127, dtype=np.int8)
+    f = np.zeros(n, dtype=np.uint8)
+    z = run_segscan(x, f)
+    check_scan(z, x, f)
+    assert (z < 0).any()
+    out, nseg = run_segsum(x, f)
+    check_sum(out, nseg, x, f)
+
+
+def test_long_segments_across_many_tiles():
+    rng = np.random.default_rng(3)
+    n = 70 * TILE + 123
+    for dtype in DTYPES:
+        x = random_values(rng, n, dtype)
+        f = np.zeros(n, dtype=np.uint8)
+        f[[0, 5, 40 * TILE + 7, 40 * TILE + 8, 69 * TILE]] = 1
+        check_scan(run_segscan(x, f), x, f)
+        out, nseg = run_segsum(x, f)
+        check_sum(out, nseg, x, f)
+
+
+def test_repeated_runs_are_bit_identical_on_integers():
+    x, f = W.segscan_i8_uniform_len(1 << 22, seed=4)
+    xt, ft = dev(x), packed_dev(f)
+    ref = oracle.segscan(x, f)
+    ws = B.new_workspace(B.MMV_OP_SEGSCAN, B.MMV_I8_I32, B.MMV_FLAGS_PACKED32, len(x))
+    for rep in range(20):
+        z = B.mmv_segscan(xt, ft, ws=ws)
+        assert np.array_equal(z.cpu().numpy(), ref), rep
+        assert B.mmv_workspace_status(ws) == 0
+
+
+def test_fp16_subnormal_single_element_segments():
+    """What the matrix cores do with fp16 subnormal inputs (the paper is silent)."""
+    n = 4096
+    x = (np.arange(n) % 1023 + 1).astype(np.uint16).view(np.float16)     # every positive subnormal
+    f = np.ones(n, dtype=np.uint8)
+    for variant in VARIANTS:
+        z = run_segscan(x, f, variant)
+        check_scan(z, x, f)                                              # gate: |err| <= 2e-3
+        kept = np.array_equal(z, x.astype(np.float32))
+        print("fp16 subnormals kept exactly (%s): %s" % (variant, kept))
+
+
+def test_in_place_fp32():
+    x, f = W.scan_sum_f32_bernoulli(3 * TILE + 5, seed=8)
+    xt = dev(x)
+    z = B.mmv_segscan(xt, packed_dev(f), z=xt)
+    check_scan(z.cpu().numpy(), x, f)
+
+
+def test_out_capacity_smaller_than_segment_count():
+    x, f = W.segscan_i8_uniform_len(50_000, max_len=16, seed=9)
+    ref = oracle.segsum(x, f)
+    out, nseg = run_segsum(x, f, out_capacity=100)
+    assert nseg == len(ref)
+    assert np.array_equal(out[:100], ref[:100])
+    assert out.shape[0] == 100
+
+
+def test_empty_input():
+    e = torch.empty(0, dtype=torch.int8, device="cuda")
+    fl = torch.zeros(1, dtype=torch.int32, device="cuda")
+    assert B.mmv_segscan(e, fl, n=0).numel() == 0
+    _, nseg = B.mmv_segsum(e, fl, n=0)
+    assert int(nseg.item()) == 0
+
+
+def test_bf16_inputs():
+    rng = np.random.default_rng(21)
+    n = 2 * TILE + 321
+    xt = torch.from_numpy(rng.standard_normal(n).astype(np.float32)).to(torch.bfloat16).cuda()
+    x32 = xt.float().cpu().numpy()                                    # the bf16 values, exactly
+    f = W.uniform_density_flags(n, 0.02, seed=2)
+    for variant in VARIANTS:
+        z = run_segscan(x32, f, variant, xt=xt)
+        check_scan(z, x32, f, tol=1e-2)
+        out, nseg = run_segsum(x32, f, variant, xt=xt)
+        check_sum(out, nseg, x32, f, tol=1e-2)
+
+
+# ---- the benchmark workloads: scaled twins, then full size ------------------------------------------
+
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_workload1_f32_bernoulli_full(variant):
+    x, f = W.scan_sum_f32_bernoulli()
+    check_scan(run_segscan(x, f, variant), x, f)
+    out, nseg = run_segsum(x, f, variant)
+    check_sum(out, nseg, x, f)
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("log2n", [20, 24])
+def test_workload2_f16_geometric(log2n, variant):
+    x, f = W.segsum_f16_geometric(1 << log2n)
+    out, nseg = run_segsum(x, f, variant)
+    worst = check_sum(out, nseg, x, f)
+    print("workload 2 n=2^%d %s: segments %d, worst |err|/max(A,1) = %.3g" % (log2n, variant, nseg, worst))
+    if log2n == 20:
+        check_scan(run_segscan(x, f, variant), x, f)
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("log2n", [22, 28])
+def test_workload3_i8_uniform_len(log2n, variant):
+    x, f = W.segscan_i8_uniform_len(1 << log2n)
+    z = run_segscan(x, f, variant)
+    check_scan(z, x, f)
+    if log2n == 22:
+        out, nseg = run_segsum(x, f, variant)
+        check_sum(out, nseg, x, f)
+
+
+@pytest.mark.parametrize("log2n", [22, 30])
+def test_workload5_stress_three_regimes(log2n):
+    x, f = W.stress_f32_three_regimes(1 << log2n)
+    xt = dev(x)
+    z = run_segscan(x, f, "mfma", xt=xt)
+    del xt
+    worst = check_scan(z, x, f)
+    print("workload 5 n=2^%d: worst |err|/max(A,1) = %.3g" % (log2n, worst))
