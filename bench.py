@@ -1,0 +1,303 @@
+#!/usr/bin/env python3
+"""Benchmark of the segmented-operation hot path on one MI355X.
+
+Default run (the contract line): workload 3 of the benchmark spec, the segmented
+inclusive scan of n = 2^28 int8 values into int32 with segment lengths uniform
+in [1, 4096] and bit-packed flags.  One "step" is one mmv_segscan call on
+inputs that already sit in HBM: workspace reset kernel + the single-pass scan
+kernel.  Prints ONE JSON line with the whole-job throughput (G elements/s), the
+HBM roofline of the scan kernel measured with HIP events inside the timed
+region, and the CPU oracle timed on the host beside it.
+
+`--report FILE` additionally times all five workloads, both variants (matrix
+cores / shuffle-only ablation) and the streaming-copy reference with the same
+read:write mix, and writes the table as JSON lines to FILE.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+
+
+class HipEvents:
+    """hipEvent_t handles through the HIP runtime that torch has loaded."""
+
+    def __init__(self):
+        import torch
+        path = os.path.join(os.path.dirname(torch.__file__), "lib", "libamdhip64.so")
+        self.hip = ctypes.CDLL(path if os.path.exists(path) else "libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self.made = []
+
+    def create(self) -> int:
+        ev = ctypes.c_void_p()
+        if self.hip.hipEventCreate(ctypes.byref(ev)) != 0:
+            raise RuntimeError("hipEventCreate failed")
+        self.made.append(ev)
+        return ev.value
+
+    def elapsed_ms(self, a: int, b: int) -> float:
+        ms = ctypes.c_float()
+        if self.hip.hipEventElapsedTime(ctypes.byref(ms), a, b) != 0:
+            raise RuntimeError("hipEventElapsedTime failed")
+        return float(ms.value)
+
+    def destroy_all(self):
+        for ev in self.made:
+            self.hip.hipEventDestroy(ev)
+        self.made = []
+
+
+def time_steps(step, steps: int, warmup: int, events: HipEvents | None):
+    """Runs warmup + steps calls of step(); returns (wall ms per step, mean kernel ms or None)."""
+    import torch
+    from paper_2506_23906_amd import binding as B
+    for _ in range(warmup):
+        step()
+    pairs = [(events.create(), events.create()) for _ in range(steps)] if events else []
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(steps):
+        if events:
+            B.mmv_set_kernel_events(*pairs[k])
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    kernel_ms = None
+    if events:
+        B.mmv_set_kernel_events(None, None)
+        kernel_ms = float(np.mean([events.elapsed_ms(a, b) for a, b in pairs]))
+        events.destroy_all()
+    return (t1 - t0) * 1e3 / steps, kernel_ms
+
+
+def load_traffic(name: str):
+    """HBM bytes per launch from the rocprofv3 --pmc runs, if a summary has been committed."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(path):
+        with open(path) as fh:
+            return json.load(fh).get(name)
+    return None
+
+
+def oracle_baseline(x, f, repeats: int = 3):
+    """The sequential CPU oracle, as it stands, on the same workload (one thread)."""
+    import oracle
+    best = None
+    for _ in range(repeats):
+        t0 = time.perf_counter()
+        oracle.segscan(x, f)
+        dt = time.perf_counter() - t0
+        best = dt if best is None else min(best, dt)
+    return best
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--log2n", type=int, default=28, help="vector length of the headline workload")
+    ap.add_argument("--variant", default="mfma", choices=["mfma", "shuffle"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--report", default=None, help="also time every workload and write JSON lines here")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (every box has one GPU; see DESIGN.md, "
+              "'How the path would shard'); --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2506_23906_amd import binding as B
+    from paper_2506_23906_amd import workloads as W
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    B.load()
+    events = HipEvents()
+
+    n = 1 << args.log2n
+    x, f = W.segscan_i8_uniform_len(n)
+    xt = torch.from_numpy(x).cuda()
+    ft = torch.from_numpy(W.pack_flags(f).view(np.int32)).cuda()
+    zt = torch.empty(n, dtype=torch.int32, device="cuda")
+    ws = B.new_workspace(B.MMV_OP_SEGSCAN, B.MMV_I8_I32, B.MMV_FLAGS_PACKED32, n)
+
+    def step():
+        B.mmv_segscan(xt, ft, n=n, z=zt, variant=args.variant, ws=ws)
+
+    ms_per_step, kernel_ms = time_steps(step, args.steps, args.warmup, events)
+    assert B.mmv_workspace_status(ws) == 0
+    algo_bytes = n * (1 + 4) + ((n + 31) // 32) * 4          # values in, result out, packed flags in
+    achieved = algo_bytes / (kernel_ms * 1e-3) / 1e9
+    line = {
+        "metric": "segmented-scan G elem/s + achieved HBM GB/s (% of peak), n=2^%d" % args.log2n,
+        "value": n / (ms_per_step * 1e-3) / 1e9,
+        "unit": "Gelem/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "i32",
+        "data": "synthetic",
+        "config": {
+            "workload": "segscan_i8_uniform_len: segmented inclusive scan, n=2^%d int8 in [-8,8] -> int32, "
+                        "segment lengths U{1..4096}, bit-packed flags, seed %d"
+                        % (args.log2n, W.SEEDS["segscan_i8_uniform_len"]),
+            "variant": args.variant,
+            "tile_elems": B.mmv_tile_elems(),
+            "kernel_ms": kernel_ms,
+            "hbm_frac_of_peak_whole_step": algo_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        },
+        "roofline": {
+            "bound": "hbm",
+            "achieved": achieved,
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS,
+            "traffic": load_traffic("segscan_i8_2p%d_%s" % (args.log2n, args.variant)),
+        },
+    }
+    if not args.no_cpu_baseline:
+        secs = oracle_baseline(x, f)
+        line["cpu_baseline"] = {
+            "value": n / secs / 1e9,
+            "unit": "Gelem/s",
+            "cores": 1,
+            "kind": "oracle",
+            "sample": "the whole n=2^%d workload, sequential C loop (gcc -O2), best of 3 runs, "
+                      "host has %d logical CPUs" % (args.log2n, os.cpu_count()),
+        }
+    if args.report:
+        write_report(args, events)
+    print(json.dumps(line))
+    return 0
+
+
+# ---- the wider report (not part of the contract line) -------------------------------------------------------
+
+def write_report(args, events: HipEvents) -> None:
+    import torch
+    from paper_2506_23906_amd import binding as B
+    from paper_2506_23906_amd import workloads as W
+    rows = []
+
+    def emit(**kw):
+        rows.append(kw)
+        print("[report] " + json.dumps(kw), file=sys.stderr, flush=True)
+
+    def copy_rate(in_bytes: int, out_bytes: int, steps=50):
+        src = torch.empty(max(in_bytes, 16), dtype=torch.uint8, device="cuda").zero_()
+        dst = torch.empty(max(out_bytes, 16), dtype=torch.uint8, device="cuda")
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for _ in range(5):
+            B.mmv_stream_copy(src, dst, in_bytes, out_bytes)
+        a.record()
+        for _ in range(steps):
+            B.mmv_stream_copy(src, dst, in_bytes, out_bytes)
+        b.record()
+        torch.cuda.synchronize()
+        ms = a.elapsed_time(b) / steps
+        return (in_bytes + out_bytes) / (ms * 1e-3) / 1e9, ms
+
+    def run(name, n, algo_bytes, step, ws, steps=args.steps):
+        wall, kern = time_steps(step, steps, args.warmup, events)
+        assert B.mmv_workspace_status(ws) == 0
+        emit(workload=name, n=n, ms_per_step=wall, kernel_ms=kern, gelem_s=n / (wall * 1e-3) / 1e9,
+             algo_bytes=algo_bytes, gb_s_kernel=algo_bytes / (kern * 1e-3) / 1e9,
+             frac_of_peak_kernel=algo_bytes / (kern * 1e-3) / 1e9 / HBM_PEAK_GBS)
+
+    # copy references: 1:4 (int8 -> int32), 1:1 (fp32 -> fp32), read only
+    for label, ib, ob in [("copy 1B:4B, 256 MiB in", 1 << 28, 1 << 30), ("copy 4B:4B, 1 GiB in", 1 << 30, 1 << 30),
+                          ("read only, 1 GiB", 1 << 30, 0), ("write only, 1 GiB", 0, 1 << 30)]:
+        gbs, ms = copy_rate(ib, ob)
+        emit(workload=label, ms=ms, gb_s=gbs, frac_of_peak=gbs / HBM_PEAK_GBS)
+
+    # workload 1
+    x, f = W.scan_sum_f32_bernoulli()
+    n = len(x)
+    xt, ft = torch.from_numpy(x).cuda(), torch.from_numpy(W.pack_flags(f).view(np.int32)).cuda()
+    for variant in ("mfma", "shuffle"):
+        zt = torch.empty(n, dtype=torch.float32, device="cuda")
+        ws = B.new_workspace(B.MMV_OP_SEGSCAN, B.MMV_F32_F32, B.MMV_FLAGS_PACKED32, n)
+        run("1 segscan f32 n=2^16 bernoulli(1/64) " + variant, n, n * 8 + n // 8,
+            lambda: B.mmv_segscan(xt, ft, n=n, z=zt, variant=variant, ws=ws), ws)
+        out = torch.empty(n, dtype=torch.float32, device="cuda")
+        nseg = torch.empty(1, dtype=torch.int64, device="cuda")
+        ws2 = B.new_workspace(B.MMV_OP_SEGSUM, B.MMV_F32_F32, B.MMV_FLAGS_PACKED32, n)
+        run("1 segsum f32 n=2^16 bernoulli(1/64) " + variant, n, n * 4 + n // 8 + int(f.sum()) * 4,
+            lambda: B.mmv_segsum(xt, ft, n=n, out=out, nseg=nseg, variant=variant, ws=ws2), ws2)
+
+    # workload 2
+    x, f = W.segsum_f16_geometric()
+    n = len(x)
+    xt, ft = torch.from_numpy(x).cuda(), torch.from_numpy(W.pack_flags(f).view(np.int32)).cuda()
+    nsegs = int(f.sum())
+    for variant in ("mfma", "shuffle"):
+        out = torch.empty(nsegs + 16, dtype=torch.float32, device="cuda")
+        nseg = torch.empty(1, dtype=torch.int64, device="cuda")
+        ws = B.new_workspace(B.MMV_OP_SEGSUM, B.MMV_F16_F32, B.MMV_FLAGS_PACKED32, n)
+        run("2 segsum f16 n=2^24 geometric(32) " + variant, n, n * 2 + n // 8 + nsegs * 4,
+            lambda: B.mmv_segsum(xt, ft, n=n, out=out, nseg=nseg, variant=variant, ws=ws), ws)
+
+    # workload 3, both variants, and a flag-density sweep on the same values
+    x, f = W.segscan_i8_uniform_len(1 << args.log2n)
+    n = len(x)
+    xt, ft = torch.from_numpy(x).cuda(), torch.from_numpy(W.pack_flags(f).view(np.int32)).cuda()
+    zt = torch.empty(n, dtype=torch.int32, device="cuda")
+    ws = B.new_workspace(B.MMV_OP_SEGSCAN, B.MMV_I8_I32, B.MMV_FLAGS_PACKED32, n)
+    for variant in ("mfma", "shuffle"):
+        run("3 segscan i8 n=2^%d U{1..4096} %s" % (args.log2n, variant), n, n * 5 + n // 8,
+            lambda: B.mmv_segscan(xt, ft, n=n, z=zt, variant=variant, ws=ws), ws)
+    for density in (0.0, 1e-4, 1e-3, 3e-3, 1e-2, 0.1, 1.0):
+        fd = torch.from_numpy(W.pack_flags(W.uniform_density_flags(n, density, 77)).view(np.int32)).cuda()
+        for variant in ("mfma", "shuffle"):
+            run("density sweep i8 n=2^%d density=%g %s" % (args.log2n, density, variant), n, n * 5 + n // 8,
+                lambda: B.mmv_segscan(xt, fd, n=n, z=zt, variant=variant, ws=ws), ws, steps=30)
+    del xt, ft, zt
+
+    # workload 4
+    nr = 1 << 20
+    row, col, val, xv = W.spmv_coo_zipf(nr, nr, 1 << 25)
+    nnz = len(val)
+    rt, ct, vt, xvt = (torch.from_numpy(a).cuda() for a in (row, col, val, xv))
+    yt = torch.empty(nr, dtype=torch.float32, device="cuda")
+    ws = B.new_workspace(B.MMV_OP_SPMV_COO, B.MMV_F32_F32, B.MMV_FLAGS_PACKED32, nnz)
+    for variant in ("mfma", "shuffle"):
+        run("4 spmv coo 2^20 x 2^20 nnz=%d zipf(1.5) %s" % (nnz, variant), nnz, nnz * 12 + 2 * nr * 4,
+            lambda: B.mmv_spmv_coo(nr, nr, rt, ct, vt, xvt, y=yt, variant=variant, ws=ws), ws)
+    del rt, ct, vt, xvt
+
+    # workload 5
+    x, f = W.stress_f32_three_regimes(1 << 30)
+    n = len(x)
+    xt, ft = torch.from_numpy(x).cuda(), torch.from_numpy(W.pack_flags(f).view(np.int32)).cuda()
+    zt = torch.empty(n, dtype=torch.float32, device="cuda")
+    ws = B.new_workspace(B.MMV_OP_SEGSCAN, B.MMV_F32_F32, B.MMV_FLAGS_PACKED32, n)
+    for variant in ("mfma", "shuffle"):
+        run("5 stress segscan f32 n=2^30 " + variant, n, n * 8 + n // 8,
+            lambda: B.mmv_segscan(xt, ft, n=n, z=zt, variant=variant, ws=ws), ws, steps=20)
+
+    with open(args.report, "w") as fh:
+        for r in rows:
+            fh.write(json.dumps(r) + "\n")
+
+
+if __name__ == "__main__":
+    sys.exit(main())

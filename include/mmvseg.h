@@ -7,7 +7,8 @@
  * Conventions shared by every call
  * --------------------------------
  *  - Every pointer whose name starts with d_ is DEVICE memory owned by the
- *    caller.  The library allocates nothing and keeps no state between calls.
+ *    caller.  The library allocates nothing and keeps no state between calls
+ *    (apart from the optional timing events of mmv_set_kernel_events).
  *  - Work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL =
  *    the default stream).  Calls return as soon as the kernels are enqueued;
  *    results are valid once the caller has synchronised that stream.
@@ -127,6 +128,14 @@ mmv_status mmv_workspace_status(const void *d_ws, void *hip_stream, uint32_t *h_
  * 16; either may be 0. */
 mmv_status mmv_stream_copy(const void *d_src, size_t in_bytes, void *d_dst, size_t out_bytes,
                            void *hip_stream);
+
+/* Instrumentation for benchmarks: from now on, every mmv_segscan / mmv_segsum /
+ * mmv_spmv_coo call made by the calling host thread records `ev_start` (a
+ * hipEvent_t passed as void*) on the call's stream immediately before its main
+ * kernel and `ev_stop` immediately after it, so that the kernel can be timed
+ * apart from the workspace reset.  The events stay owned by the caller.  Pass
+ * NULL, NULL to switch it off (the default).  Per-thread setting. */
+mmv_status mmv_set_kernel_events(void *ev_start, void *ev_stop);
 
 const char *mmv_status_string(mmv_status s);
 

@@ -24,7 +24,7 @@ MMV_OP_SEGSCAN, MMV_OP_SEGSUM, MMV_OP_SPMV_COO = 0, 1, 2
 
 EXPORTS = [
     "mmv_workspace_bytes", "mmv_segscan", "mmv_segsum", "mmv_spmv_coo", "mmv_workspace_status",
-    "mmv_stream_copy", "mmv_status_string", "mmv_tile_elems",
+    "mmv_stream_copy", "mmv_status_string", "mmv_tile_elems", "mmv_set_kernel_events",
 ]
 
 _DTYPES = {torch.float32: MMV_F32_F32, torch.float16: MMV_F16_F32, torch.bfloat16: MMV_BF16_F32,
@@ -64,6 +64,8 @@ def load() -> ctypes.CDLL:
     lib.mmv_stream_copy.restype = i32
     lib.mmv_status_string.argtypes = [i32]
     lib.mmv_status_string.restype = ctypes.c_char_p
+    lib.mmv_set_kernel_events.argtypes = [vp, vp]
+    lib.mmv_set_kernel_events.restype = i32
     lib.mmv_tile_elems.argtypes = []
     lib.mmv_tile_elems.restype = ctypes.c_uint32
     _lib = lib
@@ -170,3 +172,8 @@ def mmv_stream_copy(src: torch.Tensor, dst: torch.Tensor, in_bytes: int | None =
     ob = dst.numel() * dst.element_size() if out_bytes is None else out_bytes
     _check(load().mmv_stream_copy(_dev(src, "src"), ib, _dev(dst, "dst"), ob, _stream_ptr(stream)),
            "mmv_stream_copy")
+
+
+def mmv_set_kernel_events(ev_start: int | None, ev_stop: int | None) -> None:
+    """ev_start / ev_stop are hipEvent_t handles as integers (or None to switch off)."""
+    _check(load().mmv_set_kernel_events(ev_start, ev_stop), "mmv_set_kernel_events")

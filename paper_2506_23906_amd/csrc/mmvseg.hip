@@ -684,13 +684,20 @@ WsLayout ws_layout(mmv_op op, mmv_flag_fmt ff, uint64_t n) {
     return L;
 }
 
+// Optional instrumentation (mmv_set_kernel_events): events recorded right before and
+// right after the main kernel of a call made by this host thread.
+thread_local hipEvent_t tl_ev_start = nullptr, tl_ev_stop = nullptr;
+
 template <typename TT, int kOp>
 hipError_t launch_seg(const Params &P, mmv_variant v, hipStream_t s) {
+    if (tl_ev_start && hipEventRecord(tl_ev_start, s) != hipSuccess) return hipErrorUnknown;
     if (v == MMV_VARIANT_MFMA)
         seg_kernel<TT, kOp, true><<<P.num_tiles, kThreads, 0, s>>>(P);
     else
         seg_kernel<TT, kOp, false><<<P.num_tiles, kThreads, 0, s>>>(P);
-    return hipGetLastError();
+    const hipError_t e = hipGetLastError();
+    if (tl_ev_stop && hipEventRecord(tl_ev_stop, s) != hipSuccess) return hipErrorUnknown;
+    return e;
 }
 
 template <int kOp> hipError_t launch_dt(const Params &P, mmv_dtype dt, mmv_variant v, hipStream_t s) {
@@ -863,6 +870,12 @@ mmv_status mmv_stream_copy(const void *d_src, size_t in_bytes, void *d_dst, size
     else return MMV_ERR_UNSUPPORTED;
 #undef MMV_COPY
     return hipGetLastError() == hipSuccess ? MMV_OK : MMV_ERR_HIP;
+}
+
+mmv_status mmv_set_kernel_events(void *ev_start, void *ev_stop) {
+    tl_ev_start = (hipEvent_t)ev_start;
+    tl_ev_stop = (hipEvent_t)ev_stop;
+    return MMV_OK;
 }
 
 const char *mmv_status_string(mmv_status s) {
