@@ -144,7 +144,7 @@ def main() -> int:
     algo_bytes = n * (1 + 4) + ((n + 31) // 32) * 4          # values in, result out, packed flags in
     achieved = algo_bytes / (kernel_ms * 1e-3) / 1e9
     line = {
-        "metric": "segmented-scan G elem/s + achieved HBM GB/s (% of peak), n=2^%d" % args.log2n,
+        "metric": "segmented-scan G elem/s + achieved HBM GB/s (%% of peak), n=2^%d" % args.log2n,
         "value": n / (ms_per_step * 1e-3) / 1e9,
         "unit": "Gelem/s",
         "n_gpus": 1,
@@ -161,7 +161,7 @@ def main() -> int:
                         "segment lengths U{1..4096}, bit-packed flags, seed %d"
                         % (args.log2n, W.SEEDS["segscan_i8_uniform_len"]),
             "variant": args.variant,
-            "tile_elems": B.mmv_tile_elems(),
+            "tile_elems": B.mmv_tile_elems(B.MMV_I8_I32),
             "kernel_ms": kernel_ms,
             "hbm_frac_of_peak_whole_step": algo_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         },

@@ -139,8 +139,10 @@ mmv_status mmv_set_kernel_events(void *ev_start, void *ev_stop);
 
 const char *mmv_status_string(mmv_status s);
 
-/* Elements per workgroup tile (for tests that want to straddle tile borders). */
-uint32_t mmv_tile_elems(void);
+/* Elements per workgroup tile for an input type (for tests that want to straddle
+ * tile borders and for sizing: the workspace holds one 8-byte descriptor per tile).
+ * 0 for an invalid type. */
+uint32_t mmv_tile_elems(mmv_dtype dt);
 
 #ifdef __cplusplus
 }

@@ -28,12 +28,14 @@
 
 namespace {
 
-constexpr int kWaves = 4;
+#ifndef MMV_WAVES
+#define MMV_WAVES 4
+#endif
+constexpr int kWaves = MMV_WAVES;
 constexpr int kThreads = kWaves * 64;
 constexpr int kS = 32;                          // row length = MFMA tile edge
-constexpr int kRowsPerWave = 64;                // one row per lane
-constexpr int kWaveElems = kS * kRowsPerWave;   // 2048
-constexpr int kTileElems = kWaves * kWaveElems; // 8192
+constexpr int kRowsPerChunk = 64;               // a chunk = 64 rows, one per lane = two 32x32 tiles
+constexpr int kChunkElems = kS * kRowsPerChunk; // 2048
 constexpr int kRowStride = 36;                  // dwords per LDS row: 4 meta + 32 values
 constexpr int kSlotF = 0;                       // flag word of the row
 constexpr int kSlotE = 1;                       // segment-end mask of the row
@@ -77,7 +79,19 @@ struct Params {
     uint64_t *desc_v;       // value descriptors, one per tile
     uint64_t *desc_c;       // count descriptors (sum)
     uint32_t num_tiles;
+#ifdef MMV_TRACE
+    uint64_t *trace;        // 8 timestamps per tile (development builds only)
+#endif
 };
+
+#ifdef MMV_TRACE
+#define MMV_STAMP(k)                                                                     \
+    do {                                                                                 \
+        if (tid == 0 && P.trace) P.trace[(uint64_t)tile * 8 + (k)] = wall_clock64();     \
+    } while (0)
+#else
+#define MMV_STAMP(k) do { } while (0)
+#endif
 
 // ---- small helpers -----------------------------------------------------------------------
 
@@ -143,140 +157,157 @@ struct TI8 {
     typedef int8_t in_t;
     typedef uint32_t acc_t;  // int32 with wrap-around
     static constexpr int kEpl = 16;  // elements per 128-bit load
+#ifndef MMV_CPW_I8
+#define MMV_CPW_I8 4
+#endif
+    static constexpr int kCpw = MMV_CPW_I8;  // chunks of 2048 elements per wave: tile = 4 waves x 4 x 2048
     static __device__ __forceinline__ acc_t widen(in_t v) { return (acc_t)(int32_t)v; }
 };
 struct TF16 {
     typedef _Float16 in_t;
     typedef float acc_t;
     static constexpr int kEpl = 8;
+    static constexpr int kCpw = 4;
     static __device__ __forceinline__ acc_t widen(in_t v) { return (float)v; }
 };
 struct TBF16 {
     typedef __bf16 in_t;
     typedef float acc_t;
     static constexpr int kEpl = 8;
+    static constexpr int kCpw = 4;
     static __device__ __forceinline__ acc_t widen(in_t v) { return (float)v; }
 };
 struct TF32 {
     typedef float in_t;
     typedef float acc_t;
     static constexpr int kEpl = 4;
+    static constexpr int kCpw = 2;
     static __device__ __forceinline__ acc_t widen(in_t v) { return v; }
 };
+struct TInt {  // column indices of the COO matrix, loaded in the same layout as its values
+    typedef int32_t in_t;
+    static constexpr int kEpl = 4;
+};
 
-// Loads kCount consecutive elements starting at element index e0 (e0 * sizeof is a
-// multiple of 16 when kCount * sizeof == 16); elements at or beyond n read as zero.
-template <typename T, int kCount>
-__device__ __forceinline__ void load_elems(const T *x, uint64_t e0, uint64_t n, bool full, T (&dst)[kCount]) {
-    static_assert(kCount * sizeof(T) == 16, "one 128-bit load");
-    if (full) {
-        *reinterpret_cast<v4u *>(dst) = *reinterpret_cast<const v4u *>(x + e0);
-    } else {
-#pragma unroll
-        for (int i = 0; i < kCount; ++i) dst[i] = (e0 + i < n) ? x[e0 + i] : T(0);
+// ---- raw inputs of one wave chunk (2048 elements), kept in registers ---------------------------------
+//
+// A lane holds 2 * K 128-bit words, K = 1 (int8), 2 (fp16, bf16), 4 (fp32) per
+// 32x32 tile.  They are loaded one tile ahead of their use (software pipeline of
+// the persistent workgroup loop), so that HBM latency overlaps the previous
+// tile's look-back and stores.
+//
+// Matrix-core layout: one 32x32 tile = 32 rows ("runs") of 32 consecutive
+// elements.  D = A B with A = U_s^T (lower-triangular ones, M x K) and B = X^T
+// (K x N, column n = run n): D(m, n) = sum_{k <= m} X(n, k) = x-bar at position m
+// of run n.  Lane (c = lane % 32, h = lane / 32) holds row c of A and column c of
+// B for the K indices half h owns; A and B use the same (half, register, byte) ->
+// K map, so only "which positions does half h hold" has to agree between them.
+// Result: acc[v] of lane (n, h) = D(8 (v / 4) + 4 h + v % 4, n).
+//
+// Shuffle layout (ablation): lane l holds kEpl consecutive elements, striped.
+
+template <typename TT, bool kMfma> __device__ __forceinline__ int raw_offset(int i, int lane) {
+    constexpr int K = 16 / TT::kEpl;
+    if (kMfma) {
+        const int c = lane & 31, h = lane >> 5;
+        return 32 * c + (K == 2 ? 16 * i + 8 * h : 16 * h + 4 * i);
     }
+    return (1024 / K) * i + TT::kEpl * lane;
 }
 
-// ---- step 1, matrix-core form ---------------------------------------------------------------------
-//
-// One 32x32 tile = 32 rows ("runs") of 32 consecutive elements.  D = A B with
-// A = U_s^T (lower-triangular ones, M x K) and B = X^T (K x N, column n = run n):
-// D(m, n) = sum_{k <= m} X(n, k) = x-bar at position m of run n.
-// Operand registers: lane (c = lane % 32, h = lane / 32) holds, for A, row c and
-// for B, column c, with the K indices that half h owns.  A and B use the same
-// (half, register, byte) -> K map, so only "which positions does half h hold"
-// has to agree between the two operands.
-// Result registers: acc[v] of lane (n, h) = D(8 (v / 4) + 4 h + v % 4, n).
-
-template <typename TT> struct Spec;
-
-template <> struct Spec<TI8> {
-    // lane (n, h) loads positions 16 h .. 16 h + 15 of run n: one 128-bit load
-    static __device__ __forceinline__ void run(const int8_t *x, uint64_t tile0, uint64_t n, bool full, int lane,
-                                               uint32_t (&acc)[16]) {
-        const int c = lane & 31, h = lane >> 5;
-        alignas(16) int8_t b[16];
-        load_elems<int8_t, 16>(x, tile0 + 32 * c + 16 * h, n, full, b);
-        v4i a;
+// 128 bits = 16 / sizeof(T) consecutive elements starting at element e0; elements
+// at or beyond n read as zero.
+template <typename T> __device__ __forceinline__ v4u load128(const T *x, uint64_t e0, uint64_t n, bool full) {
+    if (full) return *reinterpret_cast<const v4u *>(x + e0);
+    constexpr int kCount = 16 / sizeof(T);
+    alignas(16) T tmp[kCount];
 #pragma unroll
-        for (int d = 0; d < 4; ++d) {  // bytes 4d..4d+3 = positions 16h+4d+j: one where position <= c
+    for (int i = 0; i < kCount; ++i) tmp[i] = (e0 + i < n) ? x[e0 + i] : T(0);
+    return *reinterpret_cast<v4u *>(tmp);
+}
+
+// The 2 * K words of one chunk (two 32x32 tiles) starting at element chunk_base.
+template <typename TT, bool kMfma>
+__device__ __forceinline__ void load_raw(const typename TT::in_t *x, uint64_t chunk_base, uint64_t n, int lane,
+                                         v4u (&raw)[2 * (16 / TT::kEpl)]) {
+    constexpr int K = 16 / TT::kEpl;
+    const bool full = chunk_base + kChunkElems <= n;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int i = 0; i < K; ++i)
+            raw[t * K + i] = load128(x, chunk_base + 1024u * t + raw_offset<TT, kMfma>(i, lane), n, full);
+}
+
+// ---- step 1, matrix-core form: x-bar of 32x32 tile t from the raw registers ------------------------------
+
+template <typename TT> struct SpecMfma;
+
+template <> struct SpecMfma<TI8> {
+    static __device__ __forceinline__ void run(const v4u *raw, int lane, uint32_t (&acc)[16]) {
+        const int c = lane & 31, h = lane >> 5;
+        v4i a;  // bytes 4d..4d+3 = positions 16h+4d+j: one where position <= c
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
             int cnt = c - (16 * h + 4 * d) + 1;
             cnt = cnt < 0 ? 0 : (cnt > 4 ? 4 : cnt);
             a[d] = cnt == 4 ? 0x01010101 : (int)(0x01010101u & ((1u << (8 * cnt)) - 1u));
         }
         v16i r = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-        r = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, *reinterpret_cast<v4i *>(b), r, 0, 0, 0);
+        r = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, __builtin_bit_cast(v4i, raw[0]), r, 0, 0, 0);
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[v] = (uint32_t)r[v];
     }
 };
 
-template <> struct Spec<TF16> {
-    // two K-steps of 16: lane (n, h) loads positions 16 ks + 8 h .. + 7 of run n
-    static __device__ __forceinline__ void run(const _Float16 *x, uint64_t tile0, uint64_t n, bool full, int lane,
-                                               float (&acc)[16]) {
+template <> struct SpecMfma<TF16> {
+    // two K-steps of 16: in step ks half h supplies positions 16 ks + 8 h .. + 7
+    static __device__ __forceinline__ void run(const v4u *raw, int lane, float (&acc)[16]) {
         const int c = lane & 31, h = lane >> 5;
         v16f r = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
-            alignas(16) _Float16 b[8];
-            load_elems<_Float16, 8>(x, tile0 + 32 * c + 16 * ks + 8 * h, n, full, b);
             v8h a;
 #pragma unroll
             for (int j = 0; j < 8; ++j) a[j] = (16 * ks + 8 * h + j <= c) ? (_Float16)1.0f : (_Float16)0.0f;
-            r = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, *reinterpret_cast<v8h *>(b), r, 0, 0, 0);
+            r = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, __builtin_bit_cast(v8h, raw[ks]), r, 0, 0, 0);
         }
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[v] = r[v];
     }
 };
 
-template <> struct Spec<TBF16> {
-    static __device__ __forceinline__ void run(const __bf16 *x, uint64_t tile0, uint64_t n, bool full, int lane,
-                                               float (&acc)[16]) {
+template <> struct SpecMfma<TBF16> {
+    static __device__ __forceinline__ void run(const v4u *raw, int lane, float (&acc)[16]) {
         const int c = lane & 31, h = lane >> 5;
         v16f r = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
-            alignas(16) __bf16 b[8];
-            load_elems<__bf16, 8>(x, tile0 + 32 * c + 16 * ks + 8 * h, n, full, b);
             v8s a;
 #pragma unroll
             for (int j = 0; j < 8; ++j) a[j] = (16 * ks + 8 * h + j <= c) ? (short)0x3F80 : (short)0;  // bf16 1.0
-            r = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a), *reinterpret_cast<v8bf *>(b), r,
-                                                        0, 0, 0);
+            r = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a),
+                                                        __builtin_bit_cast(v8bf, raw[ks]), r, 0, 0, 0);
         }
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[v] = r[v];
     }
 };
 
-// fp32: sixteen K-steps of 2; in step t half h supplies position 16 h + t.
-__device__ __forceinline__ void spec_f32_from_regs(const float (&b)[16], int lane, float (&acc)[16]) {
-    const int c = lane & 31, h = lane >> 5;
-    v16f r = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-    for (int t = 0; t < 16; ++t) {
-        const float a = (16 * h + t <= c) ? 1.0f : 0.0f;
-        r = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b[t], r, 0, 0, 0);
-    }
-#pragma unroll
-    for (int v = 0; v < 16; ++v) acc[v] = r[v];
-}
-
-template <> struct Spec<TF32> {
-    static __device__ __forceinline__ void run(const float *x, uint64_t tile0, uint64_t n, bool full, int lane,
-                                               float (&acc)[16]) {
+template <> struct SpecMfma<TF32> {
+    // sixteen K-steps of 2: in step 4 q + i half h supplies position 16 h + 4 q + i
+    static __device__ __forceinline__ void run(const v4u *raw, int lane, float (&acc)[16]) {
         const int c = lane & 31, h = lane >> 5;
-        float b[16];
+        v16f r = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            alignas(16) float t4[4];
-            load_elems<float, 4>(x, tile0 + 32 * c + 16 * h + 4 * q, n, full, t4);
+        for (int q = 0; q < 4; ++q)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) b[4 * q + i] = t4[i];
-        }
-        spec_f32_from_regs(b, lane, acc);
+            for (int i = 0; i < 4; ++i) {
+                const float a = (16 * h + 4 * q + i <= c) ? 1.0f : 0.0f;
+                r = __builtin_amdgcn_mfma_f32_32x32x2f32(a, from_bits<float>(raw[q][i]), r, 0, 0, 0);
+            }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[v] = r[v];
     }
 };
 
@@ -292,26 +323,35 @@ __device__ __forceinline__ void store_spec_rows(uint32_t *rows, int t, int lane,
     }
 }
 
-// ---- step 1, vector-only form (ablation) ------------------------------------------------------------
+// ---- step 1, vector-only form (ablation) --------------------------------------------------------------------
 //
-// Every lane loads 128 bits = kEpl consecutive elements, prefix-sums them in
-// registers, and the 32 / kEpl lanes that share a row combine with lane shuffles.
+// Every lane prefix-sums its kEpl consecutive elements in registers and the
+// 32 / kEpl lanes that share a row combine with lane shuffles.
+template <typename TT> __device__ __forceinline__ typename TT::acc_t raw_elem(const v4u &w, int i);
+template <> __device__ __forceinline__ uint32_t raw_elem<TI8>(const v4u &w, int i) {
+    return (uint32_t)(int32_t)(int8_t)(w[i >> 2] >> (8 * (i & 3)));
+}
+template <> __device__ __forceinline__ float raw_elem<TF16>(const v4u &w, int i) {
+    return (float)__builtin_bit_cast(_Float16, (unsigned short)(w[i >> 1] >> (16 * (i & 1))));
+}
+template <> __device__ __forceinline__ float raw_elem<TBF16>(const v4u &w, int i) {
+    return from_bits<float>((w[i >> 1] >> (16 * (i & 1))) << 16);
+}
+template <> __device__ __forceinline__ float raw_elem<TF32>(const v4u &w, int i) { return from_bits<float>(w[i]); }
+
 template <typename TT>
-__device__ __forceinline__ void spec_shuffle_tile(const typename TT::in_t *x, uint64_t tile0, uint64_t n, bool full,
-                                                  int lane, uint32_t *rows, int t) {
+__device__ __forceinline__ void spec_shuffle_tile(const v4u *raw, int lane, uint32_t *rows, int t) {
     typedef typename TT::acc_t A;
     constexpr int kEpl = TT::kEpl;
-    constexpr int kLpr = 32 / kEpl;         // lanes per row
+    constexpr int K = 16 / kEpl;
+    constexpr int kLpr = 32 / kEpl;  // lanes per row
     constexpr int kRowsPerLoad = 64 / kLpr;
-    constexpr int kLoads = 32 / kRowsPerLoad;
 #pragma unroll
-    for (int ld = 0; ld < kLoads; ++ld) {
-        alignas(16) typename TT::in_t b[kEpl];
-        load_elems<typename TT::in_t, kEpl>(x, tile0 + (uint64_t)(kRowsPerLoad * 32 * ld + kEpl * lane), n, full, b);
+    for (int ld = 0; ld < K; ++ld) {
         A p[kEpl];
-        p[0] = TT::widen(b[0]);
+        p[0] = raw_elem<TT>(raw[ld], 0);
 #pragma unroll
-        for (int i = 1; i < kEpl; ++i) p[i] = p[i - 1] + TT::widen(b[i]);
+        for (int i = 1; i < kEpl; ++i) p[i] = p[i - 1] + raw_elem<TT>(raw[ld], i);
         A inc = p[kEpl - 1];
 #pragma unroll
         for (int d = 1; d < kLpr; d <<= 1) {
@@ -330,169 +370,179 @@ __device__ __forceinline__ void spec_shuffle_tile(const typename TT::in_t *x, ui
 }
 
 // ---- the kernel ---------------------------------------------------------------------------------------
+//
+// One workgroup = one tile = 4 waves x kCpw chunks x 2048 elements, taken from an
+// atomic ticket counter (a tile only ever waits for tiles held by workgroups that
+// are already running).  A same-address device-scope atomic costs about 11 ns on
+// this chip and they serialise, which is why a ticket covers tens of thousands of
+// elements.  Every wave owns a contiguous span of the tile and
+//   A. loads all its inputs at once, then for each chunk computes the speculative
+//      row scans (matrix cores), the row aggregates and their segmented scan; only
+//      a few registers per chunk are kept, the row scans themselves are dropped;
+//   -  the four wave aggregates are combined, the tile's descriptor is published
+//      and wave 0 looks back for the carry of the predecessor tiles;
+//   B. recomputes the row scans of each chunk from the raw registers (cheaper than
+//      holding them: LDS is the scarce resource), reverts the mis-speculation, adds
+//      the carries and stores.
 
 template <typename TT, int kOp, bool kMfma>
 __global__ __launch_bounds__(kThreads) void seg_kernel(Params P) {
     typedef typename TT::acc_t A;
     typedef typename TT::in_t In;
+    constexpr int K = 16 / TT::kEpl;             // 128-bit words per lane and 32x32 tile
+    constexpr int kCpw = TT::kCpw;               // chunks per wave
+    constexpr int kWaveSpan = kCpw * kChunkElems;
+    constexpr int kTile = kWaves * kWaveSpan;
 
-    __shared__ __attribute__((aligned(16))) uint32_t s_rows[kWaves][kRowsPerWave * kRowStride];
-    __shared__ uint32_t s_cnt[kWaves * kRowsPerWave];  // segment starts before each row (sum)
+    __shared__ __attribute__((aligned(16))) uint32_t s_rows[kWaves][kRowsPerChunk * kRowStride];
+    __shared__ uint32_t s_cnt[kWaves * kRowsPerChunk];  // segment starts before each row (sum)
     __shared__ uint32_t s_wave_v[kWaves], s_wave_f[kWaves], s_wave_c[kWaves];
-    __shared__ uint32_t s_tile, s_carry_v, s_carry_c;
+    __shared__ uint32_t s_tile, s_carry_v, s_carry_c, s_ready;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    if (tid == 0) s_tile = __hip_atomic_fetch_add(P.hdr + kHdrTicket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __syncthreads();
-    const int tile = (int)s_tile;
     const uint64_t n = P.n;
-    const uint64_t wave_base = (uint64_t)tile * kTileElems + (uint64_t)wave * kWaveElems;
-    const bool wave_full = wave_base + kWaveElems <= n;
     uint32_t *rows = s_rows[wave];
-    const uint64_t row_start = wave_base + 32u * lane;  // first element of the row this lane owns
+#ifdef MMV_TRACE
+    const uint64_t t_begin = wall_clock64();
+#endif
+    if (tid == 0) {
+        s_ready = 0;
+        s_tile = __hip_atomic_fetch_add(P.hdr + kHdrTicket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    const uint32_t tile = s_tile;
+#ifdef MMV_TRACE
+    if (tid == 0 && P.trace) P.trace[(uint64_t)tile * 8] = t_begin;
+#endif
+    MMV_STAMP(1);
+    const uint64_t wave_base = (uint64_t)tile * kTile + (uint64_t)wave * kWaveSpan;
 
-    // ---- flags of my row (one 32-bit word = one row) ----
-    uint32_t F = 0;
-    if (kOp == kSpmv) {
-        // f(e) = [e == 0 or row(e) != row(e-1)], 64 elements per ballot
-        int prev_last = wave_base > 0 && wave_base - 1 < n ? P.row[wave_base - 1] : -1;
-        for (int j = 0; j < 32; ++j) {
-            const uint64_t e = wave_base + 64u * j + lane;
-            const int r = e < n ? P.row[e] : 0;
-            int rp = __shfl_up(r, 1);
-            if (lane == 0) rp = prev_last;
-            const uint64_t m = __ballot(e < n && (e == 0 || r != rp));
-            if (lane == 2 * j) F = (uint32_t)m;
-            if (lane == 2 * j + 1) F = (uint32_t)(m >> 32);
-            prev_last = __shfl(r, 63);
+    // ---- all inputs of my span: flag word of my row and raw values (and columns) per chunk ----
+    uint32_t F[kCpw];
+    v4u raw[kCpw][2 * K];
+    v4u rawc[kOp == kSpmv ? kCpw : 1][2 * K];  // column indices (spmv)
+#pragma unroll
+    for (int c = 0; c < kCpw; ++c) {
+        const uint64_t cb = wave_base + (uint64_t)c * kChunkElems;
+        F[c] = 0;
+        if constexpr (kOp != kSpmv) {
+            const uint64_t rs = cb + 32u * lane;
+            if (rs < n) F[c] = P.fw[rs >> 5];
+        } else {
+            load_raw<TInt, kMfma>(P.col, cb, n, lane, rawc[c]);
         }
-    } else {
-        if (row_start < n) {
-            F = P.fw[row_start >> 5];
-            if (row_start + 32 > n) F &= (1u << (uint32_t)(n - row_start)) - 1u;
-        }
+        load_raw<TT, kMfma>((const In *)P.x, cb, n, lane, raw[c]);
     }
 
-    // ---- step 1: speculative row scans into LDS ----
+    // per chunk: exclusive segmented prefix of my row inside the chunk, and of the chunk inside
+    // my span; run_* = running aggregate of the span
+    A ex_v[kCpw], pre_v[kCpw];
+    uint32_t ex_f[kCpw], pre_f[kCpw], ex_c[kCpw];
+    A run_v = A(0);
+    uint32_t run_f = 0, run_c = 0;
+
+    // ================= phase A: aggregates =================
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
-        const uint64_t tile0 = wave_base + 1024u * t;
-        if (kOp == kSpmv) {
-            // product vector p(i) = val(i) * x(col(i)), built in the layout step 1 needs
-            if (kMfma) {
-                const int c = lane & 31, h = lane >> 5;
-                float b[16];
+    for (int c = 0; c < kCpw; ++c) {
+        const uint64_t cb = wave_base + (uint64_t)c * kChunkElems;
+        const uint64_t row_start = cb + 32u * lane;  // first element of the row this lane owns
+        // ---- flags of my row (one 32-bit word = one row) ----
+        if constexpr (kOp == kSpmv) {
+            // f(e) = [e == 0 or row(e) != row(e-1)], 64 elements per ballot
+            uint32_t Fc = 0;
+            int prev_last = cb > 0 && cb - 1 < n ? P.row[cb - 1] : -1;
+            for (int j = 0; j < 32; ++j) {
+                const uint64_t e = cb + 64u * j + lane;
+                const int r = e < n ? P.row[e] : 0;
+                int rp = __shfl_up(r, 1);
+                if (lane == 0) rp = prev_last;
+                const uint64_t m = __ballot(e < n && (e == 0 || r != rp));
+                if (lane == 2 * j) Fc = (uint32_t)m;
+                if (lane == 2 * j + 1) Fc = (uint32_t)(m >> 32);
+                prev_last = __shfl(r, 63);
+            }
+            F[c] = Fc;
+            // product vector p(i) = val(i) * x(col(i)), in the layout the values were loaded in
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    alignas(16) float v4[4];
-                    alignas(16) int c4[4];
-                    const uint64_t e0 = tile0 + 32 * c + 16 * h + 4 * q;
-                    load_elems<float, 4>((const float *)P.x, e0, n, wave_full, v4);
-                    load_elems<int, 4>(P.col, e0, n, wave_full, c4);
+            for (int t = 0; t < 2; ++t)
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) b[4 * q + i] = (e0 + i < n) ? v4[i] * P.xv[c4[i]] : 0.0f;
+                for (int i = 0; i < K; ++i) {
+                    const uint64_t e0 = cb + 1024u * t + raw_offset<TT, kMfma>(i, lane);
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        const float p =
+                            (e0 + k < n) ? from_bits<float>(raw[c][t * K + i][k]) * P.xv[rawc[c][t * K + i][k]] : 0.0f;
+                        raw[c][t * K + i][k] = to_bits(p);
+                    }
                 }
-                float acc[16];
-                spec_f32_from_regs(b, lane, acc);
+        } else if (row_start + 32 > n) {
+            F[c] = row_start < n ? (F[c] & ((1u << (uint32_t)(n - row_start)) - 1u)) : 0u;
+        }
+
+        // ---- step 1: speculative row scans into LDS ----
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            if (kMfma) {
+                A acc[16];
+                SpecMfma<TT>::run(raw[c] + t * K, lane, acc);
                 store_spec_rows(rows, t, lane, acc);
             } else {
-#pragma unroll
-                for (int ld = 0; ld < 4; ++ld) {
-                    alignas(16) float v4[4];
-                    float p[4];
-                    alignas(16) int c4[4];
-                    const uint64_t e0 = tile0 + 256 * ld + 4 * lane;
-                    load_elems<float, 4>((const float *)P.x, e0, n, wave_full, v4);
-                    load_elems<int, 4>(P.col, e0, n, wave_full, c4);
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) p[i] = (e0 + i < n) ? v4[i] * P.xv[c4[i]] : 0.0f;
-                    p[1] += p[0];
-                    p[2] += p[1];
-                    p[3] += p[2];
-                    float inc = p[3];
-#pragma unroll
-                    for (int d = 1; d < 8; d <<= 1) {
-                        const float o = __shfl_up(inc, d);
-                        if ((lane & 7) >= d) inc += o;
-                    }
-                    const float ex = inc - p[3];
-                    v4u w = {to_bits(p[0] + ex), to_bits(p[1] + ex), to_bits(p[2] + ex), to_bits(p[3] + ex)};
-                    *reinterpret_cast<v4u *>(rows + (32 * t + 8 * ld + lane / 8) * kRowStride + kRowData +
-                                             4 * (lane & 7)) = w;
-                }
+                spec_shuffle_tile<TT>(raw[c] + t * K, lane, rows, t);
             }
-        } else if (kMfma) {
-            A acc[16];
-            Spec<TT>::run((const In *)P.x, tile0, n, wave_full, lane, acc);
-            store_spec_rows(rows, t, lane, acc);
-        } else {
-            spec_shuffle_tile<TT>((const In *)P.x, tile0, n, wave_full, lane, rows, t);
         }
-    }
-    rows[lane * kRowStride + kSlotZero] = 0;
-    rows[lane * kRowStride + kSlotF] = F;
-    wave_lds_sync();
+        rows[lane * kRowStride + kSlotZero] = 0;
+        wave_lds_sync();
 
-    // ---- steps 2-4 for the aggregate of my row: last element after the revert, any flag ----
-    const bool has_flag = F != 0;
-    A agg_v;
-    {
+        // ---- steps 2-4 for the aggregate of my row: last element after the revert, any flag ----
+        const uint32_t has_flag = F[c] != 0;
         const A last = from_bits<A>(rows[lane * kRowStride + kRowData + 31]);
-        const int slot = has_flag ? kSlotZero + (31 - __clz(F)) : kSlotZero;  // x-bar(start - 1)
-        agg_v = last - from_bits<A>(rows[lane * kRowStride + slot]);
-    }
-    // segment starts in my row, position 0 of the whole vector not counted (sum only)
-    const uint32_t Fc = row_start == 0 ? (F & ~1u) : F;
-    uint32_t cnt = __popc(Fc);
+        const int slot = has_flag ? kSlotZero + (31 - __clz(F[c])) : kSlotZero;  // x-bar(start - 1)
+        const A agg_v = last - from_bits<A>(rows[lane * kRowStride + slot]);
+        // segment starts in my row, position 0 of the whole vector not counted (sum only)
+        const uint32_t cnt = __popc(row_start == 0 ? (F[c] & ~1u) : F[c]);
 
-    // ---- step 5a: segmented inclusive scan of (value, flag) over the 64 rows of the wave ----
-    A inc_v = agg_v;
-    uint32_t inc_f = has_flag;
-    uint32_t inc_c = cnt;
+        // ---- step 5a: segmented inclusive scan of (value, flag) over the 64 rows of the chunk ----
+        A inc_v = agg_v;
+        uint32_t inc_f = has_flag;
+        uint32_t inc_c = cnt;
 #pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const A ov = from_bits<A>(__shfl_up(to_bits(inc_v), d));
-        const uint32_t of = __shfl_up(inc_f, d);
-        if (lane >= d) {
-            if (!inc_f) inc_v = ov + inc_v;
-            inc_f |= of;
+        for (int d = 1; d < 64; d <<= 1) {
+            const A ov = from_bits<A>(__shfl_up(to_bits(inc_v), d));
+            const uint32_t of = __shfl_up(inc_f, d);
+            if (lane >= d) {
+                if (!inc_f) inc_v = ov + inc_v;
+                inc_f |= of;
+            }
+            if (kOp == kSum) {
+                const uint32_t oc = __shfl_up(inc_c, d);
+                if (lane >= d) inc_c += oc;
+            }
         }
-        if (kOp == kSum) {
-            const uint32_t oc = __shfl_up(inc_c, d);
-            if (lane >= d) inc_c += oc;
+        ex_v[c] = from_bits<A>(__shfl_up(to_bits(inc_v), 1));
+        ex_f[c] = __shfl_up(inc_f, 1);
+        if (lane == 0) {
+            ex_v[c] = A(0);
+            ex_f[c] = 0;
         }
+        ex_c[c] = run_c + inc_c - cnt;
+        pre_v[c] = run_v;
+        pre_f[c] = run_f;
+        // chunk aggregate = inclusive value of the last row; fold it into the span's running aggregate
+        const A ca_v = from_bits<A>(__shfl(to_bits(inc_v), 63));
+        const uint32_t ca_f = __shfl(inc_f, 63);
+        run_v = ca_f ? ca_v : run_v + ca_v;
+        run_f |= ca_f;
+        if (kOp == kSum) run_c += __shfl(inc_c, 63);
+        wave_lds_sync();  // the rows are read before the next chunk overwrites them
     }
-    A ex_v = from_bits<A>(__shfl_up(to_bits(inc_v), 1));
-    uint32_t ex_f = __shfl_up(inc_f, 1);
+    MMV_STAMP(2);
     if (lane == 0) {
-        ex_v = A(0);
-        ex_f = 0;
-    }
-    const uint32_t ex_c = inc_c - cnt;
-    if (lane == 63) {
-        s_wave_v[wave] = to_bits(inc_v);
-        s_wave_f[wave] = inc_f;
-        s_wave_c[wave] = inc_c;
-    }
-
-    // segment-end mask of my row (sum, spmv): bit p set iff position p + 1 starts a segment
-    // or p is the last element of the vector
-    if (kOp != kScan) {
-        uint32_t next0 = __shfl_down(F, 1) & 1u;
-        if (lane == 63) {
-            const uint64_t en = wave_base + kWaveElems;
-            next0 = 0;
-            if (en < n) next0 = kOp == kSpmv ? (P.row[en] != P.row[en - 1]) : (P.fw[en >> 5] & 1u);
-        }
-        uint32_t E = (F >> 1) | (next0 << 31);
-        if (row_start < n) {
-            if (row_start + 32 >= n) E = (E & ((1u << (uint32_t)(n - 1 - row_start)) - 1u)) | (1u << (uint32_t)(n - 1 - row_start));
-        } else {
-            E = 0;
-        }
-        rows[lane * kRowStride + kSlotE] = E;
+        s_wave_v[wave] = to_bits(run_v);
+        s_wave_f[wave] = run_f;
+        s_wave_c[wave] = run_c;
     }
     __syncthreads();
+    MMV_STAMP(3);
 
     // ---- step 5b: waves of the tile ----
     A wex_v = A(0);
@@ -514,95 +564,156 @@ __global__ __launch_bounds__(kThreads) void seg_kernel(Params P) {
     }
 
     // ---- step 5c: tiles, by decoupled look-back ----
+    A tile_carry = A(0);
+    uint32_t count_carry = 0;
     if (wave == 0) {
         const bool final_now = tile == 0 || tagg_f;  // carry out does not depend on predecessors
         if (lane == 0) desc_store(P.desc_v + tile, final_now ? kStatusPrefix : kStatusAggregate, to_bits(tagg_v));
-        A carry = A(0);
-        if (tile > 0) carry = lookback<A>(P.desc_v, tile, lane, P.hdr);
+        if (tile > 0) tile_carry = lookback<A>(P.desc_v, (int)tile, lane, P.hdr);
+        MMV_STAMP(4);
         if (lane == 0) {
-            if (!final_now) desc_store(P.desc_v + tile, kStatusPrefix, to_bits(carry + tagg_v));
-            s_carry_v = to_bits(carry);
+            if (!final_now) desc_store(P.desc_v + tile, kStatusPrefix, to_bits(tile_carry + tagg_v));
+            s_carry_v = to_bits(tile_carry);
+            __hip_atomic_store(&s_ready, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
         }
     }
-    if (kOp == kSum && wave == 1) {
-        if (lane == 0) desc_store(P.desc_c + tile, tile == 0 ? kStatusPrefix : kStatusAggregate, tagg_c);
-        uint32_t carry = 0;
-        if (tile > 0) carry = lookback<uint32_t>(P.desc_c, tile, lane, P.hdr);
-        if (lane == 0) {
-            if (tile > 0) desc_store(P.desc_c + tile, kStatusPrefix, carry + tagg_c);
-            s_carry_c = carry;
-            if ((uint32_t)tile == P.num_tiles - 1) *P.nseg = (uint64_t)carry + tagg_c + 1u;
-        }
-    }
-    __syncthreads();
-
-    // ---- step 6: carry into my row; stored negated so that the revert subtracts it ----
-    {
-        const A tile_carry = from_bits<A>(s_carry_v);
-        const A carry = ex_f ? ex_v : (wex_f ? wex_v + ex_v : tile_carry + wex_v + ex_v);
-        rows[lane * kRowStride + kSlotNegCarry] = to_bits(A(0) - carry);
-        if (kOp == kSum) s_cnt[wave * kRowsPerWave + lane] = s_carry_c + wex_c + ex_c;
-    }
-    const uint64_t row_any = __ballot(has_flag);
-    wave_lds_sync();
-
-    // ---- steps 2 + 6 on every element, then store; lane owns 4 consecutive positions ----
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const int R = 8 * j + (lane >> 3), p0 = 4 * (lane & 7);
-        const uint32_t *rp = rows + R * kRowStride;
-        const v4u xb = *reinterpret_cast<const v4u *>(rp + kRowData + p0);
-        A o[4];
-        uint32_t Fr = 0;
-        if (((row_any >> (8 * j)) & 0xFFull) == 0) {
-            // none of these eight rows has a flag: the speculation stands, only the carry is added
-            const A nc = from_bits<A>(rp[kSlotNegCarry]);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) o[i] = from_bits<A>(xb[i]) - nc;
-        } else {
-            Fr = rp[kSlotF];
-            const uint32_t m = Fr & ((2u << p0) - 1u);  // flags at or before my first position
-            const int slot = m ? kSlotZero + (31 - __clz(m)) : kSlotNegCarry;
-            A b = from_bits<A>(rp[slot]);
-            o[0] = from_bits<A>(xb[0]) - b;
-#pragma unroll
-            for (int i = 1; i < 4; ++i) {
-                if ((Fr >> (p0 + i)) & 1u) b = from_bits<A>(xb[i - 1]);
-                o[i] = from_bits<A>(xb[i]) - b;
+    if (kOp == kSum) {
+        if (wave == 1) {
+            if (lane == 0) desc_store(P.desc_c + tile, tile == 0 ? kStatusPrefix : kStatusAggregate, tagg_c);
+            uint32_t carry = 0;
+            if (tile > 0) carry = lookback<uint32_t>(P.desc_c, (int)tile, lane, P.hdr);
+            if (lane == 0) {
+                if (tile > 0) desc_store(P.desc_c + tile, kStatusPrefix, carry + tagg_c);
+                s_carry_c = carry;
+                if (tile == P.num_tiles - 1) *P.nseg = (uint64_t)carry + tagg_c + 1u;
             }
         }
-        const uint64_t e0 = wave_base + 256u * j + 4u * lane;
-        if (kOp == kScan) {
-            A *z = (A *)P.z;
-            if (wave_full) {
-                v4u w = {to_bits(o[0]), to_bits(o[1]), to_bits(o[2]), to_bits(o[3])};
-                *reinterpret_cast<v4u *>(z + e0) = w;
+        __syncthreads();  // every output index needs the count carry
+        count_carry = s_carry_c;
+        tile_carry = from_bits<A>(s_carry_v);
+    } else if (wave != 0 && !wex_f) {
+        // my span starts inside a segment that began in an earlier tile: wait for wave 0
+        while (__hip_atomic_load(&s_ready, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) == 0)
+            __builtin_amdgcn_s_sleep(1);
+        tile_carry = from_bits<A>(s_carry_v);
+    }
+    MMV_STAMP(5);
+    // carry into my span (used only by rows with no flag before them in the tile)
+    const A span_carry = wex_f ? wex_v : tile_carry + wex_v;
+
+    // ================= phase B: recompute, revert, add carries, store =================
+#pragma unroll
+    for (int c = 0; c < kCpw; ++c) {
+        const uint64_t cb = wave_base + (uint64_t)c * kChunkElems;
+        const bool chunk_full = cb + kChunkElems <= n;
+        const uint64_t row_start = cb + 32u * lane;
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            if (kMfma) {
+                A acc[16];
+                SpecMfma<TT>::run(raw[c] + t * K, lane, acc);
+                store_spec_rows(rows, t, lane, acc);
             } else {
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    if (e0 + i < n) z[e0 + i] = o[i];
+                spec_shuffle_tile<TT>(raw[c] + t * K, lane, rows, t);
             }
-        } else {
-            const uint32_t ends = (rp[kSlotE] >> p0) & 0xFu;
-            if (ends) {
-                if (kOp == kSum) {
-                    if (!Fr) Fr = rp[kSlotF];
-                    const uint32_t Frc = (wave_base == 0 && R == 0) ? (Fr & ~1u) : Fr;
-                    const uint32_t base = s_cnt[wave * kRowsPerWave + R];
+        }
+        // ---- step 6: carry into my row; stored negated so that the revert subtracts it ----
+        const A carry = ex_f[c] ? ex_v[c] : (pre_f[c] ? pre_v[c] + ex_v[c] : (span_carry + pre_v[c]) + ex_v[c]);
+        rows[lane * kRowStride + kSlotZero] = 0;
+        rows[lane * kRowStride + kSlotF] = F[c];
+        rows[lane * kRowStride + kSlotNegCarry] = to_bits(A(0) - carry);
+        if (kOp != kScan) {
+            // segment-end mask of my row: bit p set iff position p + 1 starts a segment or p is
+            // the last element of the vector
+            uint32_t next0 = __shfl_down(F[c], 1) & 1u;
+            if (lane == 63) {
+                const uint64_t en = cb + kChunkElems;
+                next0 = 0;
+                if (en < n) next0 = kOp == kSpmv ? (P.row[en] != P.row[en - 1]) : (P.fw[en >> 5] & 1u);
+            }
+            uint32_t E = (F[c] >> 1) | (next0 << 31);
+            if (row_start < n) {
+                if (row_start + 32 >= n) {
+                    const uint32_t last = (uint32_t)(n - 1 - row_start);
+                    E = (E & ((1u << last) - 1u)) | (1u << last);
+                }
+            } else {
+                E = 0;
+            }
+            rows[lane * kRowStride + kSlotE] = E;
+            if (kOp == kSum) s_cnt[wave * kRowsPerChunk + lane] = count_carry + wex_c + ex_c[c];
+        }
+        const uint64_t row_any = __ballot(F[c] != 0);
+        wave_lds_sync();
+
+        // ---- steps 2 + 6 on every element, then store; a lane owns 4 consecutive positions ----
 #pragma unroll
-                    for (int i = 0; i < 4; ++i)
-                        if ((ends >> i) & 1u) {
-                            const uint64_t k = (uint64_t)base + __popc(Frc & ((2u << (p0 + i)) - 1u));
-                            if (k < P.out_cap) ((A *)P.out)[k] = o[i];
-                        }
+        for (int j = 0; j < 8; ++j) {
+            const int R = 8 * j + (lane >> 3), p0 = 4 * (lane & 7);
+            const uint32_t *rp = rows + R * kRowStride;
+            const v4u xb = *reinterpret_cast<const v4u *>(rp + kRowData + p0);
+            A o[4];
+            uint32_t Fr = 0;
+            if (((row_any >> (8 * j)) & 0xFFull) == 0) {
+                // none of these eight rows has a flag: the speculation stands, only the carry is added
+                const A nc = from_bits<A>(rp[kSlotNegCarry]);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) o[i] = from_bits<A>(xb[i]) - nc;
+            } else {
+                Fr = rp[kSlotF];
+                const uint32_t m = Fr & ((2u << p0) - 1u);  // flags at or before my first position
+                const int slot = m ? kSlotZero + (31 - __clz(m)) : kSlotNegCarry;
+                A b = from_bits<A>(rp[slot]);
+                o[0] = from_bits<A>(xb[0]) - b;
+#pragma unroll
+                for (int i = 1; i < 4; ++i) {
+                    if ((Fr >> (p0 + i)) & 1u) b = from_bits<A>(xb[i - 1]);
+                    o[i] = from_bits<A>(xb[i]) - b;
+                }
+            }
+            const uint64_t e0 = cb + 256u * j + 4u * lane;
+            if (kOp == kScan) {
+                A *z = (A *)P.z;
+                if (chunk_full) {
+                    v4u w = {to_bits(o[0]), to_bits(o[1]), to_bits(o[2]), to_bits(o[3])};
+#ifdef MMV_PLAIN_STORE
+                    *reinterpret_cast<v4u *>(z + e0) = w;
+#else
+                    __builtin_nontemporal_store(w, reinterpret_cast<v4u *>(z + e0));
+#endif
                 } else {
 #pragma unroll
                     for (int i = 0; i < 4; ++i)
-                        if ((ends >> i) & 1u) P.y[P.row[e0 + i]] = from_bits<float>(to_bits(o[i]));
+                        if (e0 + i < n) z[e0 + i] = o[i];
+                }
+            } else {
+                const uint32_t ends = (rp[kSlotE] >> p0) & 0xFu;
+                if (ends) {
+                    if (kOp == kSum) {
+                        if (!Fr) Fr = rp[kSlotF];
+                        const uint32_t Frc = (cb == 0 && R == 0) ? (Fr & ~1u) : Fr;
+                        const uint32_t base = s_cnt[wave * kRowsPerChunk + R];
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            if ((ends >> i) & 1u) {
+                                const uint64_t k = (uint64_t)base + __popc(Frc & ((2u << (p0 + i)) - 1u));
+                                if (k < P.out_cap) ((A *)P.out)[k] = o[i];
+                            }
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            if ((ends >> i) & 1u) P.y[P.row[e0 + i]] = from_bits<float>(to_bits(o[i]));
+                    }
                 }
             }
         }
+        wave_lds_sync();  // the rows are read before the next chunk overwrites them
     }
+    MMV_STAMP(6);
+#ifdef MMV_TRACE
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    MMV_STAMP(7);
+#endif
 }
 
 // ---- auxiliary kernels -------------------------------------------------------------------------------------
@@ -663,16 +774,25 @@ __global__ __launch_bounds__(256) void stream_copy_kernel(const v4u *src, v4u *d
 // ---- host side -------------------------------------------------------------------------------------------------
 
 inline size_t round256(size_t b) { return (b + 255) & ~(size_t)255; }
-inline uint64_t tiles_for(uint64_t n) { return (n + kTileElems - 1) / kTileElems; }
+inline uint32_t tile_elems(mmv_dtype dt) {
+    switch (dt) {
+        case MMV_F32_F32: return kWaves * TF32::kCpw * kChunkElems;
+        case MMV_F16_F32: return kWaves * TF16::kCpw * kChunkElems;
+        case MMV_BF16_F32: return kWaves * TBF16::kCpw * kChunkElems;
+        case MMV_I8_I32: return kWaves * TI8::kCpw * kChunkElems;
+    }
+    return 0;
+}
+inline uint64_t tiles_for(uint64_t n, mmv_dtype dt) { return (n + tile_elems(dt) - 1) / tile_elems(dt); }
 inline bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
 
 struct WsLayout {
     size_t desc_v, desc_c, packed, total;
 };
 
-WsLayout ws_layout(mmv_op op, mmv_flag_fmt ff, uint64_t n) {
+WsLayout ws_layout(mmv_op op, mmv_dtype dt, mmv_flag_fmt ff, uint64_t n) {
     WsLayout L;
-    const uint64_t t = tiles_for(n);
+    const uint64_t t = tiles_for(n, dt);
     size_t off = kHdrBytes;
     L.desc_v = off;
     off += round256(t * 8);
@@ -684,17 +804,30 @@ WsLayout ws_layout(mmv_op op, mmv_flag_fmt ff, uint64_t n) {
     return L;
 }
 
+#ifdef MMV_TRACE
+uint64_t *g_trace = nullptr;
+#endif
+
 // Optional instrumentation (mmv_set_kernel_events): events recorded right before and
 // right after the main kernel of a call made by this host thread.
 thread_local hipEvent_t tl_ev_start = nullptr, tl_ev_stop = nullptr;
 
+template <typename TT, int kOp, bool kMfma> hipError_t launch_variant(Params P, hipStream_t s) {
+#ifdef MMV_TRACE
+    P.trace = g_trace;
+#endif
+    seg_kernel<TT, kOp, kMfma><<<P.num_tiles, kThreads, 0, s>>>(P);
+    return hipGetLastError();
+}
+
 template <typename TT, int kOp>
 hipError_t launch_seg(const Params &P, mmv_variant v, hipStream_t s) {
     if (tl_ev_start && hipEventRecord(tl_ev_start, s) != hipSuccess) return hipErrorUnknown;
-    if (v == MMV_VARIANT_MFMA)
-        seg_kernel<TT, kOp, true><<<P.num_tiles, kThreads, 0, s>>>(P);
-    else
-        seg_kernel<TT, kOp, false><<<P.num_tiles, kThreads, 0, s>>>(P);
+    if (v == MMV_VARIANT_MFMA) {
+        if (launch_variant<TT, kOp, true>(P, s) != hipSuccess) return hipErrorUnknown;
+    } else {
+        if (launch_variant<TT, kOp, false>(P, s) != hipSuccess) return hipErrorUnknown;
+    }
     const hipError_t e = hipGetLastError();
     if (tl_ev_stop && hipEventRecord(tl_ev_stop, s) != hipSuccess) return hipErrorUnknown;
     return e;
@@ -729,7 +862,7 @@ mmv_status prepare(mmv_op op, const void *d_x, const void *d_flags, uint64_t n, 
     if (!d_x || !d_flags) return MMV_ERR_NULL;
     if (!aligned16(d_x) || !aligned16(d_flags)) return MMV_ERR_INVALID_ARG;
     if (!d_ws) return MMV_ERR_NULL;
-    const WsLayout L = ws_layout(op, ff, n);
+    const WsLayout L = ws_layout(op, dt, ff, n);
     if (((uintptr_t)d_ws & 255u) != 0 || ws_bytes < L.total) return MMV_ERR_WORKSPACE;
     char *ws = (char *)d_ws;
     P.x = d_x;
@@ -737,7 +870,7 @@ mmv_status prepare(mmv_op op, const void *d_x, const void *d_flags, uint64_t n, 
     P.hdr = (uint32_t *)ws;
     P.desc_v = (uint64_t *)(ws + L.desc_v);
     P.desc_c = (uint64_t *)(ws + L.desc_c);
-    P.num_tiles = (uint32_t)tiles_for(n);
+    P.num_tiles = (uint32_t)tiles_for(n, dt);
     const uint64_t zero_words = L.packed / 4;  // header + descriptors
     fill_zero_kernel<<<grid_for(zero_words), 256, 0, s>>>((uint32_t *)ws, zero_words, nullptr, 0);
     if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
@@ -761,7 +894,7 @@ extern "C" {
 
 size_t mmv_workspace_bytes(mmv_op op, mmv_dtype dt, mmv_flag_fmt ff, uint64_t n) {
     if ((int)op < 0 || (int)op > 2 || !valid_dtype(dt) || !valid_ff(ff) || n > kMaxN) return 0;
-    return ws_layout(op, ff, n).total;
+    return ws_layout(op, op == MMV_OP_SPMV_COO ? MMV_F32_F32 : dt, ff, n).total;
 }
 
 mmv_status mmv_segscan(const void *d_x, const void *d_flags, uint64_t n, void *d_z, mmv_dtype dt, mmv_flag_fmt ff,
@@ -813,7 +946,7 @@ mmv_status mmv_spmv_coo(uint64_t n_rows, uint64_t n_cols, uint64_t nnz, const in
     }
     if (!d_row || !d_col || !d_val || !d_x || !d_ws) return MMV_ERR_NULL;
     if (!aligned16(d_row) || !aligned16(d_col) || !aligned16(d_val) || !aligned16(d_x)) return MMV_ERR_INVALID_ARG;
-    const WsLayout L = ws_layout(MMV_OP_SPMV_COO, MMV_FLAGS_PACKED32, nnz);
+    const WsLayout L = ws_layout(MMV_OP_SPMV_COO, MMV_F32_F32, MMV_FLAGS_PACKED32, nnz);
     if (((uintptr_t)d_ws & 255u) != 0 || ws_bytes < L.total) return MMV_ERR_WORKSPACE;
     char *ws = (char *)d_ws;
     Params P = {};
@@ -826,7 +959,7 @@ mmv_status mmv_spmv_coo(uint64_t n_rows, uint64_t n_cols, uint64_t nnz, const in
     P.hdr = (uint32_t *)ws;
     P.desc_v = (uint64_t *)(ws + L.desc_v);
     P.desc_c = nullptr;
-    P.num_tiles = (uint32_t)tiles_for(nnz);
+    P.num_tiles = (uint32_t)tiles_for(nnz, MMV_F32_F32);
     const uint64_t zero_words = L.total / 4;
     fill_zero_kernel<<<grid_for(zero_words > n_rows ? zero_words : n_rows), 256, 0, s>>>((uint32_t *)ws, zero_words,
                                                                                       (uint32_t *)d_y, n_rows);
@@ -878,6 +1011,11 @@ mmv_status mmv_set_kernel_events(void *ev_start, void *ev_stop) {
     return MMV_OK;
 }
 
+#ifdef MMV_TRACE
+// Development builds only: device buffer of 8 uint64 per tile that receives phase timestamps.
+void mmv_trace_buffer(void *d_trace) { g_trace = (uint64_t *)d_trace; }
+#endif
+
 const char *mmv_status_string(mmv_status s) {
     switch (s) {
         case MMV_OK: return "ok";
@@ -890,6 +1028,6 @@ const char *mmv_status_string(mmv_status s) {
     return "unknown status";
 }
 
-uint32_t mmv_tile_elems(void) { return kTileElems; }
+uint32_t mmv_tile_elems(mmv_dtype dt) { return valid_dtype(dt) ? tile_elems(dt) : 0; }
 
 }  // extern "C"

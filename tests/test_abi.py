@@ -27,8 +27,9 @@ def test_library_exports_every_declared_symbol(libmmvseg_path):
 def test_host_only_entry_points(libmmvseg_path):
     from paper_2506_23906_amd import binding as B
     lib = B.load()
-    tile = B.mmv_tile_elems()
-    assert tile == 8192
+    tile = B.mmv_tile_elems(B.MMV_I8_I32)
+    assert tile == 32768 and B.mmv_tile_elems(B.MMV_F16_F32) == 32768
+    assert B.mmv_tile_elems(B.MMV_F32_F32) == 16384 and B.mmv_tile_elems(9) == 0
     assert lib.mmv_status_string(0) == b"ok"
     assert lib.mmv_status_string(4).startswith(b"workspace")
     # header + one 8-byte descriptor per tile, rounded to 256 bytes
