@@ -85,11 +85,13 @@ def time_steps(step, steps: int, warmup: int, events: HipEvents | None):
 
 
 def load_traffic(name: str):
-    """HBM bytes per launch from the rocprofv3 --pmc runs, if a summary has been committed."""
-    path = os.path.join(ROOT, "profiles", "traffic.json")
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary of this workload, if any."""
+    path = os.path.join(ROOT, "profiles", name + "_hbm_traffic.txt")
     if os.path.exists(path):
         with open(path) as fh:
-            return json.load(fh).get(name)
+            for line in fh:
+                if line.startswith("traffic_bytes_per_launch"):
+                    return int(line.split("=")[1])
     return None
 
 
@@ -114,6 +116,8 @@ def main() -> int:
     ap.add_argument("--variant", default="mfma", choices=["mfma", "shuffle"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--report", default=None, help="also time every workload and write JSON lines here")
+    ap.add_argument("--copy-only", action="store_true",
+                    help="run only the streaming copy reference (1 GiB in, 1 GiB out), for counter calibration")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (every box has one GPU; see DESIGN.md, "
@@ -127,6 +131,14 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     B.load()
+    if args.copy_only:
+        src = torch.zeros(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        for _ in range(args.steps):
+            B.mmv_stream_copy(src, dst)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_only": True, "in_bytes": 1 << 30, "out_bytes": 1 << 30, "launches": args.steps}))
+        return 0
     events = HipEvents()
 
     n = 1 << args.log2n
@@ -161,7 +173,7 @@ def main() -> int:
                         "segment lengths U{1..4096}, bit-packed flags, seed %d"
                         % (args.log2n, W.SEEDS["segscan_i8_uniform_len"]),
             "variant": args.variant,
-            "tile_elems": B.mmv_tile_elems(B.MMV_I8_I32),
+            "tile_elems": B.mmv_tile_elems(),
             "kernel_ms": kernel_ms,
             "hbm_frac_of_peak_whole_step": algo_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         },

@@ -17,7 +17,10 @@
  *    stream, by a small fill kernel); contents are undefined afterwards, except
  *    for the status word read by mmv_workspace_status().  Two calls that share
  *    a workspace must not overlap in time.
- *  - Value, flag, index and output pointers must be 16-byte aligned.
+ *  - Value, flag, index and output pointers must be 16-byte aligned.  Inputs are read
+ *    in aligned 16-byte blocks: the block that holds the last element is read whole
+ *    (up to 15 bytes beyond the last element, never beyond that block) and the
+ *    surplus is ignored.
  *  - Errors are returned as mmv_status; nothing aborts or throws.  Argument
  *    errors are detected on the host before anything is launched.
  *  - Position 0 always opens a segment, whatever its flag says (Problem 2.1 of
@@ -139,10 +142,11 @@ mmv_status mmv_set_kernel_events(void *ev_start, void *ev_stop);
 
 const char *mmv_status_string(mmv_status s);
 
-/* Elements per workgroup tile for an input type (for tests that want to straddle
- * tile borders and for sizing: the workspace holds one 8-byte descriptor per tile).
- * 0 for an invalid type. */
-uint32_t mmv_tile_elems(mmv_dtype dt);
+/* Elements per workgroup tile for an operation, input type and length (tiles are
+ * smaller for short inputs so that every compute unit gets one).  For tests that want
+ * to straddle tile borders and for sizing: the workspace holds one 8-byte descriptor
+ * per tile.  0 for invalid arguments. */
+uint32_t mmv_tile_elems(mmv_op op, mmv_dtype dt, uint64_t n);
 
 #ifdef __cplusplus
 }

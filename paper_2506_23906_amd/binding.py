@@ -66,7 +66,7 @@ def load() -> ctypes.CDLL:
     lib.mmv_status_string.restype = ctypes.c_char_p
     lib.mmv_set_kernel_events.argtypes = [vp, vp]
     lib.mmv_set_kernel_events.restype = i32
-    lib.mmv_tile_elems.argtypes = [i32]
+    lib.mmv_tile_elems.argtypes = [i32, i32, u64]
     lib.mmv_tile_elems.restype = ctypes.c_uint32
     _lib = lib
     return lib
@@ -96,8 +96,9 @@ def _flag_fmt(flags: torch.Tensor) -> int:
     raise MmvError("flags must be uint8 (one byte per element) or int32 (bit-packed words)")
 
 
-def mmv_tile_elems(dt: int = MMV_I8_I32) -> int:
-    return int(load().mmv_tile_elems(dt))
+def mmv_tile_elems(op: int = MMV_OP_SEGSCAN, dt: int = MMV_I8_I32, n: int = 1 << 40) -> int:
+    """Elements per workgroup tile; the default arguments give the largest tile there is."""
+    return int(load().mmv_tile_elems(op, dt, n))
 
 
 def mmv_workspace_bytes(op: int, dt: int, ff: int, n: int) -> int:

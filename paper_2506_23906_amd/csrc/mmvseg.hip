@@ -28,8 +28,18 @@
 
 namespace {
 
+// Tunables (the defaults are the measured best on MI355X; -D overrides are for experiments).
 #ifndef MMV_WAVES
-#define MMV_WAVES 4
+#define MMV_WAVES 8      // waves per workgroup
+#endif
+#ifndef MMV_CPW_F16
+#define MMV_CPW_F16 2    // most chunks per wave, 16-bit inputs (4 spills registers)
+#endif
+#ifndef MMV_CPW_F32
+#define MMV_CPW_F32 1    // most chunks per wave, fp32 inputs (2 spills registers)
+#endif
+#ifndef MMV_MIN_TILES
+#define MMV_MIN_TILES 1024  // shrink the tiles of short inputs until there are this many
 #endif
 constexpr int kWaves = MMV_WAVES;
 constexpr int kThreads = kWaves * 64;
@@ -157,32 +167,36 @@ struct TI8 {
     typedef int8_t in_t;
     typedef uint32_t acc_t;  // int32 with wrap-around
     static constexpr int kEpl = 16;  // elements per 128-bit load
-#ifndef MMV_CPW_I8
-#define MMV_CPW_I8 4
-#endif
-    static constexpr int kCpw = MMV_CPW_I8;  // chunks of 2048 elements per wave: tile = 4 waves x 4 x 2048
+    static constexpr int kMaxCpw = 4;  // most chunks of 2048 elements a wave takes (raw inputs sit in registers)
+    static constexpr mmv_dtype kDtype = MMV_I8_I32;
     static __device__ __forceinline__ acc_t widen(in_t v) { return (acc_t)(int32_t)v; }
 };
 struct TF16 {
     typedef _Float16 in_t;
     typedef float acc_t;
     static constexpr int kEpl = 8;
-    static constexpr int kCpw = 4;
+    static constexpr int kMaxCpw = MMV_CPW_F16;
+    static constexpr mmv_dtype kDtype = MMV_F16_F32;
     static __device__ __forceinline__ acc_t widen(in_t v) { return (float)v; }
 };
 struct TBF16 {
     typedef __bf16 in_t;
     typedef float acc_t;
     static constexpr int kEpl = 8;
-    static constexpr int kCpw = 4;
+    static constexpr int kMaxCpw = MMV_CPW_F16;
+    static constexpr mmv_dtype kDtype = MMV_BF16_F32;
     static __device__ __forceinline__ acc_t widen(in_t v) { return (float)v; }
 };
 struct TF32 {
     typedef float in_t;
     typedef float acc_t;
     static constexpr int kEpl = 4;
-    static constexpr int kCpw = 2;
+    static constexpr int kMaxCpw = MMV_CPW_F32;
+    static constexpr mmv_dtype kDtype = MMV_F32_F32;
     static __device__ __forceinline__ acc_t widen(in_t v) { return v; }
+};
+struct TSpmv : TF32 {  // COO SpMV: values and column indices both sit in registers, so fewer chunks
+    static constexpr int kMaxCpw = 1;
 };
 struct TInt {  // column indices of the COO matrix, loaded in the same layout as its values
     typedef int32_t in_t;
@@ -215,15 +229,22 @@ template <typename TT, bool kMfma> __device__ __forceinline__ int raw_offset(int
     return (1024 / K) * i + TT::kEpl * lane;
 }
 
-// 128 bits = 16 / sizeof(T) consecutive elements starting at element e0; elements
-// at or beyond n read as zero.
+// 128 bits = 16 / sizeof(T) consecutive elements starting at element e0 (a multiple
+// of 16 bytes); elements at or beyond n read as zero.  The aligned 16-byte block that
+// holds the last element is read whole (it cannot straddle a page) and masked.
 template <typename T> __device__ __forceinline__ v4u load128(const T *x, uint64_t e0, uint64_t n, bool full) {
     if (full) return *reinterpret_cast<const v4u *>(x + e0);
-    constexpr int kCount = 16 / sizeof(T);
-    alignas(16) T tmp[kCount];
+    v4u w = {0, 0, 0, 0};
+    if (e0 < n) {
+        w = *reinterpret_cast<const v4u *>(x + e0);
+        const uint64_t valid_bytes = (n - e0) * sizeof(T);
 #pragma unroll
-    for (int i = 0; i < kCount; ++i) tmp[i] = (e0 + i < n) ? x[e0 + i] : T(0);
-    return *reinterpret_cast<v4u *>(tmp);
+        for (int d = 0; d < 4; ++d) {
+            const int vb = valid_bytes >= 4u * d + 4u ? 4 : (valid_bytes > 4u * d ? (int)(valid_bytes - 4u * d) : 0);
+            w[d] &= vb == 4 ? ~0u : ((1u << (8 * vb)) - 1u);
+        }
+    }
+    return w;
 }
 
 // The 2 * K words of one chunk (two 32x32 tiles) starting at element chunk_base.
@@ -311,6 +332,94 @@ template <> struct SpecMfma<TF32> {
     }
 };
 
+template <> struct SpecMfma<TSpmv> : SpecMfma<TF32> {};
+
+// ---- steps 2-4 without the detour through LDS: row aggregates from the raw registers -----------------
+//
+// The aggregate of a row after the revert is x-bar(31) - x-bar(start - 1) = the sum of
+// the elements from the row's last flag on.  In the matrix-core layout a lane holds 16
+// consecutive positions of one row per 32x32 tile, so this is a masked dot product of
+// its own elements plus one exchange with the lane that holds the other half.  Returns
+// the aggregate of the row this lane owns (row r of the chunk for lane r).
+template <typename TT> struct RowAgg;
+
+__device__ __forceinline__ int last_flag_pos(uint32_t f) { return f ? 31 - __clz(f) : 0; }
+
+template <> struct RowAgg<TI8> {
+    static __device__ __forceinline__ uint32_t run(const v4u *raw, uint32_t F, int lane) {
+        const int c = lane & 31, h = lane >> 5;
+        uint32_t tot[2];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int st = last_flag_pos(__shfl(F, 32 * t + c));
+            int part = 0;
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {  // bytes of this word = positions 16h+4d .. +3; keep those >= st
+                int nv = 16 * h + 4 * d + 4 - st;
+                nv = nv < 0 ? 0 : (nv > 4 ? 4 : nv);
+                const uint32_t mask = nv == 0 ? 0u : (0x01010101u << (8 * (4 - nv)));
+                part = __builtin_amdgcn_sdot4((int)raw[t][d], (int)mask, part, false);
+            }
+            tot[t] = (uint32_t)part + (uint32_t)__shfl_xor(part, 32);
+        }
+        return lane < 32 ? tot[0] : tot[1];
+    }
+};
+
+template <bool kBf16> struct RowAggHalf {
+    static __device__ __forceinline__ float run(const v4u *raw, uint32_t F, int lane) {
+        typedef _Float16 v2h __attribute__((ext_vector_type(2)));
+        typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+        constexpr uint32_t kOne = kBf16 ? 0x3F80u : 0x3C00u;
+        const int c = lane & 31, h = lane >> 5;
+        float tot[2];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int st = last_flag_pos(__shfl(F, 32 * t + c));
+            float part = 0.0f;
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+                for (int d = 0; d < 4; ++d) {  // positions 16ks+8h+2d and +1
+                    const int p = 16 * ks + 8 * h + 2 * d;
+                    const uint32_t mask = (p >= st ? kOne : 0u) | (p + 1 >= st ? kOne << 16 : 0u);
+                    const uint32_t pair = raw[2 * t + ks][d];  // by value: bit_cast of a vector element miscompiles
+                    if (kBf16)
+                        part = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(v2bf, pair),
+                                                               __builtin_bit_cast(v2bf, mask), part, false);
+                    else
+                        part = __builtin_amdgcn_fdot2(__builtin_bit_cast(v2h, pair), __builtin_bit_cast(v2h, mask),
+                                                      part, false);
+                }
+            tot[t] = part + __shfl_xor(part, 32);
+        }
+        return lane < 32 ? tot[0] : tot[1];
+    }
+};
+template <> struct RowAgg<TF16> : RowAggHalf<false> {};
+template <> struct RowAgg<TBF16> : RowAggHalf<true> {};
+
+template <> struct RowAgg<TF32> {
+    static __device__ __forceinline__ float run(const v4u *raw, uint32_t F, int lane) {
+        const int c = lane & 31, h = lane >> 5;
+        float tot[2];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int st = last_flag_pos(__shfl(F, 32 * t + c));
+            float part = 0.0f;
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int i = 0; i < 4; ++i)  // position 16h+4q+i
+                    part += (16 * h + 4 * q + i >= st) ? from_bits<float>(raw[4 * t + q][i]) : 0.0f;
+            tot[t] = part + __shfl_xor(part, 32);
+        }
+        return lane < 32 ? tot[0] : tot[1];
+    }
+};
+template <> struct RowAgg<TSpmv> : RowAgg<TF32> {};
+
+
 // Writes the 16 results of a lane into the LDS rows of 32x32 tile t of this wave.
 template <typename A>
 __device__ __forceinline__ void store_spec_rows(uint32_t *rows, int t, int lane, const A (&acc)[16]) {
@@ -338,6 +447,7 @@ template <> __device__ __forceinline__ float raw_elem<TBF16>(const v4u &w, int i
     return from_bits<float>((w[i >> 1] >> (16 * (i & 1))) << 16);
 }
 template <> __device__ __forceinline__ float raw_elem<TF32>(const v4u &w, int i) { return from_bits<float>(w[i]); }
+template <> __device__ __forceinline__ float raw_elem<TSpmv>(const v4u &w, int i) { return from_bits<float>(w[i]); }
 
 template <typename TT>
 __device__ __forceinline__ void spec_shuffle_tile(const v4u *raw, int lane, uint32_t *rows, int t) {
@@ -371,26 +481,44 @@ __device__ __forceinline__ void spec_shuffle_tile(const v4u *raw, int lane, uint
 
 // ---- the kernel ---------------------------------------------------------------------------------------
 //
-// One workgroup = one tile = 4 waves x kCpw chunks x 2048 elements, taken from an
-// atomic ticket counter (a tile only ever waits for tiles held by workgroups that
+// One workgroup = one tile = kWaves waves x kCpw chunks x 2048 elements, taken from
+// an atomic ticket counter (a tile only ever waits for tiles held by workgroups that
 // are already running).  A same-address device-scope atomic costs about 11 ns on
 // this chip and they serialise, which is why a ticket covers tens of thousands of
 // elements.  Every wave owns a contiguous span of the tile and
 //   A. loads all its inputs at once, then for each chunk computes the speculative
 //      row scans (matrix cores), the row aggregates and their segmented scan; only
 //      a few registers per chunk are kept, the row scans themselves are dropped;
-//   -  the four wave aggregates are combined, the tile's descriptor is published
-//      and wave 0 looks back for the carry of the predecessor tiles;
+//   -  the wave aggregates are combined and the tile's descriptor is published;
 //   B. recomputes the row scans of each chunk from the raw registers (cheaper than
 //      holding them: LDS is the scarce resource), reverts the mis-speculation, adds
-//      the carries and stores.
+//      the carries and stores.  Chunks that start after a flag of the tile go first;
+//      chunks that continue a segment of an earlier tile go last, after wave 0 has
+//      looked back for the carry of the predecessor tiles.
+// The chunk loops are rolled: the per-chunk registers are rotated so that the loop
+// body always works on slot 0 (keeps the code small).
 
-template <typename TT, int kOp, bool kMfma>
-__global__ __launch_bounds__(kThreads) void seg_kernel(Params P) {
+template <typename T, int N> __device__ __forceinline__ void rotate(T (&a)[N]) {
+    const T first = a[0];
+#pragma unroll
+    for (int i = 0; i + 1 < N; ++i) a[i] = a[i + 1];
+    a[N - 1] = first;
+}
+template <int N, int M> __device__ __forceinline__ void rotate_rows(v4u (&a)[N][M]) {
+#pragma unroll
+    for (int m = 0; m < M; ++m) {
+        const v4u first = a[0][m];
+#pragma unroll
+        for (int i = 0; i + 1 < N; ++i) a[i][m] = a[i + 1][m];
+        a[N - 1][m] = first;
+    }
+}
+
+template <typename TT, int kOp, bool kMfma, int kCpw>
+__global__ __launch_bounds__(kThreads, 4) void seg_kernel(Params P) {
     typedef typename TT::acc_t A;
     typedef typename TT::in_t In;
     constexpr int K = 16 / TT::kEpl;             // 128-bit words per lane and 32x32 tile
-    constexpr int kCpw = TT::kCpw;               // chunks per wave
     constexpr int kWaveSpan = kCpw * kChunkElems;
     constexpr int kTile = kWaves * kWaveSpan;
 
@@ -438,11 +566,16 @@ __global__ __launch_bounds__(kThreads) void seg_kernel(Params P) {
     // my span; run_* = running aggregate of the span
     A ex_v[kCpw], pre_v[kCpw];
     uint32_t ex_f[kCpw], pre_f[kCpw], ex_c[kCpw];
+#pragma unroll
+    for (int c = 0; c < kCpw; ++c) {
+        ex_v[c] = pre_v[c] = A(0);
+        ex_f[c] = pre_f[c] = ex_c[c] = 0;
+    }
     A run_v = A(0);
     uint32_t run_f = 0, run_c = 0;
 
     // ================= phase A: aggregates =================
-#pragma unroll
+#pragma unroll 1
     for (int c = 0; c < kCpw; ++c) {
         const uint64_t cb = wave_base + (uint64_t)c * kChunkElems;
         const uint64_t row_start = cb + 32u * lane;  // first element of the row this lane owns
@@ -461,7 +594,7 @@ __global__ __launch_bounds__(kThreads) void seg_kernel(Params P) {
                 if (lane == 2 * j + 1) Fc = (uint32_t)(m >> 32);
                 prev_last = __shfl(r, 63);
             }
-            F[c] = Fc;
+            F[0] = Fc;
             // product vector p(i) = val(i) * x(col(i)), in the layout the values were loaded in
 #pragma unroll
             for (int t = 0; t < 2; ++t)
@@ -471,35 +604,31 @@ __global__ __launch_bounds__(kThreads) void seg_kernel(Params P) {
 #pragma unroll
                     for (int k = 0; k < 4; ++k) {
                         const float p =
-                            (e0 + k < n) ? from_bits<float>(raw[c][t * K + i][k]) * P.xv[rawc[c][t * K + i][k]] : 0.0f;
-                        raw[c][t * K + i][k] = to_bits(p);
+                            (e0 + k < n) ? from_bits<float>(raw[0][t * K + i][k]) * P.xv[rawc[0][t * K + i][k]] : 0.0f;
+                        raw[0][t * K + i][k] = to_bits(p);
                     }
                 }
         } else if (row_start + 32 > n) {
-            F[c] = row_start < n ? (F[c] & ((1u << (uint32_t)(n - row_start)) - 1u)) : 0u;
+            F[0] = row_start < n ? (F[0] & ((1u << (uint32_t)(n - row_start)) - 1u)) : 0u;
         }
 
-        // ---- step 1: speculative row scans into LDS ----
+        // ---- steps 1-4 for the aggregate of my row: last element after the revert, any flag ----
+        const uint32_t has_flag = F[0] != 0;
+        A agg_v;
+        if constexpr (kMfma) {
+            agg_v = RowAgg<TT>::run(raw[0], F[0], lane);
+        } else {
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            if (kMfma) {
-                A acc[16];
-                SpecMfma<TT>::run(raw[c] + t * K, lane, acc);
-                store_spec_rows(rows, t, lane, acc);
-            } else {
-                spec_shuffle_tile<TT>(raw[c] + t * K, lane, rows, t);
-            }
+            for (int t = 0; t < 2; ++t) spec_shuffle_tile<TT>(raw[0] + t * K, lane, rows, t);
+            rows[lane * kRowStride + kSlotZero] = 0;
+            wave_lds_sync();
+            const A last = from_bits<A>(rows[lane * kRowStride + kRowData + 31]);
+            const int slot = kSlotZero + last_flag_pos(F[0]);  // x-bar(start - 1)
+            agg_v = last - from_bits<A>(rows[lane * kRowStride + slot]);
+            wave_lds_sync();  // the rows are read before the next chunk overwrites them
         }
-        rows[lane * kRowStride + kSlotZero] = 0;
-        wave_lds_sync();
-
-        // ---- steps 2-4 for the aggregate of my row: last element after the revert, any flag ----
-        const uint32_t has_flag = F[c] != 0;
-        const A last = from_bits<A>(rows[lane * kRowStride + kRowData + 31]);
-        const int slot = has_flag ? kSlotZero + (31 - __clz(F[c])) : kSlotZero;  // x-bar(start - 1)
-        const A agg_v = last - from_bits<A>(rows[lane * kRowStride + slot]);
         // segment starts in my row, position 0 of the whole vector not counted (sum only)
-        const uint32_t cnt = __popc(row_start == 0 ? (F[c] & ~1u) : F[c]);
+        const uint32_t cnt = __popc(row_start == 0 ? (F[0] & ~1u) : F[0]);
 
         // ---- step 5a: segmented inclusive scan of (value, flag) over the 64 rows of the chunk ----
         A inc_v = agg_v;
@@ -518,22 +647,29 @@ __global__ __launch_bounds__(kThreads) void seg_kernel(Params P) {
                 if (lane >= d) inc_c += oc;
             }
         }
-        ex_v[c] = from_bits<A>(__shfl_up(to_bits(inc_v), 1));
-        ex_f[c] = __shfl_up(inc_f, 1);
+        ex_v[0] = from_bits<A>(__shfl_up(to_bits(inc_v), 1));
+        ex_f[0] = __shfl_up(inc_f, 1);
         if (lane == 0) {
-            ex_v[c] = A(0);
-            ex_f[c] = 0;
+            ex_v[0] = A(0);
+            ex_f[0] = 0;
         }
-        ex_c[c] = run_c + inc_c - cnt;
-        pre_v[c] = run_v;
-        pre_f[c] = run_f;
+        ex_c[0] = run_c + inc_c - cnt;
+        pre_v[0] = run_v;
+        pre_f[0] = run_f;
         // chunk aggregate = inclusive value of the last row; fold it into the span's running aggregate
         const A ca_v = from_bits<A>(__shfl(to_bits(inc_v), 63));
         const uint32_t ca_f = __shfl(inc_f, 63);
         run_v = ca_f ? ca_v : run_v + ca_v;
         run_f |= ca_f;
         if (kOp == kSum) run_c += __shfl(inc_c, 63);
-        wave_lds_sync();  // the rows are read before the next chunk overwrites them
+        rotate(F);
+        rotate_rows(raw);
+        if constexpr (kOp == kSpmv) rotate_rows(rawc);
+        rotate(ex_v);
+        rotate(ex_f);
+        rotate(pre_v);
+        rotate(pre_f);
+        if (kOp == kSum) rotate(ex_c);
     }
     MMV_STAMP(2);
     if (lane == 0) {
@@ -562,152 +698,170 @@ __global__ __launch_bounds__(kThreads) void seg_kernel(Params P) {
         tagg_f |= wf;
         tagg_c += s_wave_c[w];
     }
+    wex_f = __builtin_amdgcn_readfirstlane(wex_f);
 
-    // ---- step 5c: tiles, by decoupled look-back ----
-    A tile_carry = A(0);
+    // ---- step 5c, first half: publish this tile ----
+    const bool final_now = tile == 0 || tagg_f;  // carry out does not depend on predecessors
+    if (tid == 0) desc_store(P.desc_v + tile, final_now ? kStatusPrefix : kStatusAggregate, to_bits(tagg_v));
+    if (kOp == kSum && tid == 64) desc_store(P.desc_c + tile, tile == 0 ? kStatusPrefix : kStatusAggregate, tagg_c);
+
+    // carry into my span (used only by rows with no flag before them in the tile); the carry of
+    // the predecessor tiles is added once it is known
+    A span_carry = wex_v;
     uint32_t count_carry = 0;
-    if (wave == 0) {
-        const bool final_now = tile == 0 || tagg_f;  // carry out does not depend on predecessors
-        if (lane == 0) desc_store(P.desc_v + tile, final_now ? kStatusPrefix : kStatusAggregate, to_bits(tagg_v));
-        if (tile > 0) tile_carry = lookback<A>(P.desc_v, (int)tile, lane, P.hdr);
-        MMV_STAMP(4);
-        if (lane == 0) {
-            if (!final_now) desc_store(P.desc_v + tile, kStatusPrefix, to_bits(tile_carry + tagg_v));
-            s_carry_v = to_bits(tile_carry);
-            __hip_atomic_store(&s_ready, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
-        }
-    }
-    if (kOp == kSum) {
-        if (wave == 1) {
-            if (lane == 0) desc_store(P.desc_c + tile, tile == 0 ? kStatusPrefix : kStatusAggregate, tagg_c);
-            uint32_t carry = 0;
-            if (tile > 0) carry = lookback<uint32_t>(P.desc_c, (int)tile, lane, P.hdr);
-            if (lane == 0) {
-                if (tile > 0) desc_store(P.desc_c + tile, kStatusPrefix, carry + tagg_c);
-                s_carry_c = carry;
-                if (tile == P.num_tiles - 1) *P.nseg = (uint64_t)carry + tagg_c + 1u;
-            }
-        }
-        __syncthreads();  // every output index needs the count carry
-        count_carry = s_carry_c;
-        tile_carry = from_bits<A>(s_carry_v);
-    } else if (wave != 0 && !wex_f) {
-        // my span starts inside a segment that began in an earlier tile: wait for wave 0
-        while (__hip_atomic_load(&s_ready, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) == 0)
-            __builtin_amdgcn_s_sleep(1);
-        tile_carry = from_bits<A>(s_carry_v);
-    }
-    MMV_STAMP(5);
-    // carry into my span (used only by rows with no flag before them in the tile)
-    const A span_carry = wex_f ? wex_v : tile_carry + wex_v;
 
     // ================= phase B: recompute, revert, add carries, store =================
-#pragma unroll
-    for (int c = 0; c < kCpw; ++c) {
-        const uint64_t cb = wave_base + (uint64_t)c * kChunkElems;
-        const bool chunk_full = cb + kChunkElems <= n;
-        const uint64_t row_start = cb + 32u * lane;
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            if (kMfma) {
-                A acc[16];
-                SpecMfma<TT>::run(raw[c] + t * K, lane, acc);
-                store_spec_rows(rows, t, lane, acc);
-            } else {
-                spec_shuffle_tile<TT>(raw[c] + t * K, lane, rows, t);
-            }
-        }
-        // ---- step 6: carry into my row; stored negated so that the revert subtracts it ----
-        const A carry = ex_f[c] ? ex_v[c] : (pre_f[c] ? pre_v[c] + ex_v[c] : (span_carry + pre_v[c]) + ex_v[c]);
-        rows[lane * kRowStride + kSlotZero] = 0;
-        rows[lane * kRowStride + kSlotF] = F[c];
-        rows[lane * kRowStride + kSlotNegCarry] = to_bits(A(0) - carry);
-        if (kOp != kScan) {
-            // segment-end mask of my row: bit p set iff position p + 1 starts a segment or p is
-            // the last element of the vector
-            uint32_t next0 = __shfl_down(F[c], 1) & 1u;
-            if (lane == 63) {
-                const uint64_t en = cb + kChunkElems;
-                next0 = 0;
-                if (en < n) next0 = kOp == kSpmv ? (P.row[en] != P.row[en - 1]) : (P.fw[en >> 5] & 1u);
-            }
-            uint32_t E = (F[c] >> 1) | (next0 << 31);
-            if (row_start < n) {
-                if (row_start + 32 >= n) {
-                    const uint32_t last = (uint32_t)(n - 1 - row_start);
-                    E = (E & ((1u << last) - 1u)) | (1u << last);
-                }
-            } else {
-                E = 0;
-            }
-            rows[lane * kRowStride + kSlotE] = E;
-            if (kOp == kSum) s_cnt[wave * kRowsPerChunk + lane] = count_carry + wex_c + ex_c[c];
-        }
-        const uint64_t row_any = __ballot(F[c] != 0);
-        wave_lds_sync();
-
-        // ---- steps 2 + 6 on every element, then store; a lane owns 4 consecutive positions ----
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const int R = 8 * j + (lane >> 3), p0 = 4 * (lane & 7);
-            const uint32_t *rp = rows + R * kRowStride;
-            const v4u xb = *reinterpret_cast<const v4u *>(rp + kRowData + p0);
-            A o[4];
-            uint32_t Fr = 0;
-            if (((row_any >> (8 * j)) & 0xFFull) == 0) {
-                // none of these eight rows has a flag: the speculation stands, only the carry is added
-                const A nc = from_bits<A>(rp[kSlotNegCarry]);
-#pragma unroll
-                for (int i = 0; i < 4; ++i) o[i] = from_bits<A>(xb[i]) - nc;
-            } else {
-                Fr = rp[kSlotF];
-                const uint32_t m = Fr & ((2u << p0) - 1u);  // flags at or before my first position
-                const int slot = m ? kSlotZero + (31 - __clz(m)) : kSlotNegCarry;
-                A b = from_bits<A>(rp[slot]);
-                o[0] = from_bits<A>(xb[0]) - b;
-#pragma unroll
-                for (int i = 1; i < 4; ++i) {
-                    if ((Fr >> (p0 + i)) & 1u) b = from_bits<A>(xb[i - 1]);
-                    o[i] = from_bits<A>(xb[i]) - b;
+#pragma unroll 1
+    for (int pass = 0; pass < 2; ++pass) {
+        if (pass == 1) {
+            // ---- step 5c, second half: carry of the predecessor tiles by decoupled look-back ----
+            A tile_carry = A(0);
+            if (wave == 0) {
+                if (tile > 0) tile_carry = lookback<A>(P.desc_v, (int)tile, lane, P.hdr);
+                MMV_STAMP(4);
+                if (lane == 0) {
+                    if (!final_now) desc_store(P.desc_v + tile, kStatusPrefix, to_bits(tile_carry + tagg_v));
+                    s_carry_v = to_bits(tile_carry);
+                    __hip_atomic_store(&s_ready, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
                 }
             }
-            const uint64_t e0 = cb + 256u * j + 4u * lane;
-            if (kOp == kScan) {
-                A *z = (A *)P.z;
-                if (chunk_full) {
-                    v4u w = {to_bits(o[0]), to_bits(o[1]), to_bits(o[2]), to_bits(o[3])};
-#ifdef MMV_PLAIN_STORE
-                    *reinterpret_cast<v4u *>(z + e0) = w;
-#else
-                    __builtin_nontemporal_store(w, reinterpret_cast<v4u *>(z + e0));
-#endif
-                } else {
-#pragma unroll
-                    for (int i = 0; i < 4; ++i)
-                        if (e0 + i < n) z[e0 + i] = o[i];
-                }
-            } else {
-                const uint32_t ends = (rp[kSlotE] >> p0) & 0xFu;
-                if (ends) {
-                    if (kOp == kSum) {
-                        if (!Fr) Fr = rp[kSlotF];
-                        const uint32_t Frc = (cb == 0 && R == 0) ? (Fr & ~1u) : Fr;
-                        const uint32_t base = s_cnt[wave * kRowsPerChunk + R];
-#pragma unroll
-                        for (int i = 0; i < 4; ++i)
-                            if ((ends >> i) & 1u) {
-                                const uint64_t k = (uint64_t)base + __popc(Frc & ((2u << (p0 + i)) - 1u));
-                                if (k < P.out_cap) ((A *)P.out)[k] = o[i];
-                            }
-                    } else {
-#pragma unroll
-                        for (int i = 0; i < 4; ++i)
-                            if ((ends >> i) & 1u) P.y[P.row[e0 + i]] = from_bits<float>(to_bits(o[i]));
+            if (kOp == kSum) {
+                if (wave == 1) {
+                    uint32_t carry = 0;
+                    if (tile > 0) carry = lookback<uint32_t>(P.desc_c, (int)tile, lane, P.hdr);
+                    if (lane == 0) {
+                        if (tile > 0) desc_store(P.desc_c + tile, kStatusPrefix, carry + tagg_c);
+                        s_carry_c = carry;
+                        if (tile == P.num_tiles - 1) *P.nseg = (uint64_t)carry + tagg_c + 1u;
                     }
                 }
+                __syncthreads();  // every output index needs the count carry
+                count_carry = s_carry_c;
+                tile_carry = from_bits<A>(s_carry_v);
+            } else if (wave != 0 && !wex_f) {
+                // my span starts inside a segment that began in an earlier tile: wait for wave 0
+                while (__hip_atomic_load(&s_ready, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) == 0)
+                    __builtin_amdgcn_s_sleep(1);
+                tile_carry = from_bits<A>(s_carry_v);
             }
+            if (!wex_f) span_carry = tile_carry + wex_v;
+            MMV_STAMP(5);
         }
-        wave_lds_sync();  // the rows are read before the next chunk overwrites them
+#pragma unroll 1
+        for (int c = 0; c < kCpw; ++c) {
+            // a chunk is "open" when no flag of the tile precedes it; the segmented sum treats
+            // every chunk as open because all its output indices wait for the count carry
+            const bool chunk_open = kOp == kSum || !(wex_f || __builtin_amdgcn_readfirstlane(pre_f[0]));
+            if (chunk_open == (pass == 1)) {
+                const uint64_t cb = wave_base + (uint64_t)c * kChunkElems;
+                const bool chunk_full = cb + kChunkElems <= n;
+                const uint64_t row_start = cb + 32u * lane;
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    if (kMfma) {
+                        A acc[16];
+                        SpecMfma<TT>::run(raw[0] + t * K, lane, acc);
+                        store_spec_rows(rows, t, lane, acc);
+                    } else {
+                        spec_shuffle_tile<TT>(raw[0] + t * K, lane, rows, t);
+                    }
+                }
+                // ---- step 6: carry into my row; stored negated so that the revert subtracts it ----
+                const A carry = ex_f[0] ? ex_v[0] : (pre_f[0] ? pre_v[0] + ex_v[0] : (span_carry + pre_v[0]) + ex_v[0]);
+                rows[lane * kRowStride + kSlotZero] = 0;
+                rows[lane * kRowStride + kSlotF] = F[0];
+                rows[lane * kRowStride + kSlotNegCarry] = to_bits(A(0) - carry);
+                if (kOp != kScan) {
+                    // segment-end mask of my row: bit p set iff position p + 1 starts a segment or
+                    // p is the last element of the vector
+                    uint32_t next0 = __shfl_down(F[0], 1) & 1u;
+                    if (lane == 63) {
+                        const uint64_t en = cb + kChunkElems;
+                        next0 = 0;
+                        if (en < n) next0 = kOp == kSpmv ? (P.row[en] != P.row[en - 1]) : (P.fw[en >> 5] & 1u);
+                    }
+                    uint32_t E = (F[0] >> 1) | (next0 << 31);
+                    if (row_start < n) {
+                        if (row_start + 32 >= n) {
+                            const uint32_t last = (uint32_t)(n - 1 - row_start);
+                            E = (E & ((1u << last) - 1u)) | (1u << last);
+                        }
+                    } else {
+                        E = 0;
+                    }
+                    rows[lane * kRowStride + kSlotE] = E;
+                    if (kOp == kSum) s_cnt[wave * kRowsPerChunk + lane] = count_carry + wex_c + ex_c[0];
+                }
+                const uint64_t row_any = __ballot(F[0] != 0);
+                wave_lds_sync();
+
+                // ---- steps 2 + 6 on every element, then store; a lane owns 4 consecutive positions ----
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int R = 8 * j + (lane >> 3), p0 = 4 * (lane & 7);
+                    const uint32_t *rp = rows + R * kRowStride;
+                    const v4u xb = *reinterpret_cast<const v4u *>(rp + kRowData + p0);
+                    A o[4];
+                    uint32_t Fr = 0;
+                    if (((row_any >> (8 * j)) & 0xFFull) == 0) {
+                        // none of these eight rows has a flag: the speculation stands, only the carry is added
+                        const A nc = from_bits<A>(rp[kSlotNegCarry]);
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) o[i] = from_bits<A>(xb[i]) - nc;
+                    } else {
+                        Fr = rp[kSlotF];
+                        const uint32_t m = Fr & ((2u << p0) - 1u);  // flags at or before my first position
+                        const int slot = m ? kSlotZero + (31 - __clz(m)) : kSlotNegCarry;
+                        A b = from_bits<A>(rp[slot]);
+                        o[0] = from_bits<A>(xb[0]) - b;
+#pragma unroll
+                        for (int i = 1; i < 4; ++i) {
+                            if ((Fr >> (p0 + i)) & 1u) b = from_bits<A>(xb[i - 1]);
+                            o[i] = from_bits<A>(xb[i]) - b;
+                        }
+                    }
+                    const uint64_t e0 = cb + 256u * j + 4u * lane;
+                    if (kOp == kScan) {
+                        A *z = (A *)P.z;
+                        if (chunk_full) {
+                            v4u w = {to_bits(o[0]), to_bits(o[1]), to_bits(o[2]), to_bits(o[3])};
+                            __builtin_nontemporal_store(w, reinterpret_cast<v4u *>(z + e0));
+                        } else {
+#pragma unroll
+                            for (int i = 0; i < 4; ++i)
+                                if (e0 + i < n) z[e0 + i] = o[i];
+                        }
+                    } else {
+                        const uint32_t ends = (rp[kSlotE] >> p0) & 0xFu;
+                        if (ends) {
+                            if (kOp == kSum) {
+                                if (!Fr) Fr = rp[kSlotF];
+                                const uint32_t Frc = (cb == 0 && R == 0) ? (Fr & ~1u) : Fr;
+                                const uint32_t base = s_cnt[wave * kRowsPerChunk + R];
+#pragma unroll
+                                for (int i = 0; i < 4; ++i)
+                                    if ((ends >> i) & 1u) {
+                                        const uint64_t k = (uint64_t)base + __popc(Frc & ((2u << (p0 + i)) - 1u));
+                                        if (k < P.out_cap) ((A *)P.out)[k] = o[i];
+                                    }
+                            } else {
+#pragma unroll
+                                for (int i = 0; i < 4; ++i)
+                                    if ((ends >> i) & 1u) P.y[P.row[e0 + i]] = from_bits<float>(to_bits(o[i]));
+                            }
+                        }
+                    }
+                }
+                wave_lds_sync();  // the rows are read before the next chunk overwrites them
+            }
+            rotate(F);
+            rotate_rows(raw);
+            rotate(ex_v);
+            rotate(ex_f);
+            rotate(pre_v);
+            rotate(pre_f);
+            if (kOp == kSum) rotate(ex_c);
+        }
     }
     MMV_STAMP(6);
 #ifdef MMV_TRACE
@@ -748,42 +902,55 @@ __global__ __launch_bounds__(256) void pack_flags_kernel(const uint8_t *f, uint6
     }
 }
 
-// Streaming reference: 128-bit reads and writes, kIn input chunks and kOut output
-// chunks per thread and step, both striped across the workgroup.
+// Streaming reference: 128-bit non-temporal reads and writes, kIn input chunks and kOut
+// output chunks per thread, both striped across the workgroup; one workgroup per 256
+// units (measured faster than a persistent grid-stride loop on this chip).
 template <int kIn, int kOut>
 __global__ __launch_bounds__(256) void stream_copy_kernel(const v4u *src, v4u *dst, uint64_t units) {
-    const uint64_t nblocks = (units + 255) / 256;
-    for (uint64_t blk = blockIdx.x; blk < nblocks; blk += gridDim.x) {
-        const uint64_t u0 = blk * 256;
-        v4u acc = {0, 0, 0, 0};
+    const uint64_t u0 = (uint64_t)blockIdx.x * 256;
+    v4u acc = {0, 0, 0, 0};
 #pragma unroll
-        for (int i = 0; i < kIn; ++i) {
-            const uint64_t idx = u0 * kIn + (uint64_t)i * 256 + threadIdx.x;
-            if (idx < units * kIn) acc ^= src[idx];
-        }
-#pragma unroll
-        for (int i = 0; i < kOut; ++i) {
-            const uint64_t idx = u0 * kOut + (uint64_t)i * 256 + threadIdx.x;
-            if (idx < units * kOut) dst[idx] = acc + (unsigned)i;
-        }
-        if (kOut == 0 && acc[0] == 0x9E3779B9u && acc[1] == 0x7F4A7C15u && acc[2] == 1u && acc[3] == 2u)
-            dst[0] = acc;  // keeps the reads alive; practically never taken
+    for (int i = 0; i < kIn; ++i) {
+        const uint64_t idx = u0 * kIn + (uint64_t)i * 256 + threadIdx.x;
+        if (idx < units * kIn) acc ^= __builtin_nontemporal_load(src + idx);
     }
+#pragma unroll
+    for (int i = 0; i < kOut; ++i) {
+        const uint64_t idx = u0 * kOut + (uint64_t)i * 256 + threadIdx.x;
+        if (idx < units * kOut) __builtin_nontemporal_store(acc + (unsigned)i, dst + idx);
+    }
+    if (kOut == 0 && acc[0] == 0x9E3779B9u && acc[1] == 0x7F4A7C15u && acc[2] == 1u && acc[3] == 2u)
+        dst[0] = acc;  // keeps the reads alive; practically never taken
 }
 
 // ---- host side -------------------------------------------------------------------------------------------------
 
 inline size_t round256(size_t b) { return (b + 255) & ~(size_t)255; }
-inline uint32_t tile_elems(mmv_dtype dt) {
+// Chunks of 2048 elements per wave.  A tile costs one ticket (about 11 ns, serialised), so
+// tiles are as large as the registers allow, but not so large that a short input leaves
+// compute units without a tile.
+constexpr uint64_t kMinTiles = MMV_MIN_TILES;
+inline int max_cpw(mmv_op op, mmv_dtype dt) {
+    if (op == MMV_OP_SPMV_COO) return TSpmv::kMaxCpw;
     switch (dt) {
-        case MMV_F32_F32: return kWaves * TF32::kCpw * kChunkElems;
-        case MMV_F16_F32: return kWaves * TF16::kCpw * kChunkElems;
-        case MMV_BF16_F32: return kWaves * TBF16::kCpw * kChunkElems;
-        case MMV_I8_I32: return kWaves * TI8::kCpw * kChunkElems;
+        case MMV_F32_F32: return TF32::kMaxCpw;
+        case MMV_F16_F32: return TF16::kMaxCpw;
+        case MMV_BF16_F32: return TBF16::kMaxCpw;
+        case MMV_I8_I32: return TI8::kMaxCpw;
     }
-    return 0;
+    return 1;
 }
-inline uint64_t tiles_for(uint64_t n, mmv_dtype dt) { return (n + tile_elems(dt) - 1) / tile_elems(dt); }
+inline int choose_cpw(mmv_op op, mmv_dtype dt, uint64_t n) {
+    int cpw = max_cpw(op, dt);
+    while (cpw > 1 && (n + (uint64_t)kWaves * cpw * kChunkElems - 1) / ((uint64_t)kWaves * cpw * kChunkElems) < kMinTiles)
+        cpw >>= 1;
+    return cpw;
+}
+inline uint32_t tile_elems(mmv_op op, mmv_dtype dt, uint64_t n) { return kWaves * choose_cpw(op, dt, n) * kChunkElems; }
+inline uint64_t tiles_for(uint64_t n, mmv_op op, mmv_dtype dt) {
+    const uint32_t t = tile_elems(op, dt, n);
+    return (n + t - 1) / t;
+}
 inline bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
 
 struct WsLayout {
@@ -792,7 +959,7 @@ struct WsLayout {
 
 WsLayout ws_layout(mmv_op op, mmv_dtype dt, mmv_flag_fmt ff, uint64_t n) {
     WsLayout L;
-    const uint64_t t = tiles_for(n, dt);
+    const uint64_t t = tiles_for(n, op, dt);
     size_t off = kHdrBytes;
     L.desc_v = off;
     off += round256(t * 8);
@@ -812,21 +979,26 @@ uint64_t *g_trace = nullptr;
 // right after the main kernel of a call made by this host thread.
 thread_local hipEvent_t tl_ev_start = nullptr, tl_ev_stop = nullptr;
 
-template <typename TT, int kOp, bool kMfma> hipError_t launch_variant(Params P, hipStream_t s) {
+template <typename TT, int kOp, bool kMfma> hipError_t launch_variant(Params P, int cpw, hipStream_t s) {
 #ifdef MMV_TRACE
     P.trace = g_trace;
 #endif
-    seg_kernel<TT, kOp, kMfma><<<P.num_tiles, kThreads, 0, s>>>(P);
+    if (cpw == 1) seg_kernel<TT, kOp, kMfma, 1><<<P.num_tiles, kThreads, 0, s>>>(P);
+    if constexpr (TT::kMaxCpw >= 2)
+        if (cpw == 2) seg_kernel<TT, kOp, kMfma, 2><<<P.num_tiles, kThreads, 0, s>>>(P);
+    if constexpr (TT::kMaxCpw >= 4)
+        if (cpw == 4) seg_kernel<TT, kOp, kMfma, 4><<<P.num_tiles, kThreads, 0, s>>>(P);
     return hipGetLastError();
 }
 
 template <typename TT, int kOp>
 hipError_t launch_seg(const Params &P, mmv_variant v, hipStream_t s) {
     if (tl_ev_start && hipEventRecord(tl_ev_start, s) != hipSuccess) return hipErrorUnknown;
+    const int cpw = choose_cpw((mmv_op)kOp, TT::kDtype, P.n);
     if (v == MMV_VARIANT_MFMA) {
-        if (launch_variant<TT, kOp, true>(P, s) != hipSuccess) return hipErrorUnknown;
+        if (launch_variant<TT, kOp, true>(P, cpw, s) != hipSuccess) return hipErrorUnknown;
     } else {
-        if (launch_variant<TT, kOp, false>(P, s) != hipSuccess) return hipErrorUnknown;
+        if (launch_variant<TT, kOp, false>(P, cpw, s) != hipSuccess) return hipErrorUnknown;
     }
     const hipError_t e = hipGetLastError();
     if (tl_ev_stop && hipEventRecord(tl_ev_stop, s) != hipSuccess) return hipErrorUnknown;
@@ -870,7 +1042,7 @@ mmv_status prepare(mmv_op op, const void *d_x, const void *d_flags, uint64_t n, 
     P.hdr = (uint32_t *)ws;
     P.desc_v = (uint64_t *)(ws + L.desc_v);
     P.desc_c = (uint64_t *)(ws + L.desc_c);
-    P.num_tiles = (uint32_t)tiles_for(n, dt);
+    P.num_tiles = (uint32_t)tiles_for(n, op, dt);
     const uint64_t zero_words = L.packed / 4;  // header + descriptors
     fill_zero_kernel<<<grid_for(zero_words), 256, 0, s>>>((uint32_t *)ws, zero_words, nullptr, 0);
     if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
@@ -959,12 +1131,12 @@ mmv_status mmv_spmv_coo(uint64_t n_rows, uint64_t n_cols, uint64_t nnz, const in
     P.hdr = (uint32_t *)ws;
     P.desc_v = (uint64_t *)(ws + L.desc_v);
     P.desc_c = nullptr;
-    P.num_tiles = (uint32_t)tiles_for(nnz, MMV_F32_F32);
+    P.num_tiles = (uint32_t)tiles_for(nnz, MMV_OP_SPMV_COO, MMV_F32_F32);
     const uint64_t zero_words = L.total / 4;
     fill_zero_kernel<<<grid_for(zero_words > n_rows ? zero_words : n_rows), 256, 0, s>>>((uint32_t *)ws, zero_words,
                                                                                       (uint32_t *)d_y, n_rows);
     if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
-    return launch_seg<TF32, kSpmv>(P, v, s) == hipSuccess ? MMV_OK : MMV_ERR_HIP;
+    return launch_seg<TSpmv, kSpmv>(P, v, s) == hipSuccess ? MMV_OK : MMV_ERR_HIP;
 }
 
 mmv_status mmv_workspace_status(const void *d_ws, void *hip_stream, uint32_t *h_status) {
@@ -989,9 +1161,9 @@ mmv_status mmv_stream_copy(const void *d_src, size_t in_bytes, void *d_dst, size
 #define MMV_COPY(KI, KO, UNITS)                                                                          \
     do {                                                                                                 \
         const uint64_t units_ = (UNITS);                                                                 \
-        uint64_t blocks_ = (units_ + 255) / 256;                                                         \
-        if (blocks_ > 16384) blocks_ = 16384;                                                            \
-        stream_copy_kernel<KI, KO><<<(int)blocks_, 256, 0, s>>>(src, dst, units_);                       \
+        const uint64_t blocks_ = (units_ + 255) / 256;                                                   \
+        if (blocks_ > 0x7fffffffull) return MMV_ERR_INVALID_ARG;                                         \
+        stream_copy_kernel<KI, KO><<<(unsigned)blocks_, 256, 0, s>>>(src, dst, units_);                  \
     } while (0)
     if (no == 0) MMV_COPY(1, 0, ni);
     else if (ni == 0) MMV_COPY(0, 1, no);
@@ -1028,6 +1200,9 @@ const char *mmv_status_string(mmv_status s) {
     return "unknown status";
 }
 
-uint32_t mmv_tile_elems(mmv_dtype dt) { return valid_dtype(dt) ? tile_elems(dt) : 0; }
+uint32_t mmv_tile_elems(mmv_op op, mmv_dtype dt, uint64_t n) {
+    if ((int)op < 0 || (int)op > 2 || !valid_dtype(dt)) return 0;
+    return tile_elems(op, op == MMV_OP_SPMV_COO ? MMV_F32_F32 : dt, n);
+}
 
 }  // extern "C"

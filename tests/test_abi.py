@@ -27,17 +27,25 @@ def test_library_exports_every_declared_symbol(libmmvseg_path):
 def test_host_only_entry_points(libmmvseg_path):
     from paper_2506_23906_amd import binding as B
     lib = B.load()
-    tile = B.mmv_tile_elems(B.MMV_I8_I32)
-    assert tile == 32768 and B.mmv_tile_elems(B.MMV_F16_F32) == 32768
-    assert B.mmv_tile_elems(B.MMV_F32_F32) == 16384 and B.mmv_tile_elems(9) == 0
+    big = 1 << 40
+    tile = B.mmv_tile_elems(B.MMV_OP_SEGSCAN, B.MMV_I8_I32, big)
+    assert tile % 2048 == 0 and tile >= 8192
+    for dt in (B.MMV_F16_F32, B.MMV_BF16_F32, B.MMV_F32_F32):
+        t = B.mmv_tile_elems(B.MMV_OP_SEGSCAN, dt, big)
+        assert t % 2048 == 0 and 0 < t <= tile
+    small = B.mmv_tile_elems(B.MMV_OP_SEGSCAN, B.MMV_I8_I32, 1000)                # short inputs: small tiles
+    assert small % 2048 == 0 and small <= tile
+    assert B.mmv_tile_elems(B.MMV_OP_SEGSCAN, 9, big) == 0 and B.mmv_tile_elems(7, B.MMV_I8_I32, big) == 0
     assert lib.mmv_status_string(0) == b"ok"
     assert lib.mmv_status_string(4).startswith(b"workspace")
     # header + one 8-byte descriptor per tile, rounded to 256 bytes
     assert B.mmv_workspace_bytes(B.MMV_OP_SEGSCAN, B.MMV_I8_I32, B.MMV_FLAGS_PACKED32, 1) == 512
     n = 1 << 28
+    tile = B.mmv_tile_elems(B.MMV_OP_SEGSCAN, B.MMV_I8_I32, n)
     scan = B.mmv_workspace_bytes(B.MMV_OP_SEGSCAN, B.MMV_I8_I32, B.MMV_FLAGS_PACKED32, n)
     assert scan == 256 + (n // tile) * 8
-    assert B.mmv_workspace_bytes(B.MMV_OP_SEGSUM, B.MMV_F16_F32, B.MMV_FLAGS_PACKED32, n) == 256 + 2 * (n // tile) * 8
+    t16 = B.mmv_tile_elems(B.MMV_OP_SEGSUM, B.MMV_F16_F32, n)
+    assert B.mmv_workspace_bytes(B.MMV_OP_SEGSUM, B.MMV_F16_F32, B.MMV_FLAGS_PACKED32, n) == 256 + 2 * (n // t16) * 8
     assert B.mmv_workspace_bytes(B.MMV_OP_SEGSCAN, B.MMV_I8_I32, B.MMV_FLAGS_U8, n) == scan + n // 8
     assert B.mmv_workspace_bytes(B.MMV_OP_SEGSCAN, 7, B.MMV_FLAGS_U8, n) == 0      # bad dtype
     assert B.mmv_workspace_bytes(5, B.MMV_I8_I32, B.MMV_FLAGS_U8, n) == 0          # bad op
