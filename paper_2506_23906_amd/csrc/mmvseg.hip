@@ -220,23 +220,46 @@ struct TInt {  // column indices of the COO matrix, loaded in the same layout as
 //
 // Shuffle layout (ablation): lane l holds kEpl consecutive elements, striped.
 
+// fp32 is loaded striped in both variants (128 B rows would otherwise make every
+// instruction touch 32 cache lines for 1 KiB) and the matrix-core variant moves it into
+// the operand layout through LDS (to_operand_layout).
 template <typename TT, bool kMfma> __device__ __forceinline__ int raw_offset(int i, int lane) {
     constexpr int K = 16 / TT::kEpl;
-    if (kMfma) {
+    if (kMfma && K < 4) {
         const int c = lane & 31, h = lane >> 5;
-        return 32 * c + (K == 2 ? 16 * i + 8 * h : 16 * h + 4 * i);
+        return 32 * c + (K == 2 ? 16 * i + 8 * h : 16 * h);
     }
     return (1024 / K) * i + TT::kEpl * lane;
+}
+
+// fp32 chunk (2 x 4 words per lane) from the striped layout (word 4t+q of lane l = elements
+// 1024t + 256q + 4l ..+3) to the operand layout (word 4t+q of lane (c, h) = positions
+// 16h + 4q ..+3 of row 32t + c), through the wave's LDS rows (36-dword row stride keeps the
+// 128-bit writes and reads free of bank conflicts).
+__device__ __forceinline__ void to_operand_layout(v4u (&raw)[8], uint32_t *rows, int lane) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+        *reinterpret_cast<v4u *>(rows + (8 * i + (lane >> 3)) * kRowStride + kRowData + 4 * (lane & 7)) = raw[i];
+    wave_lds_sync();
+    const int c = lane & 31, h = lane >> 5;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            raw[4 * t + q] = *reinterpret_cast<const v4u *>(rows + (32 * t + c) * kRowStride + kRowData + 16 * h + 4 * q);
+    wave_lds_sync();
 }
 
 // 128 bits = 16 / sizeof(T) consecutive elements starting at element e0 (a multiple
 // of 16 bytes); elements at or beyond n read as zero.  The aligned 16-byte block that
 // holds the last element is read whole (it cannot straddle a page) and masked.
 template <typename T> __device__ __forceinline__ v4u load128(const T *x, uint64_t e0, uint64_t n, bool full) {
-    if (full) return *reinterpret_cast<const v4u *>(x + e0);
+    // streamed once: non-temporal, so that the inputs do not push the gather vector (spmv)
+    // and the descriptors out of L2
+    if (full) return __builtin_nontemporal_load(reinterpret_cast<const v4u *>(x + e0));
     v4u w = {0, 0, 0, 0};
     if (e0 < n) {
-        w = *reinterpret_cast<const v4u *>(x + e0);
+        w = __builtin_nontemporal_load(reinterpret_cast<const v4u *>(x + e0));
         const uint64_t valid_bytes = (n - e0) * sizeof(T);
 #pragma unroll
         for (int d = 0; d < 4; ++d) {
@@ -553,12 +576,9 @@ __global__ __launch_bounds__(kThreads, 4) void seg_kernel(Params P) {
     for (int c = 0; c < kCpw; ++c) {
         const uint64_t cb = wave_base + (uint64_t)c * kChunkElems;
         F[c] = 0;
-        if constexpr (kOp != kSpmv) {
-            const uint64_t rs = cb + 32u * lane;
-            if (rs < n) F[c] = P.fw[rs >> 5];
-        } else {
-            load_raw<TInt, kMfma>(P.col, cb, n, lane, rawc[c]);
-        }
+        const uint64_t rs = cb + 32u * lane;
+        if (rs < n) F[c] = __builtin_nontemporal_load(P.fw + (rs >> 5));
+        if constexpr (kOp == kSpmv) load_raw<TInt, kMfma>(P.col, cb, n, lane, rawc[c]);
         load_raw<TT, kMfma>((const In *)P.x, cb, n, lane, raw[c]);
     }
 
@@ -579,22 +599,9 @@ __global__ __launch_bounds__(kThreads, 4) void seg_kernel(Params P) {
     for (int c = 0; c < kCpw; ++c) {
         const uint64_t cb = wave_base + (uint64_t)c * kChunkElems;
         const uint64_t row_start = cb + 32u * lane;  // first element of the row this lane owns
-        // ---- flags of my row (one 32-bit word = one row) ----
+        // ---- flags of my row (one 32-bit word = one row); bits beyond n do not count ----
+        if (row_start + 32 > n) F[0] = row_start < n ? (F[0] & ((1u << (uint32_t)(n - row_start)) - 1u)) : 0u;
         if constexpr (kOp == kSpmv) {
-            // f(e) = [e == 0 or row(e) != row(e-1)], 64 elements per ballot
-            uint32_t Fc = 0;
-            int prev_last = cb > 0 && cb - 1 < n ? P.row[cb - 1] : -1;
-            for (int j = 0; j < 32; ++j) {
-                const uint64_t e = cb + 64u * j + lane;
-                const int r = e < n ? P.row[e] : 0;
-                int rp = __shfl_up(r, 1);
-                if (lane == 0) rp = prev_last;
-                const uint64_t m = __ballot(e < n && (e == 0 || r != rp));
-                if (lane == 2 * j) Fc = (uint32_t)m;
-                if (lane == 2 * j + 1) Fc = (uint32_t)(m >> 32);
-                prev_last = __shfl(r, 63);
-            }
-            F[0] = Fc;
             // product vector p(i) = val(i) * x(col(i)), in the layout the values were loaded in
 #pragma unroll
             for (int t = 0; t < 2; ++t)
@@ -608,14 +615,13 @@ __global__ __launch_bounds__(kThreads, 4) void seg_kernel(Params P) {
                         raw[0][t * K + i][k] = to_bits(p);
                     }
                 }
-        } else if (row_start + 32 > n) {
-            F[0] = row_start < n ? (F[0] & ((1u << (uint32_t)(n - row_start)) - 1u)) : 0u;
         }
 
         // ---- steps 1-4 for the aggregate of my row: last element after the revert, any flag ----
         const uint32_t has_flag = F[0] != 0;
         A agg_v;
         if constexpr (kMfma) {
+            if constexpr (K == 4) to_operand_layout(raw[0], rows, lane);
             agg_v = RowAgg<TT>::run(raw[0], F[0], lane);
         } else {
 #pragma unroll
@@ -778,7 +784,7 @@ __global__ __launch_bounds__(kThreads, 4) void seg_kernel(Params P) {
                     if (lane == 63) {
                         const uint64_t en = cb + kChunkElems;
                         next0 = 0;
-                        if (en < n) next0 = kOp == kSpmv ? (P.row[en] != P.row[en - 1]) : (P.fw[en >> 5] & 1u);
+                        if (en < n) next0 = P.fw[en >> 5] & 1u;
                     }
                     uint32_t E = (F[0] >> 1) | (next0 << 31);
                     if (row_start < n) {
@@ -902,6 +908,21 @@ __global__ __launch_bounds__(256) void pack_flags_kernel(const uint8_t *f, uint6
     }
 }
 
+// Segment-start flags of a row-sorted COO matrix, f(e) = [e == 0 or row(e) != row(e-1)],
+// bit-packed: a wave turns 64 consecutive entries into two words with one ballot.
+__global__ __launch_bounds__(256) void row_flags_kernel(const int32_t *row, uint64_t nnz, uint32_t *words) {
+    const int lane = threadIdx.x & 63;
+    const uint64_t wave0 = ((uint64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * 1024;  // 16 ballots per wave
+#pragma unroll 4
+    for (int j = 0; j < 16; ++j) {
+        const uint64_t e = wave0 + 64u * j + lane;
+        bool f = false;
+        if (e < nnz) f = e == 0 || row[e] != row[e - 1];
+        const uint64_t m = __ballot(f);
+        if (lane == 0 && wave0 + 64u * j < nnz) *reinterpret_cast<uint64_t *>(words + ((wave0 + 64u * j) >> 5)) = m;
+    }
+}
+
 // Streaming reference: 128-bit non-temporal reads and writes, kIn input chunks and kOut
 // output chunks per thread, both striped across the workgroup; one workgroup per 256
 // units (measured faster than a persistent grid-stride loop on this chip).
@@ -966,7 +987,7 @@ WsLayout ws_layout(mmv_op op, mmv_dtype dt, mmv_flag_fmt ff, uint64_t n) {
     L.desc_c = off;
     if (op == MMV_OP_SEGSUM) off += round256(t * 8);
     L.packed = off;
-    if (op != MMV_OP_SPMV_COO && ff == MMV_FLAGS_U8) off += round256(((n + 31) / 32) * 4);
+    if (op == MMV_OP_SPMV_COO || ff == MMV_FLAGS_U8) off += round256(((n + 63) / 64) * 8);
     L.total = off;
     return L;
 }
@@ -1132,9 +1153,14 @@ mmv_status mmv_spmv_coo(uint64_t n_rows, uint64_t n_cols, uint64_t nnz, const in
     P.desc_v = (uint64_t *)(ws + L.desc_v);
     P.desc_c = nullptr;
     P.num_tiles = (uint32_t)tiles_for(nnz, MMV_OP_SPMV_COO, MMV_F32_F32);
-    const uint64_t zero_words = L.total / 4;
+    P.fw = (const uint32_t *)(ws + L.packed);
+    const uint64_t zero_words = L.packed / 4;  // header + descriptors; the flag words are all written below
     fill_zero_kernel<<<grid_for(zero_words > n_rows ? zero_words : n_rows), 256, 0, s>>>((uint32_t *)ws, zero_words,
                                                                                       (uint32_t *)d_y, n_rows);
+    if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
+    const uint64_t flag_blocks = (nnz + 4095) / 4096;
+    if (flag_blocks > 0x7fffffffull) return MMV_ERR_INVALID_ARG;
+    row_flags_kernel<<<(unsigned)flag_blocks, 256, 0, s>>>(d_row, nnz, (uint32_t *)(ws + L.packed));
     if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
     return launch_seg<TSpmv, kSpmv>(P, v, s) == hipSuccess ? MMV_OK : MMV_ERR_HIP;
 }
