@@ -30,7 +30,16 @@ namespace {
 
 // Tunables (the defaults are the measured best on MI355X; -D overrides are for experiments).
 #ifndef MMV_WAVES
-#define MMV_WAVES 8      // waves per workgroup
+#define MMV_WAVES 8      // waves per workgroup (int8)
+#endif
+#ifndef MMV_WAVES_F16
+#define MMV_WAVES_F16 8
+#endif
+#ifndef MMV_WAVES_F32
+#define MMV_WAVES_F32 8
+#endif
+#ifndef MMV_WAVES_SPMV
+#define MMV_WAVES_SPMV 8
 #endif
 #ifndef MMV_CPW_F16
 #define MMV_CPW_F16 2    // most chunks per wave, 16-bit inputs (4 spills registers)
@@ -38,11 +47,13 @@ namespace {
 #ifndef MMV_CPW_F32
 #define MMV_CPW_F32 1    // most chunks per wave, fp32 inputs (2 spills registers)
 #endif
-#ifndef MMV_MIN_TILES
-#define MMV_MIN_TILES 1024  // shrink the tiles of short inputs until there are this many
+#ifndef MMV_CPW_SPMV
+#define MMV_CPW_SPMV 1
 #endif
-constexpr int kWaves = MMV_WAVES;
-constexpr int kThreads = kWaves * 64;
+#ifndef MMV_MIN_TILES
+#define MMV_MIN_TILES 512   // shrink the tiles of short inputs until there are this many (one per resident workgroup)
+#endif
+
 constexpr int kS = 32;                          // row length = MFMA tile edge
 constexpr int kRowsPerChunk = 64;               // a chunk = 64 rows, one per lane = two 32x32 tiles
 constexpr int kChunkElems = kS * kRowsPerChunk; // 2048
@@ -168,6 +179,7 @@ struct TI8 {
     typedef uint32_t acc_t;  // int32 with wrap-around
     static constexpr int kEpl = 16;  // elements per 128-bit load
     static constexpr int kMaxCpw = 4;  // most chunks of 2048 elements a wave takes (raw inputs sit in registers)
+    static constexpr int kWaves = MMV_WAVES;
     static constexpr mmv_dtype kDtype = MMV_I8_I32;
     static __device__ __forceinline__ acc_t widen(in_t v) { return (acc_t)(int32_t)v; }
 };
@@ -176,6 +188,7 @@ struct TF16 {
     typedef float acc_t;
     static constexpr int kEpl = 8;
     static constexpr int kMaxCpw = MMV_CPW_F16;
+    static constexpr int kWaves = MMV_WAVES_F16;
     static constexpr mmv_dtype kDtype = MMV_F16_F32;
     static __device__ __forceinline__ acc_t widen(in_t v) { return (float)v; }
 };
@@ -184,6 +197,7 @@ struct TBF16 {
     typedef float acc_t;
     static constexpr int kEpl = 8;
     static constexpr int kMaxCpw = MMV_CPW_F16;
+    static constexpr int kWaves = MMV_WAVES_F16;
     static constexpr mmv_dtype kDtype = MMV_BF16_F32;
     static __device__ __forceinline__ acc_t widen(in_t v) { return (float)v; }
 };
@@ -192,11 +206,13 @@ struct TF32 {
     typedef float acc_t;
     static constexpr int kEpl = 4;
     static constexpr int kMaxCpw = MMV_CPW_F32;
+    static constexpr int kWaves = MMV_WAVES_F32;
     static constexpr mmv_dtype kDtype = MMV_F32_F32;
     static __device__ __forceinline__ acc_t widen(in_t v) { return v; }
 };
 struct TSpmv : TF32 {  // COO SpMV: values and column indices both sit in registers, so fewer chunks
-    static constexpr int kMaxCpw = 1;
+    static constexpr int kMaxCpw = MMV_CPW_SPMV;
+    static constexpr int kWaves = MMV_WAVES_SPMV;
 };
 struct TInt {  // column indices of the COO matrix, loaded in the same layout as its values
     typedef int32_t in_t;
@@ -339,17 +355,45 @@ template <> struct SpecMfma<TBF16> {
 };
 
 template <> struct SpecMfma<TF32> {
-    // sixteen K-steps of 2: in step 4 q + i half h supplies position 16 h + 4 q + i
+    // fp32 through the bf16 matrix pipe, exactly: every value is split into three bf16 pieces
+    // (8 + 8 + 8 significand bits, x = hi + mid + lo with no rounding), the pieces are
+    // multiplied by the 0/1 matrix (exact products) and accumulated in fp32.  Six
+    // 32x32x16 instructions of 8 passes instead of sixteen 32x32x2 fp32 ones of 16 passes.
+    // In K-step ks half h supplies positions 16 h + 8 ks .. + 7 (the lane's own words 2 ks, 2 ks + 1).
     static __device__ __forceinline__ void run(const v4u *raw, int lane, float (&acc)[16]) {
         const int c = lane & 31, h = lane >> 5;
-        v16f r = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+        uint32_t hi[8], mid[8], lo[8];  // packed pairs of consecutive positions
 #pragma unroll
         for (int q = 0; q < 4; ++q)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const float a = (16 * h + 4 * q + i <= c) ? 1.0f : 0.0f;
-                r = __builtin_amdgcn_mfma_f32_32x32x2f32(a, from_bits<float>(raw[q][i]), r, 0, 0, 0);
+            for (int pr = 0; pr < 2; ++pr) {
+                uint32_t ph[2], pm[2], pl[2];
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    const uint32_t xb = raw[q][2 * pr + e];
+                    ph[e] = xb & 0xFFFF0000u;
+                    const float r1 = from_bits<float>(xb) - from_bits<float>(ph[e]);
+                    pm[e] = to_bits(r1) & 0xFFFF0000u;
+                    pl[e] = to_bits(r1 - from_bits<float>(pm[e]));  // at most 8 significant bits left
+                }
+                hi[2 * q + pr] = __builtin_amdgcn_perm(ph[1], ph[0], 0x07060302u);
+                mid[2 * q + pr] = __builtin_amdgcn_perm(pm[1], pm[0], 0x07060302u);
+                lo[2 * q + pr] = __builtin_amdgcn_perm(pl[1], pl[0], 0x07060302u);
             }
+        v16f r = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            v8s a;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) a[j] = (16 * h + 8 * ks + j <= c) ? (short)0x3F80 : (short)0;  // bf16 1.0
+            const v8bf ab = __builtin_bit_cast(v8bf, a);
+            const v4u wl = {lo[4 * ks], lo[4 * ks + 1], lo[4 * ks + 2], lo[4 * ks + 3]};
+            const v4u wm = {mid[4 * ks], mid[4 * ks + 1], mid[4 * ks + 2], mid[4 * ks + 3]};
+            const v4u wh = {hi[4 * ks], hi[4 * ks + 1], hi[4 * ks + 2], hi[4 * ks + 3]};
+            r = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ab, __builtin_bit_cast(v8bf, wl), r, 0, 0, 0);
+            r = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ab, __builtin_bit_cast(v8bf, wm), r, 0, 0, 0);
+            r = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ab, __builtin_bit_cast(v8bf, wh), r, 0, 0, 0);
+        }
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[v] = r[v];
     }
@@ -538,9 +582,10 @@ template <int N, int M> __device__ __forceinline__ void rotate_rows(v4u (&a)[N][
 }
 
 template <typename TT, int kOp, bool kMfma, int kCpw>
-__global__ __launch_bounds__(kThreads, 4) void seg_kernel(Params P) {
+__global__ __launch_bounds__(TT::kWaves * 64, 4) void seg_kernel(Params P) {
     typedef typename TT::acc_t A;
     typedef typename TT::in_t In;
+    constexpr int kWaves = TT::kWaves;
     constexpr int K = 16 / TT::kEpl;             // 128-bit words per lane and 32x32 tile
     constexpr int kWaveSpan = kCpw * kChunkElems;
     constexpr int kTile = kWaves * kWaveSpan;
@@ -961,13 +1006,25 @@ inline int max_cpw(mmv_op op, mmv_dtype dt) {
     }
     return 1;
 }
+inline int waves_of(mmv_op op, mmv_dtype dt) {
+    if (op == MMV_OP_SPMV_COO) return TSpmv::kWaves;
+    switch (dt) {
+        case MMV_F32_F32: return TF32::kWaves;
+        case MMV_F16_F32: return TF16::kWaves;
+        case MMV_BF16_F32: return TBF16::kWaves;
+        case MMV_I8_I32: return TI8::kWaves;
+    }
+    return 1;
+}
 inline int choose_cpw(mmv_op op, mmv_dtype dt, uint64_t n) {
     int cpw = max_cpw(op, dt);
-    while (cpw > 1 && (n + (uint64_t)kWaves * cpw * kChunkElems - 1) / ((uint64_t)kWaves * cpw * kChunkElems) < kMinTiles)
-        cpw >>= 1;
+    const uint64_t wave_chunk = (uint64_t)waves_of(op, dt) * kChunkElems;
+    while (cpw > 1 && (n + wave_chunk * cpw - 1) / (wave_chunk * cpw) < kMinTiles) cpw >>= 1;
     return cpw;
 }
-inline uint32_t tile_elems(mmv_op op, mmv_dtype dt, uint64_t n) { return kWaves * choose_cpw(op, dt, n) * kChunkElems; }
+inline uint32_t tile_elems(mmv_op op, mmv_dtype dt, uint64_t n) {
+    return waves_of(op, dt) * choose_cpw(op, dt, n) * kChunkElems;
+}
 inline uint64_t tiles_for(uint64_t n, mmv_op op, mmv_dtype dt) {
     const uint32_t t = tile_elems(op, dt, n);
     return (n + t - 1) / t;
@@ -1004,11 +1061,11 @@ template <typename TT, int kOp, bool kMfma> hipError_t launch_variant(Params P, 
 #ifdef MMV_TRACE
     P.trace = g_trace;
 #endif
-    if (cpw == 1) seg_kernel<TT, kOp, kMfma, 1><<<P.num_tiles, kThreads, 0, s>>>(P);
+    if (cpw == 1) seg_kernel<TT, kOp, kMfma, 1><<<P.num_tiles, TT::kWaves * 64, 0, s>>>(P);
     if constexpr (TT::kMaxCpw >= 2)
-        if (cpw == 2) seg_kernel<TT, kOp, kMfma, 2><<<P.num_tiles, kThreads, 0, s>>>(P);
+        if (cpw == 2) seg_kernel<TT, kOp, kMfma, 2><<<P.num_tiles, TT::kWaves * 64, 0, s>>>(P);
     if constexpr (TT::kMaxCpw >= 4)
-        if (cpw == 4) seg_kernel<TT, kOp, kMfma, 4><<<P.num_tiles, kThreads, 0, s>>>(P);
+        if (cpw == 4) seg_kernel<TT, kOp, kMfma, 4><<<P.num_tiles, TT::kWaves * 64, 0, s>>>(P);
     return hipGetLastError();
 }
 

@@ -227,3 +227,28 @@ def test_workload5_stress_three_regimes(log2n):
     del xt
     worst = check_scan(z, x, f)
     print("workload 5 n=2^%d: worst |err|/max(A,1) = %.3g" % (log2n, worst))
+
+
+def test_more_than_2_32_elements():
+    """64-bit indexing: n just above 2^32 (int8 in, int32 out: 4 GiB + 16 GiB on the GPU)."""
+    n = (1 << 32) + 70_001
+    rng = np.random.default_rng(77)
+    x = np.empty(n, dtype=np.int8)
+    step = 1 << 28
+    for a in range(0, n, step):
+        x[a:min(n, a + step)] = rng.integers(-8, 9, size=min(n, a + step) - a, dtype=np.int8)
+    f = np.zeros(n, dtype=np.uint8)
+    f[rng.integers(0, n, size=n // 3000)] = 1
+    f[[0, (1 << 32) - 1, (1 << 32), (1 << 32) + 1]] = 1
+    xt, ft = dev(x), packed_dev(f)
+    z = B.mmv_segscan(xt, ft, n=n)
+    torch.cuda.synchronize()
+    ref = oracle.segscan(x, f)
+    got = z.cpu().numpy()
+    del z
+    for a in range(0, n, step):
+        assert np.array_equal(got[a:a + step], ref[a:a + step]), a
+    out, nseg = B.mmv_segsum(xt, ft, n=n, out=torch.empty(int(f.sum()) + 8, dtype=torch.int32, device="cuda"))
+    sref = oracle.segsum(x, f)
+    assert int(nseg.item()) == len(sref)
+    assert np.array_equal(out.cpu().numpy()[:len(sref)], sref)
