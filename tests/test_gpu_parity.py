@@ -252,3 +252,62 @@ def test_more_than_2_32_elements():
     sref = oracle.segsum(x, f)
     assert int(nseg.item()) == len(sref)
     assert np.array_equal(out.cpu().numpy()[:len(sref)], sref)
+
+
+def test_two_streams_at_once_do_not_block_each_other():
+    """Two calls in flight on different streams, each with its own workspace: tiles are handed
+    out by ticket, so neither call can starve the other of a predecessor tile."""
+    x1, f1 = W.segscan_i8_uniform_len(1 << 24, seed=31)
+    x2, f2 = W.scan_sum_f32_bernoulli(1 << 23, p=1e-4, seed=32)
+    a = (dev(x1), packed_dev(f1), torch.empty(len(x1), dtype=torch.int32, device="cuda"),
+         B.new_workspace(B.MMV_OP_SEGSCAN, B.MMV_I8_I32, B.MMV_FLAGS_PACKED32, len(x1)))
+    b = (dev(x2), packed_dev(f2), torch.empty(len(x2), dtype=torch.float32, device="cuda"),
+         B.new_workspace(B.MMV_OP_SEGSCAN, B.MMV_F32_F32, B.MMV_FLAGS_PACKED32, len(x2)))
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    for _ in range(5):
+        B.mmv_segscan(a[0], a[1], z=a[2], ws=a[3], stream=s1)
+        B.mmv_segscan(b[0], b[1], z=b[2], ws=b[3], stream=s2)
+    torch.cuda.synchronize()
+    assert B.mmv_workspace_status(a[3]) == 0 and B.mmv_workspace_status(b[3]) == 0
+    check_scan(a[2].cpu().numpy(), x1, f1)
+    check_scan(b[2].cpu().numpy(), x2, f2)
+
+
+def test_hip_graph_replay():
+    """The calls enqueue only kernels (the workspace reset is a fill kernel), so they can be
+    captured; every replay must give the eager result."""
+    x, f = W.segscan_i8_uniform_len(1 << 22, seed=41)
+    xt, ft = dev(x), packed_dev(f)
+    n = len(x)
+    z = torch.zeros(n, dtype=torch.int32, device="cuda")
+    ws = B.new_workspace(B.MMV_OP_SEGSCAN, B.MMV_I8_I32, B.MMV_FLAGS_PACKED32, n)
+    ref = oracle.segscan(x, f)
+    B.mmv_segscan(xt, ft, z=z, ws=ws)                      # eager
+    assert np.array_equal(z.cpu().numpy(), ref)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        B.mmv_segscan(xt, ft, z=z, ws=ws)
+    for rep in range(4):
+        z.zero_()                                          # the program's own eager work in between
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(z.cpu().numpy(), ref), rep
+        assert B.mmv_workspace_status(ws) == 0
+
+
+def test_status_codes_on_device_pointers():
+    x = torch.zeros(1000, dtype=torch.int8, device="cuda")
+    fl = torch.zeros(32, dtype=torch.int32, device="cuda")
+    z = torch.zeros(1000, dtype=torch.int32, device="cuda")
+    small = torch.zeros(256, dtype=torch.uint8, device="cuda")
+    lib = B.load()
+    st = lib.mmv_segscan(x.data_ptr(), fl.data_ptr(), 1000, z.data_ptr(), B.MMV_I8_I32, B.MMV_FLAGS_PACKED32, 0,
+                         small.data_ptr(), 256, None)
+    assert st == 4                                          # workspace too small
+    with pytest.raises(B.MmvError):
+        B.mmv_segscan(x, fl, z=z, ws=small)
+    st = lib.mmv_segscan(x.data_ptr() + 1, fl.data_ptr(), 999, z.data_ptr(), B.MMV_I8_I32, B.MMV_FLAGS_PACKED32, 0,
+                         small.data_ptr(), 256, None)
+    assert st == 1                                          # misaligned values
