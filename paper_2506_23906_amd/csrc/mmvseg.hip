@@ -51,7 +51,7 @@ namespace {
 #define MMV_CPW_SPMV 1
 #endif
 #ifndef MMV_MIN_TILES
-#define MMV_MIN_TILES 512   // shrink the tiles of short inputs until there are this many (one per resident workgroup)
+#define MMV_MIN_TILES 512   // workgroups resident at once: 2 per compute unit (LDS)
 #endif
 
 constexpr int kS = 32;                          // row length = MFMA tile edge
@@ -59,7 +59,6 @@ constexpr int kRowsPerChunk = 64;               // a chunk = 64 rows, one per la
 constexpr int kChunkElems = kS * kRowsPerChunk; // 2048
 constexpr int kRowStride = 36;                  // dwords per LDS row: 4 meta + 32 values
 constexpr int kSlotF = 0;                       // flag word of the row
-constexpr int kSlotE = 1;                       // segment-end mask of the row
 constexpr int kSlotNegCarry = 2;                // minus the carry into the row
 constexpr int kSlotZero = 3;                    // x-bar(-1) = 0
 constexpr int kRowData = 4;
@@ -100,6 +99,8 @@ struct Params {
     uint64_t *desc_v;       // value descriptors, one per tile
     uint64_t *desc_c;       // count descriptors (sum)
     uint32_t num_tiles;
+    uint32_t big_tiles;     // tiles [0, big_tiles) have the full number of chunks per wave ...
+    uint32_t tail_cpw;      // ... the rest have this many (shorter tiles at the end shorten the tail)
 #ifdef MMV_TRACE
     uint64_t *trace;        // 8 timestamps per tile (development builds only)
 #endif
@@ -581,17 +582,15 @@ template <int N, int M> __device__ __forceinline__ void rotate_rows(v4u (&a)[N][
     }
 }
 
-template <typename TT, int kOp, bool kMfma, int kCpw>
+template <typename TT, int kOp, bool kMfma>
 __global__ __launch_bounds__(TT::kWaves * 64, 4) void seg_kernel(Params P) {
     typedef typename TT::acc_t A;
     typedef typename TT::in_t In;
     constexpr int kWaves = TT::kWaves;
+    constexpr int kCpw = TT::kMaxCpw;            // most chunks a wave takes (register arrays)
     constexpr int K = 16 / TT::kEpl;             // 128-bit words per lane and 32x32 tile
-    constexpr int kWaveSpan = kCpw * kChunkElems;
-    constexpr int kTile = kWaves * kWaveSpan;
 
     __shared__ __attribute__((aligned(16))) uint32_t s_rows[kWaves][kRowsPerChunk * kRowStride];
-    __shared__ uint32_t s_cnt[kWaves * kRowsPerChunk];  // segment starts before each row (sum)
     __shared__ uint32_t s_wave_v[kWaves], s_wave_f[kWaves], s_wave_c[kWaves];
     __shared__ uint32_t s_tile, s_carry_v, s_carry_c, s_ready;
 
@@ -611,7 +610,14 @@ __global__ __launch_bounds__(TT::kWaves * 64, 4) void seg_kernel(Params P) {
     if (tid == 0 && P.trace) P.trace[(uint64_t)tile * 8] = t_begin;
 #endif
     MMV_STAMP(1);
-    const uint64_t wave_base = (uint64_t)tile * kTile + (uint64_t)wave * kWaveSpan;
+    // tiles at the end of the vector are shorter (fewer chunks per wave)
+    const bool big_tile = tile < P.big_tiles;
+    const int cpw_t = big_tile ? kCpw : (int)P.tail_cpw;
+    const uint64_t tile_base =
+        big_tile ? (uint64_t)tile * (kWaves * kCpw * kChunkElems)
+                 : (uint64_t)P.big_tiles * (kWaves * kCpw * kChunkElems) +
+                       (uint64_t)(tile - P.big_tiles) * ((uint64_t)kWaves * P.tail_cpw * kChunkElems);
+    const uint64_t wave_base = tile_base + (uint64_t)wave * cpw_t * kChunkElems;
 
     // ---- all inputs of my span: flag word of my row and raw values (and columns) per chunk ----
     uint32_t F[kCpw];
@@ -621,10 +627,12 @@ __global__ __launch_bounds__(TT::kWaves * 64, 4) void seg_kernel(Params P) {
     for (int c = 0; c < kCpw; ++c) {
         const uint64_t cb = wave_base + (uint64_t)c * kChunkElems;
         F[c] = 0;
-        const uint64_t rs = cb + 32u * lane;
-        if (rs < n) F[c] = __builtin_nontemporal_load(P.fw + (rs >> 5));
-        if constexpr (kOp == kSpmv) load_raw<TInt, kMfma>(P.col, cb, n, lane, rawc[c]);
-        load_raw<TT, kMfma>((const In *)P.x, cb, n, lane, raw[c]);
+        if (c < cpw_t) {
+            const uint64_t rs = cb + 32u * lane;
+            if (rs < n) F[c] = __builtin_nontemporal_load(P.fw + (rs >> 5));
+            if constexpr (kOp == kSpmv) load_raw<TInt, kMfma>(P.col, cb, n, lane, rawc[c]);
+            load_raw<TT, kMfma>((const In *)P.x, cb, n, lane, raw[c]);
+        }
     }
 
     // per chunk: exclusive segmented prefix of my row inside the chunk, and of the chunk inside
@@ -642,6 +650,7 @@ __global__ __launch_bounds__(TT::kWaves * 64, 4) void seg_kernel(Params P) {
     // ================= phase A: aggregates =================
 #pragma unroll 1
     for (int c = 0; c < kCpw; ++c) {
+      if (c < cpw_t) {
         const uint64_t cb = wave_base + (uint64_t)c * kChunkElems;
         const uint64_t row_start = cb + 32u * lane;  // first element of the row this lane owns
         // ---- flags of my row (one 32-bit word = one row); bits beyond n do not count ----
@@ -713,6 +722,7 @@ __global__ __launch_bounds__(TT::kWaves * 64, 4) void seg_kernel(Params P) {
         run_v = ca_f ? ca_v : run_v + ca_v;
         run_f |= ca_f;
         if (kOp == kSum) run_c += __shfl(inc_c, 63);
+      }
         rotate(F);
         rotate_rows(raw);
         if constexpr (kOp == kSpmv) rotate_rows(rawc);
@@ -803,7 +813,7 @@ __global__ __launch_bounds__(TT::kWaves * 64, 4) void seg_kernel(Params P) {
             // a chunk is "open" when no flag of the tile precedes it; the segmented sum treats
             // every chunk as open because all its output indices wait for the count carry
             const bool chunk_open = kOp == kSum || !(wex_f || __builtin_amdgcn_readfirstlane(pre_f[0]));
-            if (chunk_open == (pass == 1)) {
+            if (c < cpw_t && chunk_open == (pass == 1)) {
                 const uint64_t cb = wave_base + (uint64_t)c * kChunkElems;
                 const bool chunk_full = cb + kChunkElems <= n;
                 const uint64_t row_start = cb + 32u * lane;
@@ -817,14 +827,55 @@ __global__ __launch_bounds__(TT::kWaves * 64, 4) void seg_kernel(Params P) {
                         spec_shuffle_tile<TT>(raw[0] + t * K, lane, rows, t);
                     }
                 }
-                // ---- step 6: carry into my row; stored negated so that the revert subtracts it ----
+                // ---- step 6: carry into my row ----
                 const A carry = ex_f[0] ? ex_v[0] : (pre_f[0] ? pre_v[0] + ex_v[0] : (span_carry + pre_v[0]) + ex_v[0]);
-                rows[lane * kRowStride + kSlotZero] = 0;
-                rows[lane * kRowStride + kSlotF] = F[0];
-                rows[lane * kRowStride + kSlotNegCarry] = to_bits(A(0) - carry);
-                if (kOp != kScan) {
-                    // segment-end mask of my row: bit p set iff position p + 1 starts a segment or
-                    // p is the last element of the vector
+                if constexpr (kOp == kScan) {
+                    // stored negated in the slot before x-bar(-1), so that the revert subtracts it
+                    rows[lane * kRowStride + kSlotZero] = 0;
+                    rows[lane * kRowStride + kSlotF] = F[0];
+                    rows[lane * kRowStride + kSlotNegCarry] = to_bits(A(0) - carry);
+                    const uint64_t row_any = __ballot(F[0] != 0);
+                    wave_lds_sync();
+
+                    // ---- steps 2 + 6 on every element, then store; a lane owns 4 consecutive positions ----
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        const int R = 8 * j + (lane >> 3), p0 = 4 * (lane & 7);
+                        const uint32_t *rp = rows + R * kRowStride;
+                        const v4u xb = *reinterpret_cast<const v4u *>(rp + kRowData + p0);
+                        A o[4];
+                        if (((row_any >> (8 * j)) & 0xFFull) == 0) {
+                            // none of these eight rows has a flag: the speculation stands, only the carry is added
+                            const A nc = from_bits<A>(rp[kSlotNegCarry]);
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) o[i] = from_bits<A>(xb[i]) - nc;
+                        } else {
+                            const uint32_t Fr = rp[kSlotF];
+                            const uint32_t m = Fr & ((2u << p0) - 1u);  // flags at or before my first position
+                            const int slot = m ? kSlotZero + (31 - __clz(m)) : kSlotNegCarry;
+                            A b = from_bits<A>(rp[slot]);
+                            o[0] = from_bits<A>(xb[0]) - b;
+#pragma unroll
+                            for (int i = 1; i < 4; ++i) {
+                                if ((Fr >> (p0 + i)) & 1u) b = from_bits<A>(xb[i - 1]);
+                                o[i] = from_bits<A>(xb[i]) - b;
+                            }
+                        }
+                        const uint64_t e0 = cb + 256u * j + 4u * lane;
+                        A *z = (A *)P.z;
+                        if (chunk_full) {
+                            v4u w = {to_bits(o[0]), to_bits(o[1]), to_bits(o[2]), to_bits(o[3])};
+                            __builtin_nontemporal_store(w, reinterpret_cast<v4u *>(z + e0));
+                        } else {
+#pragma unroll
+                            for (int i = 0; i < 4; ++i)
+                                if (e0 + i < n) z[e0 + i] = o[i];
+                        }
+                    }
+                } else {
+                    // ---- sum, spmv: only the segment ends produce output; the lane that owns a row
+                    // walks the ends of its row (steps 2 + 6 for those positions only) ----
+                    // end mask: bit p set iff position p + 1 starts a segment or p is the last element
                     uint32_t next0 = __shfl_down(F[0], 1) & 1u;
                     if (lane == 63) {
                         const uint64_t en = cb + kChunkElems;
@@ -840,66 +891,26 @@ __global__ __launch_bounds__(TT::kWaves * 64, 4) void seg_kernel(Params P) {
                     } else {
                         E = 0;
                     }
-                    rows[lane * kRowStride + kSlotE] = E;
-                    if (kOp == kSum) s_cnt[wave * kRowsPerChunk + lane] = count_carry + wex_c + ex_c[0];
-                }
-                const uint64_t row_any = __ballot(F[0] != 0);
-                wave_lds_sync();
-
-                // ---- steps 2 + 6 on every element, then store; a lane owns 4 consecutive positions ----
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const int R = 8 * j + (lane >> 3), p0 = 4 * (lane & 7);
-                    const uint32_t *rp = rows + R * kRowStride;
-                    const v4u xb = *reinterpret_cast<const v4u *>(rp + kRowData + p0);
-                    A o[4];
-                    uint32_t Fr = 0;
-                    if (((row_any >> (8 * j)) & 0xFFull) == 0) {
-                        // none of these eight rows has a flag: the speculation stands, only the carry is added
-                        const A nc = from_bits<A>(rp[kSlotNegCarry]);
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) o[i] = from_bits<A>(xb[i]) - nc;
-                    } else {
-                        Fr = rp[kSlotF];
-                        const uint32_t m = Fr & ((2u << p0) - 1u);  // flags at or before my first position
-                        const int slot = m ? kSlotZero + (31 - __clz(m)) : kSlotNegCarry;
-                        A b = from_bits<A>(rp[slot]);
-                        o[0] = from_bits<A>(xb[0]) - b;
-#pragma unroll
-                        for (int i = 1; i < 4; ++i) {
-                            if ((Fr >> (p0 + i)) & 1u) b = from_bits<A>(xb[i - 1]);
-                            o[i] = from_bits<A>(xb[i]) - b;
-                        }
-                    }
-                    const uint64_t e0 = cb + 256u * j + 4u * lane;
-                    if (kOp == kScan) {
-                        A *z = (A *)P.z;
-                        if (chunk_full) {
-                            v4u w = {to_bits(o[0]), to_bits(o[1]), to_bits(o[2]), to_bits(o[3])};
-                            __builtin_nontemporal_store(w, reinterpret_cast<v4u *>(z + e0));
+                    wave_lds_sync();
+                    const uint32_t *rp = rows + lane * kRowStride + kRowData;
+                    const uint32_t Fc = row_start == 0 ? (F[0] & ~1u) : F[0];  // position 0 is not counted
+                    const uint64_t count_base = (uint64_t)count_carry + wex_c + ex_c[0];
+                    while (E) {
+                        const int e = __builtin_ctz(E);
+                        E &= E - 1u;
+                        const uint32_t m = F[0] & ((2u << e) - 1u);  // flags at or before the end
+                        A v = from_bits<A>(rp[e]);
+                        if (m) {
+                            const int st = 31 - __clz(m);
+                            if (st > 0) v -= from_bits<A>(rp[st - 1]);   // REVSPEC: x-bar(e) - x-bar(start - 1)
                         } else {
-#pragma unroll
-                            for (int i = 0; i < 4; ++i)
-                                if (e0 + i < n) z[e0 + i] = o[i];
+                            v += carry;                                  // the segment began before this row
                         }
-                    } else {
-                        const uint32_t ends = (rp[kSlotE] >> p0) & 0xFu;
-                        if (ends) {
-                            if (kOp == kSum) {
-                                if (!Fr) Fr = rp[kSlotF];
-                                const uint32_t Frc = (cb == 0 && R == 0) ? (Fr & ~1u) : Fr;
-                                const uint32_t base = s_cnt[wave * kRowsPerChunk + R];
-#pragma unroll
-                                for (int i = 0; i < 4; ++i)
-                                    if ((ends >> i) & 1u) {
-                                        const uint64_t k = (uint64_t)base + __popc(Frc & ((2u << (p0 + i)) - 1u));
-                                        if (k < P.out_cap) ((A *)P.out)[k] = o[i];
-                                    }
-                            } else {
-#pragma unroll
-                                for (int i = 0; i < 4; ++i)
-                                    if ((ends >> i) & 1u) P.y[P.row[e0 + i]] = from_bits<float>(to_bits(o[i]));
-                            }
+                        if (kOp == kSum) {
+                            const uint64_t k = count_base + __popc(Fc & ((2u << e) - 1u));
+                            if (k < P.out_cap) ((A *)P.out)[k] = v;
+                        } else {
+                            P.y[P.row[row_start + e]] = from_bits<float>(to_bits(v));
                         }
                     }
                 }
@@ -992,10 +1003,16 @@ __global__ __launch_bounds__(256) void stream_copy_kernel(const v4u *src, v4u *d
 // ---- host side -------------------------------------------------------------------------------------------------
 
 inline size_t round256(size_t b) { return (b + 255) & ~(size_t)255; }
-// Chunks of 2048 elements per wave.  A tile costs one ticket (about 11 ns, serialised), so
-// tiles are as large as the registers allow, but not so large that a short input leaves
-// compute units without a tile.
-constexpr uint64_t kMinTiles = MMV_MIN_TILES;
+// Tile plan.  A tile costs one ticket (about 11 ns, serialised), so tiles are as large as the
+// registers allow: kMaxCpw chunks of 2048 elements per wave.  The workgroups of the last round
+// would leave most of the chip idle while they finish, so the end of the vector is cut into
+// shorter tiles (one chunk per wave); inputs that fit into one round of resident workgroups
+// get equal tiles of just the size that gives every workgroup one.
+constexpr uint64_t kResident = MMV_MIN_TILES;   // workgroups resident at once (2 per compute unit)
+#ifndef MMV_TAIL_ROUNDS
+#define MMV_TAIL_ROUNDS 1
+#endif
+constexpr uint64_t kTailTiles = MMV_TAIL_ROUNDS * kResident;  // short tiles at the end of a long vector
 inline int max_cpw(mmv_op op, mmv_dtype dt) {
     if (op == MMV_OP_SPMV_COO) return TSpmv::kMaxCpw;
     switch (dt) {
@@ -1016,19 +1033,34 @@ inline int waves_of(mmv_op op, mmv_dtype dt) {
     }
     return 1;
 }
-inline int choose_cpw(mmv_op op, mmv_dtype dt, uint64_t n) {
-    int cpw = max_cpw(op, dt);
-    const uint64_t wave_chunk = (uint64_t)waves_of(op, dt) * kChunkElems;
-    while (cpw > 1 && (n + wave_chunk * cpw - 1) / (wave_chunk * cpw) < kMinTiles) cpw >>= 1;
-    return cpw;
+struct TilePlan {
+    uint64_t big_tiles, tail_tiles;
+    uint32_t big_elems, tail_cpw, tail_elems;
+    uint64_t tiles() const { return big_tiles + tail_tiles; }
+};
+inline TilePlan tile_plan(mmv_op op, mmv_dtype dt, uint64_t n) {
+    TilePlan p;
+    const uint64_t unit = (uint64_t)waves_of(op, dt) * kChunkElems;  // one chunk per wave
+    const int cpw = max_cpw(op, dt);
+    p.big_elems = (uint32_t)(unit * cpw);
+    if (n <= kResident * p.big_elems) {
+        // one round: equal tiles, as small as gives every resident workgroup at most one
+        uint64_t c = (n + kResident * unit - 1) / (kResident * unit);
+        if (c < 1) c = 1;
+        if (c > (uint64_t)cpw) c = cpw;
+        p.tail_cpw = (uint32_t)c;
+        p.big_tiles = 0;
+    } else {
+        p.tail_cpw = 1;
+        const uint64_t tail = kTailTiles * unit < n ? kTailTiles * unit : n;
+        p.big_tiles = (n - tail) / p.big_elems;
+    }
+    p.tail_elems = (uint32_t)(unit * p.tail_cpw);
+    const uint64_t rest = n - p.big_tiles * p.big_elems;
+    p.tail_tiles = (rest + p.tail_elems - 1) / p.tail_elems;
+    return p;
 }
-inline uint32_t tile_elems(mmv_op op, mmv_dtype dt, uint64_t n) {
-    return waves_of(op, dt) * choose_cpw(op, dt, n) * kChunkElems;
-}
-inline uint64_t tiles_for(uint64_t n, mmv_op op, mmv_dtype dt) {
-    const uint32_t t = tile_elems(op, dt, n);
-    return (n + t - 1) / t;
-}
+inline uint64_t tiles_for(uint64_t n, mmv_op op, mmv_dtype dt) { return tile_plan(op, dt, n).tiles(); }
 inline bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
 
 struct WsLayout {
@@ -1057,26 +1089,26 @@ uint64_t *g_trace = nullptr;
 // right after the main kernel of a call made by this host thread.
 thread_local hipEvent_t tl_ev_start = nullptr, tl_ev_stop = nullptr;
 
-template <typename TT, int kOp, bool kMfma> hipError_t launch_variant(Params P, int cpw, hipStream_t s) {
+template <typename TT, int kOp, bool kMfma> hipError_t launch_variant(Params P, hipStream_t s) {
 #ifdef MMV_TRACE
     P.trace = g_trace;
 #endif
-    if (cpw == 1) seg_kernel<TT, kOp, kMfma, 1><<<P.num_tiles, TT::kWaves * 64, 0, s>>>(P);
-    if constexpr (TT::kMaxCpw >= 2)
-        if (cpw == 2) seg_kernel<TT, kOp, kMfma, 2><<<P.num_tiles, TT::kWaves * 64, 0, s>>>(P);
-    if constexpr (TT::kMaxCpw >= 4)
-        if (cpw == 4) seg_kernel<TT, kOp, kMfma, 4><<<P.num_tiles, TT::kWaves * 64, 0, s>>>(P);
+    seg_kernel<TT, kOp, kMfma><<<P.num_tiles, TT::kWaves * 64, 0, s>>>(P);
     return hipGetLastError();
 }
 
 template <typename TT, int kOp>
-hipError_t launch_seg(const Params &P, mmv_variant v, hipStream_t s) {
+hipError_t launch_seg(Params P, mmv_variant v, hipStream_t s) {
+    const TilePlan plan = tile_plan((mmv_op)kOp, TT::kDtype, P.n);
+    if (plan.tiles() > 0x7fffffffull) return hipErrorInvalidValue;
+    P.num_tiles = (uint32_t)plan.tiles();
+    P.big_tiles = (uint32_t)plan.big_tiles;
+    P.tail_cpw = plan.tail_cpw;
     if (tl_ev_start && hipEventRecord(tl_ev_start, s) != hipSuccess) return hipErrorUnknown;
-    const int cpw = choose_cpw((mmv_op)kOp, TT::kDtype, P.n);
     if (v == MMV_VARIANT_MFMA) {
-        if (launch_variant<TT, kOp, true>(P, cpw, s) != hipSuccess) return hipErrorUnknown;
+        if (launch_variant<TT, kOp, true>(P, s) != hipSuccess) return hipErrorUnknown;
     } else {
-        if (launch_variant<TT, kOp, false>(P, cpw, s) != hipSuccess) return hipErrorUnknown;
+        if (launch_variant<TT, kOp, false>(P, s) != hipSuccess) return hipErrorUnknown;
     }
     const hipError_t e = hipGetLastError();
     if (tl_ev_stop && hipEventRecord(tl_ev_stop, s) != hipSuccess) return hipErrorUnknown;
@@ -1285,7 +1317,8 @@ const char *mmv_status_string(mmv_status s) {
 
 uint32_t mmv_tile_elems(mmv_op op, mmv_dtype dt, uint64_t n) {
     if ((int)op < 0 || (int)op > 2 || !valid_dtype(dt)) return 0;
-    return tile_elems(op, op == MMV_OP_SPMV_COO ? MMV_F32_F32 : dt, n);
+    const TilePlan p = tile_plan(op, op == MMV_OP_SPMV_COO ? MMV_F32_F32 : dt, n);
+    return p.big_tiles ? p.big_elems : p.tail_elems;
 }
 
 }  // extern "C"
