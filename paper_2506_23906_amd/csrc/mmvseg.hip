@@ -237,23 +237,23 @@ struct TInt {  // column indices of the COO matrix, loaded in the same layout as
 //
 // Shuffle layout (ablation): lane l holds kEpl consecutive elements, striped.
 
-// fp32 is loaded striped in both variants (128 B rows would otherwise make every
-// instruction touch 32 cache lines for 1 KiB) and the matrix-core variant moves it into
-// the operand layout through LDS (to_operand_layout).
+// 16- and 32-bit values are loaded striped in both variants (rows of 64 or 128 bytes would
+// otherwise make every load instruction touch 32 cache lines for 1 KiB) and the matrix-core
+// variant moves them into the operand layout through LDS (to_operand_layout).
 template <typename TT, bool kMfma> __device__ __forceinline__ int raw_offset(int i, int lane) {
     constexpr int K = 16 / TT::kEpl;
-    if (kMfma && K < 4) {
-        const int c = lane & 31, h = lane >> 5;
-        return 32 * c + (K == 2 ? 16 * i + 8 * h : 16 * h);
-    }
+    if (kMfma && K == 1) return 32 * (lane & 31) + 16 * (lane >> 5);  // int8: 32-byte rows, already contiguous
     return (1024 / K) * i + TT::kEpl * lane;
 }
 
-// fp32 chunk (2 x 4 words per lane) from the striped layout (word 4t+q of lane l = elements
-// 1024t + 256q + 4l ..+3) to the operand layout (word 4t+q of lane (c, h) = positions
-// 16h + 4q ..+3 of row 32t + c), through the wave's LDS rows (36-dword row stride keeps the
-// 128-bit writes and reads free of bank conflicts).
-__device__ __forceinline__ void to_operand_layout(v4u (&raw)[8], uint32_t *rows, int lane) {
+// One chunk from the striped layout (word w of lane l = elements (2048 / W) w + kEpl l ..,
+// W = 2 K words per lane) to the operand layout, through the wave's LDS rows.
+//   fp32 (K = 4): word 4t+q of lane (c, h) = positions 16h + 4q .. +3 of row 32t + c
+//   16-bit (K = 2): word 2t+ks of lane (c, h) = positions 16ks + 8h .. +7 of row 32t + c
+// The padded row strides keep the 128-bit accesses (almost) free of bank conflicts.
+template <int K> __device__ __forceinline__ void to_operand_layout(v4u (&raw)[2 * K], uint32_t *rows, int lane);
+
+template <> __device__ __forceinline__ void to_operand_layout<4>(v4u (&raw)[8], uint32_t *rows, int lane) {
 #pragma unroll
     for (int i = 0; i < 8; ++i)
         *reinterpret_cast<v4u *>(rows + (8 * i + (lane >> 3)) * kRowStride + kRowData + 4 * (lane & 7)) = raw[i];
@@ -264,6 +264,21 @@ __device__ __forceinline__ void to_operand_layout(v4u (&raw)[8], uint32_t *rows,
 #pragma unroll
         for (int q = 0; q < 4; ++q)
             raw[4 * t + q] = *reinterpret_cast<const v4u *>(rows + (32 * t + c) * kRowStride + kRowData + 16 * h + 4 * q);
+    wave_lds_sync();
+}
+
+template <> __device__ __forceinline__ void to_operand_layout<2>(v4u (&raw)[4], uint32_t *rows, int lane) {
+    constexpr int kStride = 20;  // dwords per row of 32 halves (16) + padding
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        *reinterpret_cast<v4u *>(rows + (16 * i + (lane >> 2)) * kStride + 4 * (lane & 3)) = raw[i];
+    wave_lds_sync();
+    const int c = lane & 31, h = lane >> 5;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+            raw[2 * t + ks] = *reinterpret_cast<const v4u *>(rows + (32 * t + c) * kStride + 8 * ks + 4 * h);
     wave_lds_sync();
 }
 
@@ -675,7 +690,7 @@ __global__ __launch_bounds__(TT::kWaves * 64, 4) void seg_kernel(Params P) {
         const uint32_t has_flag = F[0] != 0;
         A agg_v;
         if constexpr (kMfma) {
-            if constexpr (K == 4) to_operand_layout(raw[0], rows, lane);
+            if constexpr (K > 1) to_operand_layout<K>(raw[0], rows, lane);
             agg_v = RowAgg<TT>::run(raw[0], F[0], lane);
         } else {
 #pragma unroll
