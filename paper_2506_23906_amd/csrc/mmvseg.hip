@@ -41,6 +41,9 @@ namespace {
 #ifndef MMV_WAVES_SPMV
 #define MMV_WAVES_SPMV 8
 #endif
+#ifndef MMV_CPW_I8
+#define MMV_CPW_I8 4     // most chunks per wave, int8 inputs (6 spills registers)
+#endif
 #ifndef MMV_CPW_F16
 #define MMV_CPW_F16 2    // most chunks per wave, 16-bit inputs (4 spills registers)
 #endif
@@ -144,6 +147,9 @@ template <typename T> __device__ __forceinline__ T wave_sum(T v) {
 // Sum of the payloads of the predecessor tiles back to (and including) the first
 // one whose descriptor says "prefix".  The whole wave polls 64 descriptors at a
 // time.  Tile -1 counts as prefix 0, so the loop always ends there at the latest.
+// (Polling 128 or 256 descriptors per round trip was measured 3-9 % slower on long
+// chains: the polls are served by the memory side and compete with the streams,
+// and in steady state the nearest "prefix" is within 64 tiles anyway.)
 template <typename T>
 __device__ T lookback(const uint64_t *desc, int tile, int lane, uint32_t *hdr) {
     T carry = T(0);
@@ -179,7 +185,7 @@ struct TI8 {
     typedef int8_t in_t;
     typedef uint32_t acc_t;  // int32 with wrap-around
     static constexpr int kEpl = 16;  // elements per 128-bit load
-    static constexpr int kMaxCpw = 4;  // most chunks of 2048 elements a wave takes (raw inputs sit in registers)
+    static constexpr int kMaxCpw = MMV_CPW_I8;  // most chunks of 2048 elements a wave takes (raw inputs sit in registers)
     static constexpr int kWaves = MMV_WAVES;
     static constexpr mmv_dtype kDtype = MMV_I8_I32;
     static __device__ __forceinline__ acc_t widen(in_t v) { return (acc_t)(int32_t)v; }
