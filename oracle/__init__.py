@@ -12,6 +12,10 @@ holds the paper's other routes to the same results (SCD, SSCR, the
 block-recursive algorithm, the REVSPEC lemma) in plain numpy / Python, used
 to pin the definitions against each other.
 
+The parallel primitives that Algorithms SCD and SSCR are composed of (SCAN,
+COMPRESS, DIFF, REVERT) and CSR SpMV have their plain definitions here too
+(pins: tests/test_oracle_primitives.py).
+
 Pins (tests/test_oracle_pins.py, tests/test_formulations.py): the worked
 example printed in Sec. 2, closed forms (all-ones values give segment lengths,
 arithmetic series), library special cases (numpy.cumsum, numpy.add.reduceat,
@@ -60,6 +64,24 @@ def _load():
         lib.oracle_segsum_f64.restype = u64
         lib.oracle_spmv_coo.argtypes = [u64, u64, u64, vp, vp, vp, vp, vp]
         lib.oracle_spmv_coo.restype = ctypes.c_int
+        lib.oracle_scan_i8.argtypes = [vp, u64, vp]
+        lib.oracle_scan_i8.restype = None
+        lib.oracle_scan_f32in.argtypes = [vp, u64, vp]
+        lib.oracle_scan_f32in.restype = None
+        lib.oracle_scan_f64.argtypes = [vp, u64, vp]
+        lib.oracle_scan_f64.restype = None
+        lib.oracle_compress_u32.argtypes = [vp, vp, u64, vp]
+        lib.oracle_compress_u32.restype = u64
+        lib.oracle_diff_i32.argtypes = [vp, u64, vp]
+        lib.oracle_diff_i32.restype = None
+        lib.oracle_diff_f32in.argtypes = [vp, u64, vp]
+        lib.oracle_diff_f32in.restype = None
+        lib.oracle_revert_i32.argtypes = [vp, vp, vp, u64, u64, vp]
+        lib.oracle_revert_i32.restype = ctypes.c_int
+        lib.oracle_revert_f32in.argtypes = [vp, vp, vp, u64, u64, vp]
+        lib.oracle_revert_f32in.restype = ctypes.c_int
+        lib.oracle_spmv_csr.argtypes = [u64, u64, vp, vp, vp, vp, vp]
+        lib.oracle_spmv_csr.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -137,4 +159,97 @@ def spmv_coo(n_rows: int, n_cols: int, row, col, val, x) -> np.ndarray:
                                   _ptr(x), _ptr(y))
     if bad:
         raise ValueError("row or column index out of range")
+    return y
+
+
+# ---- the parallel primitives of Algorithms SCD and SSCR (Sec. 4.1) -----------------------------
+
+def scan(x) -> np.ndarray:
+    """Unsegmented inclusive scan z(i) = x(0) + ... + x(i) (Sec. 1.1; Algorithm Scan computes it).
+
+    int8 -> int32 with wrap-around; float16/float32/float64 -> float64 accumulated in float64.
+    """
+    x = np.ascontiguousarray(x)
+    n = x.shape[0]
+    lib = _load()
+    if x.dtype == np.int8:
+        z = np.empty(n, dtype=np.int32)
+        lib.oracle_scan_i8(_ptr(x), n, _ptr(z))
+        return z
+    if x.dtype == np.float32:
+        z = np.empty(n, dtype=np.float64)
+        lib.oracle_scan_f32in(_ptr(x), n, _ptr(z))
+        return z
+    if x.dtype in (np.float16, np.float64):
+        xd = np.ascontiguousarray(x, dtype=np.float64)
+        z = np.empty(n, dtype=np.float64)
+        lib.oracle_scan_f64(_ptr(xd), n, _ptr(z))
+        return z
+    raise TypeError("unsupported value dtype %s" % x.dtype)
+
+
+def compress(x, mask) -> np.ndarray:
+    """COMPRESS (Sec. 2): the entries of x (any 32-bit type) whose mask entry is non-zero, in order."""
+    x = np.ascontiguousarray(x)
+    if x.dtype.itemsize != 4:
+        raise TypeError("compress works on 32-bit elements")
+    n = x.shape[0]
+    m = _flags_u8(mask, n)
+    out = np.empty(n, dtype=x.dtype)
+    k = _load().oracle_compress_u32(_ptr(x), _ptr(m), n, _ptr(out))
+    return out[:k].copy()
+
+
+def diff(x) -> np.ndarray:
+    """DIFF (Sec. 4.1): z(i) = x(i) - x(i-1), x(-1) = 0.  int32 wraps; float32 -> float64."""
+    x = np.ascontiguousarray(x)
+    n = x.shape[0]
+    lib = _load()
+    if x.dtype == np.int32:
+        z = np.empty(n, dtype=np.int32)
+        lib.oracle_diff_i32(_ptr(x), n, _ptr(z))
+        return z
+    if x.dtype == np.float32:
+        z = np.empty(n, dtype=np.float64)
+        lib.oracle_diff_f32in(_ptr(x), n, _ptr(z))
+        return z
+    raise TypeError("unsupported value dtype %s" % x.dtype)
+
+
+def revert(xhat, fhat, w) -> np.ndarray:
+    """REVERT (Sec. 4.1): xhat(i) - w(fhat(i) - 2) where the inclusive segment count fhat(i) >= 2."""
+    xhat = np.ascontiguousarray(xhat)
+    fhat = np.ascontiguousarray(fhat, dtype=np.int32)
+    w = np.ascontiguousarray(w, dtype=xhat.dtype)
+    n = xhat.shape[0]
+    if fhat.shape != (n,):
+        raise ValueError("shape mismatch")
+    lib = _load()
+    if xhat.dtype == np.int32:
+        z = np.empty(n, dtype=np.int32)
+        bad = lib.oracle_revert_i32(_ptr(xhat), _ptr(fhat), _ptr(w), n, w.shape[0], _ptr(z))
+    elif xhat.dtype == np.float32:
+        z = np.empty(n, dtype=np.float64)
+        bad = lib.oracle_revert_f32in(_ptr(xhat), _ptr(fhat), _ptr(w), n, w.shape[0], _ptr(z))
+    else:
+        raise TypeError("unsupported value dtype %s" % xhat.dtype)
+    if bad:
+        raise ValueError("a segment count points outside w")
+    return z
+
+
+def spmv_csr(n_rows: int, n_cols: int, rowptr, col, val, x) -> np.ndarray:
+    """y = A x in float64 for a CSR matrix (Algorithm "MMV-RAM CSR SpMV", Sec. 4.3)."""
+    rowptr = np.ascontiguousarray(rowptr, dtype=np.int32)
+    col = np.ascontiguousarray(col, dtype=np.int32)
+    val = np.ascontiguousarray(val, dtype=np.float32)
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    if rowptr.shape != (n_rows + 1,) or col.shape != val.shape or x.shape != (n_cols,):
+        raise ValueError("shape mismatch")
+    if n_rows and (rowptr[0] != 0 or rowptr[-1] != val.shape[0]):
+        raise ValueError("rowptr must start at 0 and end at nnz")
+    y = np.empty(n_rows, dtype=np.float64)
+    bad = _load().oracle_spmv_csr(n_rows, n_cols, _ptr(rowptr), _ptr(col), _ptr(val), _ptr(x), _ptr(y))
+    if bad:
+        raise ValueError("row pointers not monotone or column index out of range")
     return y

@@ -5,7 +5,7 @@ triples) and converts between the two flag encodings.  It holds none of the
 method's arithmetic, so both the tests' CPU oracle and the GPU library can be
 fed from it without sharing anything else.
 
-The five workloads mirror the shapes the paper measures on: uniformly random
+The five main workloads mirror the shapes the paper measures on: uniformly random
 segment-start flags over a range of densities (Sec. 5.2.1, density sweep) and
 the row-length structure of sparse matrices (Sec. 5.2.1 / 5.2.3), which are
 not available offline; these generators stand in for them.
@@ -23,6 +23,7 @@ SEEDS = {
     "segscan_i8_uniform_len": 2390603,
     "spmv_coo_zipf": 2390604,
     "stress_f32_three_regimes": 2390605,
+    "blocked_sparse_attention": 2390606,
 }
 
 
@@ -166,3 +167,52 @@ def uniform_density_flags(n: int, density: float, seed: int) -> np.ndarray:
     if n:
         f[0] = 1
     return f
+
+
+# ---- CSR inputs (Sec. 4.3, Algorithm "MMV-RAM CSR SpMV"; Sec. 5.2.3 workloads) --------------------
+
+def csr_rowptr(row: np.ndarray, n_rows: int) -> np.ndarray:
+    """Row pointers (n_rows + 1 int32 entries) of a row-sorted COO index vector: a format conversion."""
+    counts = np.bincount(np.asarray(row, dtype=np.int64), minlength=n_rows)
+    rowptr = np.zeros(n_rows + 1, dtype=np.int64)
+    np.cumsum(counts, out=rowptr[1:])
+    return rowptr.astype(np.int32)
+
+
+def blocked_sparse_attention(n: int = 1 << 16, block: int = 64, n_random: int = 2, n_global: int = 2,
+                             n_window: int = 3, seed: int | None = None):
+    """Blocked sparse-attention matrix in CSR form, after the synthetic matrices of Sec. 5.2.3.
+
+    The n x n matrix is cut into blocks of ``block`` x ``block``; the paper states the size
+    (65,536), two blocks of global attention, three blocks of window attention, block sizes
+    {2, 4, 16, 64} and {2, 4, 8} random blocks, and nothing else.  Reading taken here: block row
+    i holds the first ``n_global`` block columns, the ``n_window`` block columns centred on i
+    (clipped at the borders) and ``n_random`` block columns drawn uniformly (a draw that hits a
+    block already present adds nothing); the first ``n_global`` block rows are full.  Every entry
+    of a present block is a non-zero ~ N(0, 1); x ~ N(0, 1).  Returns (rowptr, col, val, x).
+    """
+    if n % block:
+        raise ValueError("n must be a multiple of the block size")
+    rng = np.random.default_rng(SEEDS["blocked_sparse_attention"] + 1000 * block + n_random
+                                if seed is None else seed)
+    nb = n // block
+    half = n_window // 2
+    inner = np.arange(block, dtype=np.int64)
+    cols, lens = [], np.empty(nb, dtype=np.int64)
+    for i in range(nb):
+        if i < n_global:
+            bc = np.arange(nb, dtype=np.int64)
+        else:
+            window = np.arange(i - half, i - half + n_window, dtype=np.int64)
+            window = window[(window >= 0) & (window < nb)]
+            bc = np.unique(np.concatenate([np.arange(min(n_global, nb), dtype=np.int64), window,
+                                           rng.integers(0, nb, size=n_random)]))
+        one_row = (bc[:, None] * block + inner[None, :]).ravel()
+        cols.append(np.tile(one_row, block))
+        lens[i] = one_row.shape[0]
+    col = np.concatenate(cols).astype(np.int32)
+    rowptr = np.zeros(n + 1, dtype=np.int64)
+    np.cumsum(np.repeat(lens, block), out=rowptr[1:])
+    val = rng.standard_normal(col.shape[0], dtype=np.float32)
+    x = rng.standard_normal(n, dtype=np.float32)
+    return rowptr.astype(np.int32), col, val, x
