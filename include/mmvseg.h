@@ -69,11 +69,25 @@ typedef enum {
     MMV_VARIANT_SHUFFLE = 1 /* ablation: same rows scanned with vector adds and lane shuffles */
 } mmv_variant;
 
-typedef enum { MMV_OP_SEGSCAN = 0, MMV_OP_SEGSUM = 1, MMV_OP_SPMV_COO = 2 } mmv_op;
+typedef enum {
+    MMV_OP_SEGSCAN = 0,
+    MMV_OP_SEGSUM = 1,
+    MMV_OP_SPMV_COO = 2,
+    MMV_OP_SCAN = 3,         /* mmv_scan */
+    MMV_OP_COMPRESS = 4,     /* mmv_compress (dt ignored) */
+    MMV_OP_SEGSUM_SCD = 5,   /* mmv_segsum_scd, sized for out_capacity = n */
+    MMV_OP_SEGSCAN_SSCR = 6, /* mmv_segscan_sscr */
+    MMV_OP_SPMV_CSR = 7      /* sized by mmv_spmv_csr_workspace_bytes */
+} mmv_op;
+
+/* Element type of the 32-bit vectors that DIFF and REVERT work on. */
+typedef enum { MMV_ELEM_I32 = 0 /* wraps */, MMV_ELEM_F32 = 1 } mmv_elem;
 
 /* Bytes of scratch needed for one call.  `n` is the vector length (nnz for
- * SpMV).  Pure host function; returns 0 for invalid arguments. */
+ * SpMV).  Pure host function; returns 0 for invalid arguments and for
+ * MMV_OP_SPMV_CSR, whose size depends on two lengths. */
 size_t mmv_workspace_bytes(mmv_op op, mmv_dtype dt, mmv_flag_fmt ff, uint64_t n);
+size_t mmv_spmv_csr_workspace_bytes(uint64_t n_rows, uint64_t nnz);
 
 /* Segmented inclusive scan (Problem 2.1, Sec. 2):
  *   z(i) = x(i) if i == 0 or f(i) == 1, else z(i-1) + x(i).
@@ -97,7 +111,8 @@ mmv_status mmv_segscan(const void *d_x, const void *d_flags, uint64_t n, void *d
  *   d_nseg        device uint64: receives the true number of segments,
  *                 1 + #{i >= 1 : f(i) = 1} for n >= 1
  * Sums with index >= out_capacity are not written (d_nseg still holds the true
- * count); pass out_capacity = n to be safe. */
+ * count); pass out_capacity = n to be safe.  The number of segments must be
+ * below 2^32 (counts are carried in 32 bits). */
 mmv_status mmv_segsum(const void *d_x, const void *d_flags, uint64_t n,
                       void *d_out, uint64_t out_capacity, uint64_t *d_nseg,
                       mmv_dtype dt, mmv_flag_fmt ff, mmv_variant v,
@@ -117,6 +132,77 @@ mmv_status mmv_spmv_coo(uint64_t n_rows, uint64_t n_cols, uint64_t nnz,
                         const int32_t *d_row, const int32_t *d_col, const float *d_val,
                         const float *d_x, float *d_y, mmv_variant v,
                         void *d_ws, size_t ws_bytes, void *hip_stream);
+
+/* y = A x for a CSR matrix (Algorithm "MMV-RAM CSR SpMV", Sec. 4.3: the row
+ * vector holds the segment start indices instead of flags), rows without
+ * entries allowed (appendix "SpMV implementation").  The row pointers are turned
+ * into segment-start flags over the non-zeros and into the list of rows that have
+ * entries (a COMPRESS of the row indices); the sum of the k-th segment goes to
+ * the k-th such row.
+ *   d_rowptr  n_rows + 1 int32, non-decreasing, d_rowptr[0] = 0,
+ *             d_rowptr[n_rows] = nnz (not checked; otherwise undefined)
+ *   d_col, d_val, d_x, d_y  as for mmv_spmv_coo; d_y is fully written.
+ * n_rows, n_cols, nnz < 2^31. */
+mmv_status mmv_spmv_csr(uint64_t n_rows, uint64_t n_cols, uint64_t nnz,
+                        const int32_t *d_rowptr, const int32_t *d_col, const float *d_val,
+                        const float *d_x, float *d_y, mmv_variant v,
+                        void *d_ws, size_t ws_bytes, void *hip_stream);
+
+/* ---- The parallel primitives of Sec. 4.1, one call each, and the paper's
+ * ---- un-fused compositions of them (for comparison with the fused calls above).
+
+ * SCAN: unsegmented inclusive scan z(i) = x(0) + ... + x(i) (Sec. 1.1;
+ * Algorithm "Scan in MMV-RAM", Sec. 4): the same single-pass kernel as
+ * mmv_segscan without a flag vector.  Types and aliasing as for mmv_segscan. */
+mmv_status mmv_scan(const void *d_x, uint64_t n, void *d_z, mmv_dtype dt, mmv_variant v,
+                    void *d_ws, size_t ws_bytes, void *hip_stream);
+
+/* COMPRESS (Sec. 2: "the entries of x whose flag is 1", example
+ * COMPRESS((2,2,3,3,1,3,1,2), (1,0,1,0,0,1,0,0)) = (2,3,3)); the output position
+ * of an entry is the number of selected entries before it (the scan of the mask
+ * in the proof of the SCD / SSCR theorem).
+ *   d_x      n 32-bit entries of any type, copied bit for bit; NULL = compress
+ *            the positions 0 .. n-1 themselves (uint32)
+ *   d_mask   n mask entries in format `ff` (position 0 has no special role here)
+ *   d_out    room for `out_capacity` entries; entries with index >= out_capacity
+ *            are not written
+ *   d_count  device uint64: receives the number of selected entries, which
+ *            must be below 2^32 */
+mmv_status mmv_compress(const void *d_x, const void *d_mask, uint64_t n,
+                        void *d_out, uint64_t out_capacity, uint64_t *d_count,
+                        mmv_flag_fmt ff, void *d_ws, size_t ws_bytes, void *hip_stream);
+
+/* DIFF (Sec. 4.1, "vector differentiation"): z(i) = x(i) - x(i-1), x(-1) = 0.
+ * d_z must not alias d_x.  No workspace. */
+mmv_status mmv_diff(const void *d_x, uint64_t n, void *d_z, mmv_elem et, void *hip_stream);
+
+/* REVERT (Sec. 4.1): undoes the speculation of an unsegmented scan,
+ *   z(i) = xhat(i) - w(fhat(i) - 2)  if fhat(i) >= 2,   z(i) = xhat(i) otherwise,
+ * where fhat(i) is the number of segment starts at positions 0 .. i (position 0
+ * counted) and w(k) is xhat at the last position of segment k.  (The printed
+ * procedure compares fhat with idx + 1; that would also subtract from the first
+ * segment, so the index is read shifted by one.)  A count that points beyond
+ * w(nw - 1) subtracts nothing.  d_z may alias d_xhat.  No workspace. */
+mmv_status mmv_revert(const void *d_xhat, const int32_t *d_fhat, const void *d_w,
+                      uint64_t n, uint64_t nw, void *d_z, mmv_elem et, void *hip_stream);
+
+/* Algorithm SCD (Sec. 4.1) as printed: segmented sum = DIFF(COMPRESS(SCAN(x),
+ * f^-)), four kernels and three passes over HBM.  Same arguments and results as
+ * mmv_segsum (entries of d_out beyond the segment count are left untouched).  The
+ * speculative scan runs over the whole vector, so floating-point sums carry the
+ * rounding error of the global prefix (up to ulp(|xhat|) per sum); integers are
+ * exact. */
+mmv_status mmv_segsum_scd(const void *d_x, const void *d_flags, uint64_t n,
+                          void *d_out, uint64_t out_capacity, uint64_t *d_nseg,
+                          mmv_dtype dt, mmv_flag_fmt ff, mmv_variant v,
+                          void *d_ws, size_t ws_bytes, void *hip_stream);
+
+/* Algorithm SSCR (Sec. 4.1) as printed: segmented scan = REVERT(SCAN(x), SCAN(f),
+ * COMPRESS(SCAN(x), f^-)).  Same arguments and results as mmv_segscan, same
+ * remark on floating point as mmv_segsum_scd. */
+mmv_status mmv_segscan_sscr(const void *d_x, const void *d_flags, uint64_t n, void *d_z,
+                            mmv_dtype dt, mmv_flag_fmt ff, mmv_variant v,
+                            void *d_ws, size_t ws_bytes, void *hip_stream);
 
 /* Reads the status word the last call on this workspace left behind: 0 = fine,
  * non-zero = a workgroup gave up waiting for a predecessor tile's carry (should

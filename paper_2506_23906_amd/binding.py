@@ -21,10 +21,14 @@ MMV_F32_F32, MMV_F16_F32, MMV_BF16_F32, MMV_I8_I32 = 0, 1, 2, 3
 MMV_FLAGS_U8, MMV_FLAGS_PACKED32 = 0, 1
 MMV_VARIANT_MFMA, MMV_VARIANT_SHUFFLE = 0, 1
 MMV_OP_SEGSCAN, MMV_OP_SEGSUM, MMV_OP_SPMV_COO = 0, 1, 2
+MMV_OP_SCAN, MMV_OP_COMPRESS, MMV_OP_SEGSUM_SCD, MMV_OP_SEGSCAN_SSCR, MMV_OP_SPMV_CSR = 3, 4, 5, 6, 7
+MMV_ELEM_I32, MMV_ELEM_F32 = 0, 1
 
 EXPORTS = [
     "mmv_workspace_bytes", "mmv_segscan", "mmv_segsum", "mmv_spmv_coo", "mmv_workspace_status",
     "mmv_stream_copy", "mmv_status_string", "mmv_tile_elems", "mmv_set_kernel_events",
+    "mmv_spmv_csr_workspace_bytes", "mmv_spmv_csr", "mmv_scan", "mmv_compress", "mmv_diff", "mmv_revert",
+    "mmv_segsum_scd", "mmv_segscan_sscr",
 ]
 
 _DTYPES = {torch.float32: MMV_F32_F32, torch.float16: MMV_F16_F32, torch.bfloat16: MMV_BF16_F32,
@@ -68,6 +72,22 @@ def load() -> ctypes.CDLL:
     lib.mmv_set_kernel_events.restype = i32
     lib.mmv_tile_elems.argtypes = [i32, i32, u64]
     lib.mmv_tile_elems.restype = ctypes.c_uint32
+    lib.mmv_spmv_csr_workspace_bytes.argtypes = [u64, u64]
+    lib.mmv_spmv_csr_workspace_bytes.restype = sz
+    lib.mmv_spmv_csr.argtypes = [u64, u64, u64, vp, vp, vp, vp, vp, i32, vp, sz, vp]
+    lib.mmv_spmv_csr.restype = i32
+    lib.mmv_scan.argtypes = [vp, u64, vp, i32, i32, vp, sz, vp]
+    lib.mmv_scan.restype = i32
+    lib.mmv_compress.argtypes = [vp, vp, u64, vp, u64, vp, i32, vp, sz, vp]
+    lib.mmv_compress.restype = i32
+    lib.mmv_diff.argtypes = [vp, u64, vp, i32, vp]
+    lib.mmv_diff.restype = i32
+    lib.mmv_revert.argtypes = [vp, vp, vp, u64, u64, vp, i32, vp]
+    lib.mmv_revert.restype = i32
+    lib.mmv_segsum_scd.argtypes = [vp, vp, u64, vp, u64, vp, i32, i32, i32, vp, sz, vp]
+    lib.mmv_segsum_scd.restype = i32
+    lib.mmv_segscan_sscr.argtypes = [vp, vp, u64, vp, i32, i32, i32, vp, sz, vp]
+    lib.mmv_segscan_sscr.restype = i32
     _lib = lib
     return lib
 
@@ -178,3 +198,122 @@ def mmv_stream_copy(src: torch.Tensor, dst: torch.Tensor, in_bytes: int | None =
 def mmv_set_kernel_events(ev_start: int | None, ev_stop: int | None) -> None:
     """ev_start / ev_stop are hipEvent_t handles as integers (or None to switch off)."""
     _check(load().mmv_set_kernel_events(ev_start, ev_stop), "mmv_set_kernel_events")
+
+
+# ---- CSR SpMV, the stand-alone primitives of Sec. 4.1 and the un-fused compositions ------------------------
+
+_ELEMS = {torch.int32: MMV_ELEM_I32, torch.float32: MMV_ELEM_F32}
+
+
+def mmv_spmv_csr_workspace_bytes(n_rows: int, nnz: int) -> int:
+    return int(load().mmv_spmv_csr_workspace_bytes(n_rows, nnz))
+
+
+def mmv_spmv_csr(n_rows: int, n_cols: int, rowptr: torch.Tensor, col: torch.Tensor, val: torch.Tensor,
+                 x: torch.Tensor, y: torch.Tensor | None = None, variant: str = "mfma",
+                 ws: torch.Tensor | None = None, stream=None, nnz: int | None = None) -> torch.Tensor:
+    """y = A x for a CSR matrix (int32 row pointers and column indices, fp32 values)."""
+    lib = load()
+    nnz = val.numel() if nnz is None else nnz
+    if y is None:
+        y = torch.empty(n_rows, dtype=torch.float32, device=val.device)
+    if ws is None:
+        ws = torch.empty(max(256, mmv_spmv_csr_workspace_bytes(n_rows, nnz)), dtype=torch.uint8, device=val.device)
+    st = lib.mmv_spmv_csr(n_rows, n_cols, nnz, _dev(rowptr, "rowptr"), _dev(col, "col"), _dev(val, "val"),
+                          _dev(x, "x"), _dev(y, "y"), _VARIANTS[variant], _dev(ws, "ws"), ws.numel(),
+                          _stream_ptr(stream))
+    _check(st, "mmv_spmv_csr")
+    return y
+
+
+def mmv_scan(x: torch.Tensor, n: int | None = None, z: torch.Tensor | None = None, variant: str = "mfma",
+             ws: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+    """Unsegmented inclusive scan; returns z (fp32 or int32)."""
+    lib = load()
+    n = x.numel() if n is None else n
+    dt = _DTYPES[x.dtype]
+    if z is None:
+        z = torch.empty(n, dtype=_OUT_DTYPE[dt], device=x.device)
+    if ws is None:
+        ws = new_workspace(MMV_OP_SCAN, dt, MMV_FLAGS_PACKED32, n, x.device)
+    st = lib.mmv_scan(_dev(x, "x"), n, _dev(z, "z"), dt, _VARIANTS[variant], _dev(ws, "ws"), ws.numel(),
+                      _stream_ptr(stream))
+    _check(st, "mmv_scan")
+    return z
+
+
+def mmv_compress(x: torch.Tensor | None, mask: torch.Tensor, n: int, out: torch.Tensor | None = None,
+                 count: torch.Tensor | None = None, ws: torch.Tensor | None = None, stream=None):
+    """COMPRESS of a 32-bit vector (or of the positions, x=None); returns (out, count)."""
+    lib = load()
+    ff = _flag_fmt(mask)
+    if x is not None and x.element_size() != 4:
+        raise MmvError("mmv_compress works on 32-bit elements")
+    if out is None:
+        out = torch.empty(max(n, 1), dtype=torch.int32 if x is None else x.dtype, device=mask.device)
+    if count is None:
+        count = torch.empty(1, dtype=torch.int64, device=mask.device)
+    if ws is None:
+        ws = new_workspace(MMV_OP_COMPRESS, MMV_I8_I32, ff, n, mask.device)
+    st = lib.mmv_compress(None if x is None else _dev(x, "x"), _dev(mask, "mask"), n, _dev(out, "out"), out.numel(),
+                          _dev(count, "count"), ff, _dev(ws, "ws"), ws.numel(), _stream_ptr(stream))
+    _check(st, "mmv_compress")
+    return out, count
+
+
+def mmv_diff(x: torch.Tensor, n: int | None = None, z: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+    """DIFF of an int32 or fp32 vector."""
+    n = x.numel() if n is None else n
+    if z is None:
+        z = torch.empty(max(n, 1), dtype=x.dtype, device=x.device)
+    _check(load().mmv_diff(_dev(x, "x"), n, _dev(z, "z"), _ELEMS[x.dtype], _stream_ptr(stream)), "mmv_diff")
+    return z
+
+
+def mmv_revert(xhat: torch.Tensor, fhat: torch.Tensor, w: torch.Tensor, n: int | None = None,
+               nw: int | None = None, z: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+    """REVERT: xhat(i) - w(fhat(i) - 2) where fhat(i) >= 2; int32 or fp32, fhat int32."""
+    n = xhat.numel() if n is None else n
+    nw = w.numel() if nw is None else nw
+    if fhat.dtype != torch.int32 or w.dtype != xhat.dtype:
+        raise MmvError("fhat must be int32 and w must have the type of xhat")
+    if z is None:
+        z = torch.empty(max(n, 1), dtype=xhat.dtype, device=xhat.device)
+    _check(load().mmv_revert(_dev(xhat, "xhat"), _dev(fhat, "fhat"), _dev(w, "w"), n, nw, _dev(z, "z"),
+                             _ELEMS[xhat.dtype], _stream_ptr(stream)), "mmv_revert")
+    return z
+
+
+def mmv_segsum_scd(x: torch.Tensor, flags: torch.Tensor, n: int | None = None, out: torch.Tensor | None = None,
+                   nseg: torch.Tensor | None = None, variant: str = "mfma", ws: torch.Tensor | None = None,
+                   stream=None):
+    """Segmented sum through the un-fused Algorithm SCD; returns (out, nseg) like mmv_segsum."""
+    lib = load()
+    n = x.numel() if n is None else n
+    dt, ff = _DTYPES[x.dtype], _flag_fmt(flags)
+    if out is None:
+        out = torch.empty(max(n, 1), dtype=_OUT_DTYPE[dt], device=x.device)
+    if nseg is None:
+        nseg = torch.empty(1, dtype=torch.int64, device=x.device)
+    if ws is None:
+        ws = new_workspace(MMV_OP_SEGSUM_SCD, dt, ff, n, x.device)
+    st = lib.mmv_segsum_scd(_dev(x, "x"), _dev(flags, "flags"), n, _dev(out, "out"), out.numel(), _dev(nseg, "nseg"),
+                            dt, ff, _VARIANTS[variant], _dev(ws, "ws"), ws.numel(), _stream_ptr(stream))
+    _check(st, "mmv_segsum_scd")
+    return out, nseg
+
+
+def mmv_segscan_sscr(x: torch.Tensor, flags: torch.Tensor, n: int | None = None, z: torch.Tensor | None = None,
+                     variant: str = "mfma", ws: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+    """Segmented scan through the un-fused Algorithm SSCR; returns z like mmv_segscan."""
+    lib = load()
+    n = x.numel() if n is None else n
+    dt, ff = _DTYPES[x.dtype], _flag_fmt(flags)
+    if z is None:
+        z = torch.empty(n, dtype=_OUT_DTYPE[dt], device=x.device)
+    if ws is None:
+        ws = new_workspace(MMV_OP_SEGSCAN_SSCR, dt, ff, n, x.device)
+    st = lib.mmv_segscan_sscr(_dev(x, "x"), _dev(flags, "flags"), n, _dev(z, "z"), dt, ff, _VARIANTS[variant],
+                              _dev(ws, "ws"), ws.numel(), _stream_ptr(stream))
+    _check(st, "mmv_segscan_sscr")
+    return z

@@ -84,7 +84,13 @@ typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 typedef short v8s __attribute__((ext_vector_type(8)));
 
-enum Op { kScan = 0, kSum = 1, kSpmv = 2 };
+// What a kernel instantiation computes (values match mmv_op where there is one):
+//   kScan       segmented inclusive scan
+//   kSum        segmented sum (one output per segment, index = number of segment ends before it)
+//   kSpmv       row-sorted COO SpMV: products val * x[col], sums scattered to y[row]
+//   kPlainScan  unsegmented inclusive scan (no flag vector: every row aggregate is carried on)
+//   kSpmvCsr    CSR SpMV: as kSpmv, but the sum of the k-th segment goes to y[rowmap[k]]
+enum Op { kScan = 0, kSum = 1, kSpmv = 2, kPlainScan = 3, kSpmvCsr = 7 };
 
 struct Params {
     const void *x;          // values (scan, sum) / val (spmv)
@@ -94,7 +100,9 @@ struct Params {
     void *out;              // sum output
     uint64_t out_cap;
     uint64_t *nseg;
-    const int32_t *row;     // spmv
+    const int32_t *row;     // spmv (coo)
+    const uint32_t *rowmap; // spmv (csr): row index of the k-th non-empty row
+    uint32_t first_one;     // plain scan of a flag vector: element 0 counts as 1 whatever it holds
     const int32_t *col;
     const float *xv;
     float *y;
@@ -610,6 +618,9 @@ __global__ __launch_bounds__(TT::kWaves * 64, 4) void seg_kernel(Params P) {
     constexpr int kWaves = TT::kWaves;
     constexpr int kCpw = TT::kMaxCpw;            // most chunks a wave takes (register arrays)
     constexpr int K = 16 / TT::kEpl;             // 128-bit words per lane and 32x32 tile
+    constexpr bool kScanLike = kOp == kScan || kOp == kPlainScan;   // every element is an output
+    constexpr bool kCounts = kOp == kSum || kOp == kSpmvCsr;        // output index = segment ordinal
+    constexpr bool kProduct = kOp == kSpmv || kOp == kSpmvCsr;      // values are val * x[col]
 
     __shared__ __attribute__((aligned(16))) uint32_t s_rows[kWaves][kRowsPerChunk * kRowStride];
     __shared__ uint32_t s_wave_v[kWaves], s_wave_f[kWaves], s_wave_c[kWaves];
@@ -643,17 +654,24 @@ __global__ __launch_bounds__(TT::kWaves * 64, 4) void seg_kernel(Params P) {
     // ---- all inputs of my span: flag word of my row and raw values (and columns) per chunk ----
     uint32_t F[kCpw];
     v4u raw[kCpw][2 * K];
-    v4u rawc[kOp == kSpmv ? kCpw : 1][2 * K];  // column indices (spmv)
+    v4u rawc[kProduct ? kCpw : 1][2 * K];  // column indices (spmv)
 #pragma unroll
     for (int c = 0; c < kCpw; ++c) {
         const uint64_t cb = wave_base + (uint64_t)c * kChunkElems;
         F[c] = 0;
         if (c < cpw_t) {
             const uint64_t rs = cb + 32u * lane;
-            if (rs < n) F[c] = __builtin_nontemporal_load(P.fw + (rs >> 5));
-            if constexpr (kOp == kSpmv) load_raw<TInt, kMfma>(P.col, cb, n, lane, rawc[c]);
+            if constexpr (kOp != kPlainScan) {
+                if (rs < n) F[c] = __builtin_nontemporal_load(P.fw + (rs >> 5));
+            }
+            if constexpr (kProduct) load_raw<TInt, kMfma>(P.col, cb, n, lane, rawc[c]);
             load_raw<TT, kMfma>((const In *)P.x, cb, n, lane, raw[c]);
         }
+    }
+
+    if constexpr (kOp == kPlainScan && sizeof(In) == 1) {
+        // counting segment starts: position 0 always opens a segment (byte 0 of the first word, both layouts)
+        if (P.first_one && tile == 0 && tid == 0) raw[0][0][0] = (raw[0][0][0] & ~0xFFu) | 1u;
     }
 
     // per chunk: exclusive segmented prefix of my row inside the chunk, and of the chunk inside
@@ -676,7 +694,7 @@ __global__ __launch_bounds__(TT::kWaves * 64, 4) void seg_kernel(Params P) {
         const uint64_t row_start = cb + 32u * lane;  // first element of the row this lane owns
         // ---- flags of my row (one 32-bit word = one row); bits beyond n do not count ----
         if (row_start + 32 > n) F[0] = row_start < n ? (F[0] & ((1u << (uint32_t)(n - row_start)) - 1u)) : 0u;
-        if constexpr (kOp == kSpmv) {
+        if constexpr (kProduct) {
             // product vector p(i) = val(i) * x(col(i)), in the layout the values were loaded in
 #pragma unroll
             for (int t = 0; t < 2; ++t)
@@ -723,7 +741,7 @@ __global__ __launch_bounds__(TT::kWaves * 64, 4) void seg_kernel(Params P) {
                 if (!inc_f) inc_v = ov + inc_v;
                 inc_f |= of;
             }
-            if (kOp == kSum) {
+            if (kCounts) {
                 const uint32_t oc = __shfl_up(inc_c, d);
                 if (lane >= d) inc_c += oc;
             }
@@ -742,16 +760,16 @@ __global__ __launch_bounds__(TT::kWaves * 64, 4) void seg_kernel(Params P) {
         const uint32_t ca_f = __shfl(inc_f, 63);
         run_v = ca_f ? ca_v : run_v + ca_v;
         run_f |= ca_f;
-        if (kOp == kSum) run_c += __shfl(inc_c, 63);
+        if (kCounts) run_c += __shfl(inc_c, 63);
       }
         rotate(F);
         rotate_rows(raw);
-        if constexpr (kOp == kSpmv) rotate_rows(rawc);
+        if constexpr (kProduct) rotate_rows(rawc);
         rotate(ex_v);
         rotate(ex_f);
         rotate(pre_v);
         rotate(pre_f);
-        if (kOp == kSum) rotate(ex_c);
+        if (kCounts) rotate(ex_c);
     }
     MMV_STAMP(2);
     if (lane == 0) {
@@ -785,7 +803,7 @@ __global__ __launch_bounds__(TT::kWaves * 64, 4) void seg_kernel(Params P) {
     // ---- step 5c, first half: publish this tile ----
     const bool final_now = tile == 0 || tagg_f;  // carry out does not depend on predecessors
     if (tid == 0) desc_store(P.desc_v + tile, final_now ? kStatusPrefix : kStatusAggregate, to_bits(tagg_v));
-    if (kOp == kSum && tid == 64) desc_store(P.desc_c + tile, tile == 0 ? kStatusPrefix : kStatusAggregate, tagg_c);
+    if (kCounts && tid == 64) desc_store(P.desc_c + tile, tile == 0 ? kStatusPrefix : kStatusAggregate, tagg_c);
 
     // carry into my span (used only by rows with no flag before them in the tile); the carry of
     // the predecessor tiles is added once it is known
@@ -807,14 +825,14 @@ __global__ __launch_bounds__(TT::kWaves * 64, 4) void seg_kernel(Params P) {
                     __hip_atomic_store(&s_ready, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
                 }
             }
-            if (kOp == kSum) {
+            if (kCounts) {
                 if (wave == 1) {
                     uint32_t carry = 0;
                     if (tile > 0) carry = lookback<uint32_t>(P.desc_c, (int)tile, lane, P.hdr);
                     if (lane == 0) {
                         if (tile > 0) desc_store(P.desc_c + tile, kStatusPrefix, carry + tagg_c);
                         s_carry_c = carry;
-                        if (tile == P.num_tiles - 1) *P.nseg = (uint64_t)carry + tagg_c + 1u;
+                        if (kOp == kSum && tile == P.num_tiles - 1) *P.nseg = (uint64_t)carry + tagg_c + 1u;
                     }
                 }
                 __syncthreads();  // every output index needs the count carry
@@ -833,7 +851,7 @@ __global__ __launch_bounds__(TT::kWaves * 64, 4) void seg_kernel(Params P) {
         for (int c = 0; c < kCpw; ++c) {
             // a chunk is "open" when no flag of the tile precedes it; the segmented sum treats
             // every chunk as open because all its output indices wait for the count carry
-            const bool chunk_open = kOp == kSum || !(wex_f || __builtin_amdgcn_readfirstlane(pre_f[0]));
+            const bool chunk_open = kCounts || !(wex_f || __builtin_amdgcn_readfirstlane(pre_f[0]));
             if (c < cpw_t && chunk_open == (pass == 1)) {
                 const uint64_t cb = wave_base + (uint64_t)c * kChunkElems;
                 const bool chunk_full = cb + kChunkElems <= n;
@@ -850,7 +868,7 @@ __global__ __launch_bounds__(TT::kWaves * 64, 4) void seg_kernel(Params P) {
                 }
                 // ---- step 6: carry into my row ----
                 const A carry = ex_f[0] ? ex_v[0] : (pre_f[0] ? pre_v[0] + ex_v[0] : (span_carry + pre_v[0]) + ex_v[0]);
-                if constexpr (kOp == kScan) {
+                if constexpr (kScanLike) {
                     // stored negated in the slot before x-bar(-1), so that the revert subtracts it
                     rows[lane * kRowStride + kSlotZero] = 0;
                     rows[lane * kRowStride + kSlotF] = F[0];
@@ -930,6 +948,9 @@ __global__ __launch_bounds__(TT::kWaves * 64, 4) void seg_kernel(Params P) {
                         if (kOp == kSum) {
                             const uint64_t k = count_base + __popc(Fc & ((2u << e) - 1u));
                             if (k < P.out_cap) ((A *)P.out)[k] = v;
+                        } else if (kOp == kSpmvCsr) {
+                            const uint64_t k = count_base + __popc(Fc & ((2u << e) - 1u));
+                            if (k < P.out_cap) P.y[P.rowmap[k]] = from_bits<float>(to_bits(v));
                         } else {
                             P.y[P.row[row_start + e]] = from_bits<float>(to_bits(v));
                         }
@@ -943,7 +964,7 @@ __global__ __launch_bounds__(TT::kWaves * 64, 4) void seg_kernel(Params P) {
             rotate(ex_f);
             rotate(pre_v);
             rotate(pre_f);
-            if (kOp == kSum) rotate(ex_c);
+            if (kCounts) rotate(ex_c);
         }
     }
     MMV_STAMP(6);
@@ -1000,6 +1021,213 @@ __global__ __launch_bounds__(256) void row_flags_kernel(const int32_t *row, uint
     }
 }
 
+// ---- the stand-alone primitives of Algorithms SCD and SSCR (Sec. 4.1) ------------------------------------
+//
+// SCAN is the main kernel without a flag vector (kPlainScan).  COMPRESS, DIFF and REVERT follow.
+// They exist so that the paper's un-fused compositions (SCD = DIFF o COMPRESS o SCAN, SSCR =
+// REVERT o COMPRESS o (SCAN, SCAN)) can be run and timed next to the fused single-pass kernel.
+
+// End markers f^- of Algorithm SCD: f shifted left by one position with a 1 appended, bit-packed.
+__global__ __launch_bounds__(256) void end_markers_kernel(const uint32_t *fw, uint64_t n, uint32_t *out,
+                                                          uint64_t nwords) {
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t w = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; w < nwords; w += stride) {
+        const uint32_t next = w + 1 < nwords ? fw[w + 1] : 0u;
+        uint32_t e = (fw[w] >> 1) | (next << 31);
+        if (w == nwords - 1) {
+            const uint32_t last = (uint32_t)((n - 1) & 31u);   // position of element n - 1 in this word
+            e = (e & ((1u << last) - 1u)) | (1u << last);
+        }
+        out[w] = e;
+    }
+}
+
+// Bit-packed flags -> one int8 (0 / 1) per element, for the count scan SCAN(f) of Algorithm SSCR.
+__global__ __launch_bounds__(256) void unpack_flags_kernel(const uint32_t *fw, uint64_t n, int8_t *out) {
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    const uint64_t nquads = (n + 3) / 4;   // a thread writes four bytes; out has room for the padding
+    for (uint64_t q = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; q < nquads; q += stride) {
+        const uint32_t bits = (fw[q >> 3] >> (4 * (q & 7))) & 0xFu;
+        reinterpret_cast<uint32_t *>(out)[q] = (bits & 1u) | ((bits & 2u) << 7) | ((bits & 4u) << 14) | ((bits & 8u) << 21);
+    }
+}
+
+// COMPRESS (Sec. 2): out = the 32-bit entries of x whose mask bit is set, in order; with
+// x == nullptr the positions themselves are compressed.  The mask is bit-packed; the output
+// index of an entry is the number of set bits before it (the scan of the mask in the paper's
+// COMPRESS), found per tile from popcounts and across tiles by decoupled look-back.
+// A wave owns 4096 consecutive positions: lane j holds the 64-bit mask word j, and for every
+// word the wave reads only the selected entries (one coalesced load, skipped when the word is
+// empty) and writes them to consecutive output slots.
+constexpr int kCompressWaves = 8;
+constexpr int kCompressTile = kCompressWaves * 4096;
+
+__global__ __launch_bounds__(kCompressWaves * 64) void compress_kernel(
+    const uint32_t *__restrict__ x, const uint32_t *__restrict__ mw, uint64_t n, uint32_t *__restrict__ out,
+    uint64_t out_cap, uint64_t *__restrict__ count, uint32_t *hdr, uint64_t *desc, uint32_t num_tiles) {
+    __shared__ uint32_t s_tile, s_wave[kCompressWaves], s_carry;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid == 0) s_tile = __hip_atomic_fetch_add(hdr + kHdrTicket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    const uint32_t tile = s_tile;
+    const uint64_t span = (uint64_t)tile * kCompressTile + (uint64_t)wave * 4096;  // first position of my wave
+    const uint64_t p0 = span + 64u * lane;                                          // first position of my word
+    uint64_t m = 0;
+    if (p0 < n) {
+        const uint64_t wi = p0 >> 5;
+        m = mw[wi];
+        if (p0 + 32 < n) m |= (uint64_t)mw[wi + 1] << 32;
+        if (p0 + 64 > n) m &= (1ull << (n - p0)) - 1ull;
+    }
+    const uint32_t cnt = (uint32_t)__popcll((unsigned long long)m);
+    uint32_t inc = cnt;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t o = __shfl_up(inc, d);
+        if (lane >= d) inc += o;
+    }
+    if (lane == 63) s_wave[wave] = inc;
+    __syncthreads();
+    uint32_t wave_ex = 0, tile_cnt = 0;
+#pragma unroll
+    for (int w = 0; w < kCompressWaves; ++w) {
+        if (w == wave) wave_ex = tile_cnt;
+        tile_cnt += s_wave[w];
+    }
+    if (tid == 0) desc_store(desc + tile, tile == 0 ? kStatusPrefix : kStatusAggregate, tile_cnt);
+    if (wave == 0) {
+        uint32_t carry = 0;
+        if (tile > 0) carry = lookback<uint32_t>(desc, (int)tile, lane, hdr);
+        if (lane == 0) {
+            if (tile > 0) desc_store(desc + tile, kStatusPrefix, carry + tile_cnt);
+            s_carry = carry;
+            if (tile == num_tiles - 1) *count = (uint64_t)carry + tile_cnt;
+        }
+    }
+    __syncthreads();
+    // output index of the first selected entry of word j of my wave (lane j holds it)
+    const uint64_t word_base = (uint64_t)s_carry + wave_ex + (inc - cnt);
+    const uint32_t m_lo = (uint32_t)m, m_hi = (uint32_t)(m >> 32);
+    const uint32_t base_lo = (uint32_t)word_base, base_hi = (uint32_t)(word_base >> 32);
+    const uint64_t lane_below = (1ull << lane) - 1ull;
+#pragma unroll 8
+    for (int j = 0; j < 64; ++j) {
+        const uint64_t mj = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)m_hi, j) << 32) |
+                            (uint32_t)__builtin_amdgcn_readlane((int)m_lo, j);
+        const uint64_t bj = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)base_hi, j) << 32) |
+                            (uint32_t)__builtin_amdgcn_readlane((int)base_lo, j);
+        if ((mj >> lane) & 1ull) {
+            const uint64_t p = span + 64u * j + lane;
+            const uint32_t v = x ? __builtin_nontemporal_load(x + p) : (uint32_t)p;
+            const uint64_t k = bj + (uint32_t)__popcll((unsigned long long)(mj & lane_below));
+            if (k < out_cap) out[k] = v;
+        }
+    }
+}
+
+// DIFF (Sec. 4.1): z(i) = x(i) - x(i-1) with x(-1) = 0, on int32 (wrap-around) or fp32.  The
+// paper writes it as the product with the bidiagonal matrix D_s plus a vector fix of the block
+// borders; here a lane takes four consecutive elements and gets the element before them from
+// its neighbour lane (one extra load at the wave border).
+// With `limit` the vector ends at min(n, *limit) (a count that an earlier kernel left on the device).
+template <typename A>
+__global__ __launch_bounds__(256) void diff_kernel(const uint32_t *__restrict__ x, uint64_t n, uint32_t *__restrict__ z,
+                                                   const uint64_t *__restrict__ limit) {
+    const int lane = threadIdx.x & 63;
+    if (limit) {
+        const uint64_t m = *limit;
+        n = m < n ? m : n;
+    }
+    const uint64_t e0 = ((uint64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    v4u w = {0, 0, 0, 0};
+    if (e0 + 4 <= n) {
+        w = __builtin_nontemporal_load(reinterpret_cast<const v4u *>(x + e0));
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (e0 + i < n) w[i] = x[e0 + i];
+    }
+    uint32_t prev = __shfl_up(w[3], 1);
+    if (lane == 0) prev = (e0 > 0 && e0 - 1 < n) ? x[e0 - 1] : 0u;
+    v4u o;
+    o[0] = to_bits(from_bits<A>(w[0]) - from_bits<A>(prev));
+#pragma unroll
+    for (int i = 1; i < 4; ++i) o[i] = to_bits(from_bits<A>(w[i]) - from_bits<A>(w[i - 1]));
+    if (e0 + 4 <= n) {
+        __builtin_nontemporal_store(o, reinterpret_cast<v4u *>(z + e0));
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (e0 + i < n) z[e0 + i] = o[i];
+    }
+}
+
+// REVERT (Sec. 4.1): z(i) = xhat(i) - w(fhat(i) - 2) where the inclusive count of segment
+// starts fhat(i) is at least 2 (the printed index is read shifted by one: the first segment is
+// left alone).  A count that points outside w subtracts nothing and raises the error word.
+template <typename A>
+__global__ __launch_bounds__(256) void revert_kernel(const uint32_t *xhat, const int32_t *__restrict__ fhat,
+                                                     const uint32_t *__restrict__ w, uint64_t n, uint64_t nw,
+                                                     uint32_t *z, uint32_t *err) {
+    const uint64_t e0 = ((uint64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (e0 >= n) return;
+    v4u xv = {0, 0, 0, 0};
+    v4i kv = {0, 0, 0, 0};
+    const bool full = e0 + 4 <= n;
+    if (full) {
+        xv = __builtin_nontemporal_load(reinterpret_cast<const v4u *>(xhat + e0));
+        kv = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(fhat + e0));
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (e0 + i < n) {
+                xv[i] = xhat[e0 + i];
+                kv[i] = fhat[e0 + i];
+            }
+    }
+    v4u o;
+    bool bad = false;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        A v = from_bits<A>(xv[i]);
+        const int64_t k = kv[i];
+        if (k >= 2) {
+            if ((uint64_t)(k - 2) < nw) v -= from_bits<A>(w[k - 2]);
+            else if (e0 + i < n) bad = true;
+        }
+        o[i] = to_bits(v);
+    }
+    if (bad && err) __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (full) {
+        __builtin_nontemporal_store(o, reinterpret_cast<v4u *>(z + e0));
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (e0 + i < n) z[e0 + i] = o[i];
+    }
+}
+
+// Row pointers of a CSR matrix -> (a) bit-packed segment-start flags over the non-zeros (a row
+// with entries sets the bit of its first entry; rows that share a word meet in an atomic OR on
+// a zeroed word) and (b) the bit-packed mask of rows that have entries (one ballot per 64 rows).
+__global__ __launch_bounds__(256) void csr_flags_kernel(const int32_t *rowptr, uint64_t n_rows, uint32_t *fw,
+                                                        uint32_t *rowmask) {
+    const int lane = threadIdx.x & 63;
+    const uint64_t r = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    bool nonempty = false;
+    if (r < n_rows) {
+        const int32_t a = rowptr[r], b = rowptr[r + 1];
+        nonempty = b > a;
+        if (nonempty) atomicOr(fw + ((uint32_t)a >> 5), 1u << ((uint32_t)a & 31u));
+    }
+    const uint64_t m = __ballot(nonempty);
+    const uint64_t r0 = r - lane;
+    if (lane == 0 && r0 < n_rows) {
+        rowmask[r0 >> 5] = (uint32_t)m;
+        if (r0 + 32 < n_rows) rowmask[(r0 >> 5) + 1] = (uint32_t)(m >> 32);
+    }
+}
+
 // Streaming reference: 128-bit non-temporal reads and writes, kIn input chunks and kOut
 // output chunks per thread, both striped across the workgroup; one workgroup per 256
 // units (measured faster than a persistent grid-stride loop on this chip).
@@ -1034,8 +1262,9 @@ constexpr uint64_t kResident = MMV_MIN_TILES;   // workgroups resident at once (
 #define MMV_TAIL_ROUNDS 1
 #endif
 constexpr uint64_t kTailTiles = MMV_TAIL_ROUNDS * kResident;  // short tiles at the end of a long vector
+inline bool is_spmv(mmv_op op) { return op == MMV_OP_SPMV_COO || op == MMV_OP_SPMV_CSR; }
 inline int max_cpw(mmv_op op, mmv_dtype dt) {
-    if (op == MMV_OP_SPMV_COO) return TSpmv::kMaxCpw;
+    if (is_spmv(op)) return TSpmv::kMaxCpw;
     switch (dt) {
         case MMV_F32_F32: return TF32::kMaxCpw;
         case MMV_F16_F32: return TF16::kMaxCpw;
@@ -1045,7 +1274,7 @@ inline int max_cpw(mmv_op op, mmv_dtype dt) {
     return 1;
 }
 inline int waves_of(mmv_op op, mmv_dtype dt) {
-    if (op == MMV_OP_SPMV_COO) return TSpmv::kWaves;
+    if (is_spmv(op)) return TSpmv::kWaves;
     switch (dt) {
         case MMV_F32_F32: return TF32::kWaves;
         case MMV_F16_F32: return TF16::kWaves;
@@ -1095,9 +1324,96 @@ WsLayout ws_layout(mmv_op op, mmv_dtype dt, mmv_flag_fmt ff, uint64_t n) {
     L.desc_v = off;
     off += round256(t * 8);
     L.desc_c = off;
-    if (op == MMV_OP_SEGSUM) off += round256(t * 8);
+    if (op == MMV_OP_SEGSUM || op == MMV_OP_SPMV_CSR) off += round256(t * 8);
     L.packed = off;
-    if (op == MMV_OP_SPMV_COO || ff == MMV_FLAGS_U8) off += round256(((n + 63) / 64) * 8);
+    if (is_spmv(op) || (ff == MMV_FLAGS_U8 && op != MMV_OP_SCAN)) off += round256(((n + 63) / 64) * 8);
+    L.total = off;
+    return L;
+}
+
+// Workspace of COMPRESS: header, one count descriptor per tile, packed mask if the caller gave bytes.
+struct CompressLayout {
+    size_t desc, packed, total;
+    uint64_t tiles;
+};
+CompressLayout compress_layout(mmv_flag_fmt ff, uint64_t n) {
+    CompressLayout L;
+    L.tiles = (n + kCompressTile - 1) / kCompressTile;
+    size_t off = kHdrBytes;
+    L.desc = off;
+    off += round256(L.tiles * 8);
+    L.packed = off;
+    if (ff == MMV_FLAGS_U8) off += round256(((n + 63) / 64) * 8);
+    L.total = off;
+    return L;
+}
+
+// Workspaces of the un-fused compositions: the sub-workspaces of the primitives they call and
+// their intermediate vectors, one after the other (every offset a multiple of 256).
+struct ScdLayout {
+    size_t scan_ws, xhat, packed, fminus, compress_ws, w, total;
+};
+ScdLayout scd_layout(mmv_dtype dt, mmv_flag_fmt ff, uint64_t n, uint64_t cap) {
+    ScdLayout L;
+    size_t off = 0;
+    L.scan_ws = off;
+    off += round256(ws_layout(MMV_OP_SCAN, dt, MMV_FLAGS_PACKED32, n).total);
+    L.xhat = off;
+    off += round256(n * 4);
+    L.packed = off;
+    if (ff == MMV_FLAGS_U8) off += round256(((n + 63) / 64) * 8);
+    L.fminus = off;
+    off += round256(((n + 63) / 64) * 8);
+    L.compress_ws = off;
+    off += round256(compress_layout(MMV_FLAGS_PACKED32, n).total);
+    L.w = off;
+    off += round256((cap < n ? cap : n) * 4 + 16);
+    L.total = off;
+    return L;
+}
+struct SscrLayout {
+    size_t scan_ws_x, scan_ws_f, fhat, f8, packed, fminus, compress_ws, w, total;
+};
+SscrLayout sscr_layout(mmv_dtype dt, mmv_flag_fmt ff, uint64_t n) {
+    SscrLayout L;
+    size_t off = 0;
+    L.scan_ws_x = off;
+    off += round256(ws_layout(MMV_OP_SCAN, dt, MMV_FLAGS_PACKED32, n).total);
+    L.scan_ws_f = off;
+    off += round256(ws_layout(MMV_OP_SCAN, MMV_I8_I32, MMV_FLAGS_PACKED32, n).total);
+    L.fhat = off;
+    off += round256(n * 4);
+    L.f8 = off;
+    off += round256(n + 16);   // flags as one 0 / 1 byte per element for SCAN(f)
+    L.packed = off;
+    if (ff == MMV_FLAGS_U8) off += round256(((n + 63) / 64) * 8);
+    L.fminus = off;
+    off += round256(((n + 63) / 64) * 8);
+    L.compress_ws = off;
+    off += round256(compress_layout(MMV_FLAGS_PACKED32, n).total);
+    L.w = off;
+    off += round256(n * 4 + 16);   // one entry per segment, at most n
+    L.total = off;
+    return L;
+}
+// CSR SpMV: the main kernel's workspace (flags over the non-zeros included), the mask of rows
+// with entries, their indices (rowmap) and the workspace of the COMPRESS that makes them.
+struct CsrLayout {
+    size_t main_ws, rowmask, rowmap, rowcount, compress_ws, total;
+};
+CsrLayout csr_layout(uint64_t n_rows, uint64_t nnz) {
+    CsrLayout L;
+    size_t off = 0;
+    L.main_ws = off;
+    off += round256(ws_layout(MMV_OP_SPMV_CSR, MMV_F32_F32, MMV_FLAGS_PACKED32, nnz).total);
+    L.rowmask = off;
+    off += round256(((n_rows + 63) / 64) * 8);
+    L.rowmap = off;
+    off += round256(n_rows * 4 + 16);
+    L.rowcount = off;
+    off += 256;
+    L.compress_ws = off;
+    off += round256(compress_layout(MMV_FLAGS_PACKED32, n_rows).total);
     L.total = off;
     return L;
 }
@@ -1156,6 +1472,7 @@ int grid_for(uint64_t items_per_thread_total) {
 bool valid_dtype(int dt) { return dt >= 0 && dt <= 3; }
 bool valid_ff(int ff) { return ff == 0 || ff == 1; }
 bool valid_variant(int v) { return v == 0 || v == 1; }
+bool valid_elem(int et) { return et == 0 || et == 1; }
 constexpr uint64_t kMaxN = 1ull << 40;
 
 // Common part of scan and sum: checks, workspace reset, flag packing.
@@ -1189,6 +1506,92 @@ mmv_status prepare(mmv_op op, const void *d_x, const void *d_flags, uint64_t n, 
     return MMV_OK;
 }
 
+// Turns timing events off for the sub-calls of a composition (each would re-record them).
+struct EventsOff {
+    hipEvent_t a, b;
+    EventsOff() : a(tl_ev_start), b(tl_ev_stop) { tl_ev_start = tl_ev_stop = nullptr; }
+    ~EventsOff() {
+        tl_ev_start = a;
+        tl_ev_stop = b;
+    }
+};
+
+// SCAN on an input that is already checked; first_one makes element 0 count as 1 (flag bytes).
+mmv_status scan_impl(const void *d_x, uint64_t n, void *d_z, mmv_dtype dt, mmv_variant v, void *d_ws,
+                     size_t ws_bytes, hipStream_t s, bool first_one) {
+    const WsLayout L = ws_layout(MMV_OP_SCAN, dt, MMV_FLAGS_PACKED32, n);
+    if (((uintptr_t)d_ws & 255u) != 0 || ws_bytes < L.total) return MMV_ERR_WORKSPACE;
+    char *ws = (char *)d_ws;
+    Params P = {};
+    P.x = d_x;
+    P.n = n;
+    P.z = d_z;
+    P.hdr = (uint32_t *)ws;
+    P.desc_v = (uint64_t *)(ws + L.desc_v);
+    P.first_one = first_one ? 1u : 0u;
+    const uint64_t zero_words = L.total / 4;
+    fill_zero_kernel<<<grid_for(zero_words), 256, 0, s>>>((uint32_t *)ws, zero_words, nullptr, 0);
+    if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
+    return launch_dt<kPlainScan>(P, dt, v, s) == hipSuccess ? MMV_OK : MMV_ERR_HIP;
+}
+
+// COMPRESS on checked arguments; d_x == nullptr compresses the positions.
+mmv_status compress_impl(const void *d_x, const void *d_mask, uint64_t n, void *d_out, uint64_t out_capacity,
+                         uint64_t *d_count, mmv_flag_fmt ff, void *d_ws, size_t ws_bytes, hipStream_t s) {
+    const CompressLayout L = compress_layout(ff, n);
+    if (((uintptr_t)d_ws & 255u) != 0 || ws_bytes < L.total) return MMV_ERR_WORKSPACE;
+    if (L.tiles > 0x7fffffffull) return MMV_ERR_INVALID_ARG;
+    char *ws = (char *)d_ws;
+    const uint64_t zero_words = L.packed / 4;
+    fill_zero_kernel<<<grid_for(zero_words), 256, 0, s>>>((uint32_t *)ws, zero_words, nullptr, 0);
+    if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
+    const uint32_t *mw = (const uint32_t *)d_mask;
+    if (ff == MMV_FLAGS_U8) {
+        const uint64_t nwords = (n + 31) / 32;
+        uint32_t *packed = (uint32_t *)(ws + L.packed);
+        pack_flags_kernel<<<grid_for(nwords), 256, 0, s>>>((const uint8_t *)d_mask, n, packed, nwords);
+        if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
+        mw = packed;
+    }
+    if (tl_ev_start && hipEventRecord(tl_ev_start, s) != hipSuccess) return MMV_ERR_HIP;
+    compress_kernel<<<(unsigned)L.tiles, kCompressWaves * 64, 0, s>>>(
+        (const uint32_t *)d_x, mw, n, (uint32_t *)d_out, out_capacity, d_count, (uint32_t *)ws,
+        (uint64_t *)(ws + L.desc), (uint32_t)L.tiles);
+    const hipError_t e = hipGetLastError();
+    if (tl_ev_stop && hipEventRecord(tl_ev_stop, s) != hipSuccess) return MMV_ERR_HIP;
+    return e == hipSuccess ? MMV_OK : MMV_ERR_HIP;
+}
+
+mmv_status diff_impl(const void *d_x, uint64_t n, void *d_z, mmv_elem et, hipStream_t s,
+                     const uint64_t *d_limit = nullptr) {
+    const uint64_t blocks = (n + 1023) / 1024;
+    if (blocks > 0x7fffffffull) return MMV_ERR_INVALID_ARG;
+    if (tl_ev_start && hipEventRecord(tl_ev_start, s) != hipSuccess) return MMV_ERR_HIP;
+    if (et == MMV_ELEM_I32)
+        diff_kernel<uint32_t><<<(unsigned)blocks, 256, 0, s>>>((const uint32_t *)d_x, n, (uint32_t *)d_z, d_limit);
+    else
+        diff_kernel<float><<<(unsigned)blocks, 256, 0, s>>>((const uint32_t *)d_x, n, (uint32_t *)d_z, d_limit);
+    const hipError_t e = hipGetLastError();
+    if (tl_ev_stop && hipEventRecord(tl_ev_stop, s) != hipSuccess) return MMV_ERR_HIP;
+    return e == hipSuccess ? MMV_OK : MMV_ERR_HIP;
+}
+
+mmv_status revert_impl(const void *d_xhat, const int32_t *d_fhat, const void *d_w, uint64_t n, uint64_t nw,
+                       void *d_z, mmv_elem et, hipStream_t s) {
+    const uint64_t blocks = (n + 1023) / 1024;
+    if (blocks > 0x7fffffffull) return MMV_ERR_INVALID_ARG;
+    if (tl_ev_start && hipEventRecord(tl_ev_start, s) != hipSuccess) return MMV_ERR_HIP;
+    if (et == MMV_ELEM_I32)
+        revert_kernel<uint32_t><<<(unsigned)blocks, 256, 0, s>>>((const uint32_t *)d_xhat, d_fhat, (const uint32_t *)d_w,
+                                                                  n, nw, (uint32_t *)d_z, nullptr);
+    else
+        revert_kernel<float><<<(unsigned)blocks, 256, 0, s>>>((const uint32_t *)d_xhat, d_fhat, (const uint32_t *)d_w, n,
+                                                               nw, (uint32_t *)d_z, nullptr);
+    const hipError_t e = hipGetLastError();
+    if (tl_ev_stop && hipEventRecord(tl_ev_stop, s) != hipSuccess) return MMV_ERR_HIP;
+    return e == hipSuccess ? MMV_OK : MMV_ERR_HIP;
+}
+
 }  // namespace
 
 // ---- C ABI ------------------------------------------------------------------------------------------------------
@@ -1196,8 +1599,23 @@ mmv_status prepare(mmv_op op, const void *d_x, const void *d_flags, uint64_t n, 
 extern "C" {
 
 size_t mmv_workspace_bytes(mmv_op op, mmv_dtype dt, mmv_flag_fmt ff, uint64_t n) {
-    if ((int)op < 0 || (int)op > 2 || !valid_dtype(dt) || !valid_ff(ff) || n > kMaxN) return 0;
-    return ws_layout(op, op == MMV_OP_SPMV_COO ? MMV_F32_F32 : dt, ff, n).total;
+    if (!valid_dtype(dt) || !valid_ff(ff) || n > kMaxN) return 0;
+    switch (op) {
+        case MMV_OP_SEGSCAN:
+        case MMV_OP_SEGSUM:
+        case MMV_OP_SCAN: return ws_layout(op, dt, ff, n).total;
+        case MMV_OP_SPMV_COO: return ws_layout(op, MMV_F32_F32, ff, n).total;
+        case MMV_OP_COMPRESS: return compress_layout(ff, n).total;
+        case MMV_OP_SEGSUM_SCD: return scd_layout(dt, ff, n, n).total;
+        case MMV_OP_SEGSCAN_SSCR: return sscr_layout(dt, ff, n).total;
+        case MMV_OP_SPMV_CSR: return 0;  // two sizes: see mmv_spmv_csr_workspace_bytes
+    }
+    return 0;
+}
+
+size_t mmv_spmv_csr_workspace_bytes(uint64_t n_rows, uint64_t nnz) {
+    if (n_rows >= (1ull << 31) || nnz >= (1ull << 31)) return 0;
+    return csr_layout(n_rows, nnz).total;
 }
 
 mmv_status mmv_segscan(const void *d_x, const void *d_flags, uint64_t n, void *d_z, mmv_dtype dt, mmv_flag_fmt ff,
@@ -1217,7 +1635,7 @@ mmv_status mmv_segscan(const void *d_x, const void *d_flags, uint64_t n, void *d
 mmv_status mmv_segsum(const void *d_x, const void *d_flags, uint64_t n, void *d_out, uint64_t out_capacity,
                       uint64_t *d_nseg, mmv_dtype dt, mmv_flag_fmt ff, mmv_variant v, void *d_ws, size_t ws_bytes,
                       void *hip_stream) {
-    if (!valid_dtype(dt) || !valid_ff(ff) || !valid_variant(v)) return MMV_ERR_INVALID_ARG;
+    if (!valid_dtype(dt) || !valid_ff(ff) || !valid_variant(v) || n > kMaxN) return MMV_ERR_INVALID_ARG;
     if (!d_nseg) return MMV_ERR_NULL;
     hipStream_t s = (hipStream_t)hip_stream;
     if (n == 0) {
@@ -1273,6 +1691,182 @@ mmv_status mmv_spmv_coo(uint64_t n_rows, uint64_t n_cols, uint64_t nnz, const in
     row_flags_kernel<<<(unsigned)flag_blocks, 256, 0, s>>>(d_row, nnz, (uint32_t *)(ws + L.packed));
     if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
     return launch_seg<TSpmv, kSpmv>(P, v, s) == hipSuccess ? MMV_OK : MMV_ERR_HIP;
+}
+
+mmv_status mmv_scan(const void *d_x, uint64_t n, void *d_z, mmv_dtype dt, mmv_variant v, void *d_ws, size_t ws_bytes,
+                    void *hip_stream) {
+    if (!valid_dtype(dt) || !valid_variant(v) || n > kMaxN) return MMV_ERR_INVALID_ARG;
+    if (n == 0) return MMV_OK;
+    if (!d_x || !d_z || !d_ws) return MMV_ERR_NULL;
+    if (!aligned16(d_x) || !aligned16(d_z)) return MMV_ERR_INVALID_ARG;
+    if (d_z == d_x && dt != MMV_F32_F32) return MMV_ERR_INVALID_ARG;
+    return scan_impl(d_x, n, d_z, dt, v, d_ws, ws_bytes, (hipStream_t)hip_stream, false);
+}
+
+mmv_status mmv_compress(const void *d_x, const void *d_mask, uint64_t n, void *d_out, uint64_t out_capacity,
+                        uint64_t *d_count, mmv_flag_fmt ff, void *d_ws, size_t ws_bytes, void *hip_stream) {
+    if (!valid_ff(ff) || n > kMaxN) return MMV_ERR_INVALID_ARG;
+    if (!d_count) return MMV_ERR_NULL;
+    if ((uintptr_t)d_count & 7u) return MMV_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)hip_stream;
+    if (n == 0) {
+        fill_zero_kernel<<<1, 256, 0, s>>>((uint32_t *)d_count, 2, nullptr, 0);
+        return hipGetLastError() == hipSuccess ? MMV_OK : MMV_ERR_HIP;
+    }
+    if (!d_mask || !d_ws || (!d_out && out_capacity > 0)) return MMV_ERR_NULL;
+    if (!aligned16(d_x) || !aligned16(d_mask) || !aligned16(d_out)) return MMV_ERR_INVALID_ARG;
+    return compress_impl(d_x, d_mask, n, d_out, out_capacity, d_count, ff, d_ws, ws_bytes, s);
+}
+
+mmv_status mmv_diff(const void *d_x, uint64_t n, void *d_z, mmv_elem et, void *hip_stream) {
+    if (!valid_elem(et) || n > kMaxN) return MMV_ERR_INVALID_ARG;
+    if (n == 0) return MMV_OK;
+    if (!d_x || !d_z) return MMV_ERR_NULL;
+    if (!aligned16(d_x) || !aligned16(d_z) || d_x == d_z) return MMV_ERR_INVALID_ARG;
+    return diff_impl(d_x, n, d_z, et, (hipStream_t)hip_stream);
+}
+
+mmv_status mmv_revert(const void *d_xhat, const int32_t *d_fhat, const void *d_w, uint64_t n, uint64_t nw,
+                      void *d_z, mmv_elem et, void *hip_stream) {
+    if (!valid_elem(et) || n > kMaxN) return MMV_ERR_INVALID_ARG;
+    if (n == 0) return MMV_OK;
+    if (!d_xhat || !d_fhat || !d_z || (!d_w && nw > 0)) return MMV_ERR_NULL;
+    if (!aligned16(d_xhat) || !aligned16(d_fhat) || !aligned16(d_z) || ((uintptr_t)d_w & 3u)) return MMV_ERR_INVALID_ARG;
+    return revert_impl(d_xhat, d_fhat, d_w, n, nw, d_z, et, (hipStream_t)hip_stream);
+}
+
+mmv_status mmv_segsum_scd(const void *d_x, const void *d_flags, uint64_t n, void *d_out, uint64_t out_capacity,
+                          uint64_t *d_nseg, mmv_dtype dt, mmv_flag_fmt ff, mmv_variant v, void *d_ws, size_t ws_bytes,
+                          void *hip_stream) {
+    if (!valid_dtype(dt) || !valid_ff(ff) || !valid_variant(v) || n > kMaxN) return MMV_ERR_INVALID_ARG;
+    if (!d_nseg) return MMV_ERR_NULL;
+    hipStream_t s = (hipStream_t)hip_stream;
+    if (n == 0) {
+        fill_zero_kernel<<<1, 256, 0, s>>>((uint32_t *)d_nseg, 2, nullptr, 0);
+        return hipGetLastError() == hipSuccess ? MMV_OK : MMV_ERR_HIP;
+    }
+    if (!d_x || !d_flags || !d_ws || (!d_out && out_capacity > 0)) return MMV_ERR_NULL;
+    if (!aligned16(d_x) || !aligned16(d_flags) || !aligned16(d_out) || ((uintptr_t)d_nseg & 7u)) return MMV_ERR_INVALID_ARG;
+    const ScdLayout L = scd_layout(dt, ff, n, out_capacity);
+    if (((uintptr_t)d_ws & 255u) != 0 || ws_bytes < L.total) return MMV_ERR_WORKSPACE;
+    char *ws = (char *)d_ws;
+    EventsOff quiet;
+    const uint64_t nwords = (n + 31) / 32;
+    const uint64_t cap = out_capacity < n ? out_capacity : n;
+    // 1. speculative scan of the whole vector
+    mmv_status st = scan_impl(d_x, n, ws + L.xhat, dt, v, ws + L.scan_ws, L.xhat - L.scan_ws, s, false);
+    if (st != MMV_OK) return st;
+    // 2. end markers f^- (from packed flags)
+    const uint32_t *fw = (const uint32_t *)d_flags;
+    if (ff == MMV_FLAGS_U8) {
+        uint32_t *packed = (uint32_t *)(ws + L.packed);
+        pack_flags_kernel<<<grid_for(nwords), 256, 0, s>>>((const uint8_t *)d_flags, n, packed, nwords);
+        if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
+        fw = packed;
+    }
+    end_markers_kernel<<<grid_for(nwords), 256, 0, s>>>(fw, n, (uint32_t *)(ws + L.fminus), nwords);
+    if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
+    // 3. scanned values at the segment ends
+    st = compress_impl(ws + L.xhat, ws + L.fminus, n, ws + L.w, cap, d_nseg, MMV_FLAGS_PACKED32, ws + L.compress_ws,
+                       L.w - L.compress_ws, s);
+    if (st != MMV_OK) return st;
+    // 4. adjacent differences of the first min(nseg, capacity) of them
+    if (cap == 0) return MMV_OK;
+    return diff_impl(ws + L.w, cap, d_out, dt == MMV_I8_I32 ? MMV_ELEM_I32 : MMV_ELEM_F32, s, d_nseg);
+}
+
+mmv_status mmv_segscan_sscr(const void *d_x, const void *d_flags, uint64_t n, void *d_z, mmv_dtype dt, mmv_flag_fmt ff,
+                            mmv_variant v, void *d_ws, size_t ws_bytes, void *hip_stream) {
+    if (!valid_dtype(dt) || !valid_ff(ff) || !valid_variant(v) || n > kMaxN) return MMV_ERR_INVALID_ARG;
+    if (n == 0) return MMV_OK;
+    if (!d_x || !d_flags || !d_z || !d_ws) return MMV_ERR_NULL;
+    if (!aligned16(d_x) || !aligned16(d_flags) || !aligned16(d_z)) return MMV_ERR_INVALID_ARG;
+    if (d_z == d_x && dt != MMV_F32_F32) return MMV_ERR_INVALID_ARG;
+    const SscrLayout L = sscr_layout(dt, ff, n);
+    if (((uintptr_t)d_ws & 255u) != 0 || ws_bytes < L.total) return MMV_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)hip_stream;
+    char *ws = (char *)d_ws;
+    EventsOff quiet;
+    const uint64_t nwords = (n + 31) / 32;
+    // flags in both encodings: bits for the end markers, 0 / 1 bytes for SCAN(f) (the caller's
+    // bytes may hold any non-zero value for "set", so they are not summed as they are)
+    const uint32_t *fw = (const uint32_t *)d_flags;
+    if (ff == MMV_FLAGS_U8) {
+        uint32_t *packed = (uint32_t *)(ws + L.packed);
+        pack_flags_kernel<<<grid_for(nwords), 256, 0, s>>>((const uint8_t *)d_flags, n, packed, nwords);
+        if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
+        fw = packed;
+    }
+    unpack_flags_kernel<<<grid_for((n + 3) / 4), 256, 0, s>>>(fw, n, (int8_t *)(ws + L.f8));
+    if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
+    const void *f8 = ws + L.f8;
+    // 1. (SCAN(x), SCAN(f)); the speculative scan goes straight to z and is reverted in place
+    mmv_status st = scan_impl(d_x, n, d_z, dt, v, ws + L.scan_ws_x, L.scan_ws_f - L.scan_ws_x, s, false);
+    if (st != MMV_OK) return st;
+    st = scan_impl(f8, n, ws + L.fhat, MMV_I8_I32, v, ws + L.scan_ws_f, L.fhat - L.scan_ws_f, s, true);
+    if (st != MMV_OK) return st;
+    // 2. end markers, 3. w = scanned values at the segment ends
+    end_markers_kernel<<<grid_for(nwords), 256, 0, s>>>(fw, n, (uint32_t *)(ws + L.fminus), nwords);
+    if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
+    uint64_t *d_nw = (uint64_t *)(ws + L.w);          // the count sits in front of w
+    st = compress_impl(d_z, ws + L.fminus, n, ws + L.w + 16, n, d_nw, MMV_FLAGS_PACKED32, ws + L.compress_ws,
+                       L.w - L.compress_ws, s);
+    if (st != MMV_OK) return st;
+    // 4. REVERT; every count is at most the number of segments, so nw = n is a safe bound
+    return revert_impl(d_z, (const int32_t *)(ws + L.fhat), ws + L.w + 16, n, n, d_z,
+                       dt == MMV_I8_I32 ? MMV_ELEM_I32 : MMV_ELEM_F32, s);
+}
+
+mmv_status mmv_spmv_csr(uint64_t n_rows, uint64_t n_cols, uint64_t nnz, const int32_t *d_rowptr, const int32_t *d_col,
+                        const float *d_val, const float *d_x, float *d_y, mmv_variant v, void *d_ws, size_t ws_bytes,
+                        void *hip_stream) {
+    if (!valid_variant(v) || n_rows >= (1ull << 31) || n_cols >= (1ull << 31) || nnz >= (1ull << 31))
+        return MMV_ERR_INVALID_ARG;
+    if (n_rows == 0) return MMV_OK;
+    if (!d_y) return MMV_ERR_NULL;
+    if (!aligned16(d_y)) return MMV_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)hip_stream;
+    if (nnz == 0) {
+        fill_zero_kernel<<<grid_for(n_rows), 256, 0, s>>>((uint32_t *)d_y, n_rows, nullptr, 0);
+        return hipGetLastError() == hipSuccess ? MMV_OK : MMV_ERR_HIP;
+    }
+    if (!d_rowptr || !d_col || !d_val || !d_x || !d_ws) return MMV_ERR_NULL;
+    if (!aligned16(d_rowptr) || !aligned16(d_col) || !aligned16(d_val) || !aligned16(d_x)) return MMV_ERR_INVALID_ARG;
+    const CsrLayout C = csr_layout(n_rows, nnz);
+    if (((uintptr_t)d_ws & 255u) != 0 || ws_bytes < C.total) return MMV_ERR_WORKSPACE;
+    char *ws = (char *)d_ws;
+    const WsLayout L = ws_layout(MMV_OP_SPMV_CSR, MMV_F32_F32, MMV_FLAGS_PACKED32, nnz);
+    // zero: the main kernel's header, descriptors and flag words; y
+    const uint64_t zero_words = L.total / 4;
+    fill_zero_kernel<<<grid_for(zero_words > n_rows ? zero_words : n_rows), 256, 0, s>>>((uint32_t *)ws, zero_words,
+                                                                                      (uint32_t *)d_y, n_rows);
+    if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
+    // segment-start flags over the non-zeros and the mask of rows that have entries
+    uint32_t *fw = (uint32_t *)(ws + C.main_ws + L.packed);
+    const uint64_t row_blocks = (n_rows + 255) / 256;
+    csr_flags_kernel<<<(unsigned)row_blocks, 256, 0, s>>>(d_rowptr, n_rows, fw, (uint32_t *)(ws + C.rowmask));
+    if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
+    // rowmap = COMPRESS(0 .. n_rows - 1, rowmask): the k-th segment belongs to row rowmap[k]
+    {
+        EventsOff quiet;
+        const mmv_status st = compress_impl(nullptr, ws + C.rowmask, n_rows, ws + C.rowmap, n_rows,
+                                            (uint64_t *)(ws + C.rowcount), MMV_FLAGS_PACKED32, ws + C.compress_ws,
+                                            C.total - C.compress_ws, s);
+        if (st != MMV_OK) return st;
+    }
+    Params P = {};
+    P.x = d_val;
+    P.n = nnz;
+    P.col = d_col;
+    P.xv = d_x;
+    P.y = d_y;
+    P.rowmap = (const uint32_t *)(ws + C.rowmap);
+    P.out_cap = n_rows;
+    P.hdr = (uint32_t *)(ws + C.main_ws);
+    P.desc_v = (uint64_t *)(ws + C.main_ws + L.desc_v);
+    P.desc_c = (uint64_t *)(ws + C.main_ws + L.desc_c);
+    P.fw = fw;
+    return launch_seg<TSpmv, kSpmvCsr>(P, v, s) == hipSuccess ? MMV_OK : MMV_ERR_HIP;
 }
 
 mmv_status mmv_workspace_status(const void *d_ws, void *hip_stream, uint32_t *h_status) {
@@ -1337,8 +1931,10 @@ const char *mmv_status_string(mmv_status s) {
 }
 
 uint32_t mmv_tile_elems(mmv_op op, mmv_dtype dt, uint64_t n) {
-    if ((int)op < 0 || (int)op > 2 || !valid_dtype(dt)) return 0;
-    const TilePlan p = tile_plan(op, op == MMV_OP_SPMV_COO ? MMV_F32_F32 : dt, n);
+    if (!valid_dtype(dt)) return 0;
+    if (op == MMV_OP_COMPRESS) return kCompressTile;
+    if (op != MMV_OP_SEGSCAN && op != MMV_OP_SEGSUM && op != MMV_OP_SCAN && !is_spmv(op)) return 0;
+    const TilePlan p = tile_plan(op, is_spmv(op) ? MMV_F32_F32 : dt, n);
     return p.big_tiles ? p.big_elems : p.tail_elems;
 }
 

@@ -35,7 +35,7 @@ def test_host_only_entry_points(libmmvseg_path):
         assert t % 2048 == 0 and 0 < t <= tile
     small = B.mmv_tile_elems(B.MMV_OP_SEGSCAN, B.MMV_I8_I32, 1000)                # short inputs: small tiles
     assert small % 2048 == 0 and small <= tile
-    assert B.mmv_tile_elems(B.MMV_OP_SEGSCAN, 9, big) == 0 and B.mmv_tile_elems(7, B.MMV_I8_I32, big) == 0
+    assert B.mmv_tile_elems(B.MMV_OP_SEGSCAN, 9, big) == 0 and B.mmv_tile_elems(99, B.MMV_I8_I32, big) == 0
     assert lib.mmv_status_string(0) == b"ok"
     assert lib.mmv_status_string(4).startswith(b"workspace")
     # header + one 8-byte descriptor per tile, rounded to 256 bytes
@@ -49,7 +49,16 @@ def test_host_only_entry_points(libmmvseg_path):
     assert ssum == 256 + 2 * (scan - 256)                                          # second descriptor array
     assert B.mmv_workspace_bytes(B.MMV_OP_SEGSCAN, B.MMV_I8_I32, B.MMV_FLAGS_U8, n) == scan + n // 8
     assert B.mmv_workspace_bytes(B.MMV_OP_SEGSCAN, 7, B.MMV_FLAGS_U8, n) == 0      # bad dtype
-    assert B.mmv_workspace_bytes(5, B.MMV_I8_I32, B.MMV_FLAGS_U8, n) == 0          # bad op
+    assert B.mmv_workspace_bytes(99, B.MMV_I8_I32, B.MMV_FLAGS_U8, n) == 0         # bad op
+    # the un-fused compositions need room for their intermediate vectors (4 bytes per element each)
+    assert B.mmv_workspace_bytes(B.MMV_OP_SCAN, B.MMV_I8_I32, B.MMV_FLAGS_U8, n) == scan
+    assert B.mmv_workspace_bytes(B.MMV_OP_SEGSUM_SCD, B.MMV_I8_I32, B.MMV_FLAGS_PACKED32, n) >= 8 * n
+    assert B.mmv_workspace_bytes(B.MMV_OP_SEGSCAN_SSCR, B.MMV_I8_I32, B.MMV_FLAGS_PACKED32, n) >= 9 * n
+    assert B.mmv_workspace_bytes(B.MMV_OP_SPMV_CSR, B.MMV_I8_I32, B.MMV_FLAGS_PACKED32, n) == 0
+    csr = B.mmv_spmv_csr_workspace_bytes(1 << 20, 1 << 25)
+    assert csr % 256 == 0 and (1 << 25) // 8 + 4 * (1 << 20) <= csr <= 16 << 20
+    assert B.mmv_spmv_csr_workspace_bytes(1 << 31, 4) == 0
+    assert B.mmv_tile_elems(B.MMV_OP_COMPRESS, B.MMV_I8_I32, n) == 32768
 
 
 def test_argument_errors_are_caught_on_the_host(libmmvseg_path):
@@ -79,6 +88,28 @@ def test_argument_errors_are_caught_on_the_host(libmmvseg_path):
     assert lib.mmv_segscan(a16, a16, 10, a16 * 2, B.MMV_I8_I32, B.MMV_FLAGS_U8, 0, (a16 << 4) + 16, 4096, None) == WORKSPACE
     assert lib.mmv_spmv_coo(1 << 31, 4, 4, a16, a16, a16, a16, a16, 0, a16 << 4, 4096, None) == INVALID
     assert lib.mmv_spmv_coo(4, 4, 4, a16, None, a16, a16, a16, 0, a16 << 4, 4096, None) == NULL
+    # the primitives, the compositions and the CSR entry point
+    assert lib.mmv_scan(None, 0, None, B.MMV_I8_I32, 0, None, 0, None) == OK
+    assert lib.mmv_scan(a16, 10, None, B.MMV_I8_I32, 0, a16 << 4, 4096, None) == NULL
+    assert lib.mmv_scan(a16, 10, a16, B.MMV_I8_I32, 0, a16 << 4, 4096, None) == INVALID      # aliasing
+    assert lib.mmv_scan(a16, 10, a16 * 2, B.MMV_I8_I32, 0, a16 << 4, 16, None) == WORKSPACE
+    assert lib.mmv_compress(a16, a16, 10, a16 * 2, 10, None, B.MMV_FLAGS_U8, a16 << 4, 4096, None) == NULL
+    assert lib.mmv_compress(a16, a16, 10, a16 * 2, 10, a16 + 4, B.MMV_FLAGS_U8, a16 << 4, 4096, None) == INVALID
+    assert lib.mmv_compress(a16, a16, 10, a16 * 2, 10, a16, 2, a16 << 4, 4096, None) == INVALID
+    assert lib.mmv_compress(a16, a16, 10, a16 * 2, 10, a16, B.MMV_FLAGS_U8, a16 << 4, 16, None) == WORKSPACE
+    assert lib.mmv_diff(a16, 10, a16, B.MMV_ELEM_I32, None) == INVALID                         # aliasing
+    assert lib.mmv_diff(a16, 10, a16 * 2, 2, None) == INVALID
+    assert lib.mmv_diff(None, 0, None, B.MMV_ELEM_F32, None) == OK
+    assert lib.mmv_revert(a16, None, a16, 10, 3, a16, B.MMV_ELEM_I32, None) == NULL
+    assert lib.mmv_revert(a16, a16, a16, 10, 3, a16, 7, None) == INVALID
+    assert lib.mmv_segsum_scd(a16, a16, 10, a16, 10, None, B.MMV_I8_I32, B.MMV_FLAGS_U8, 0, a16 << 4, 1 << 20, None) == NULL
+    assert lib.mmv_segsum_scd(a16, a16, 10, a16, 10, a16, B.MMV_I8_I32, B.MMV_FLAGS_U8, 0, a16 << 4, 16, None) == WORKSPACE
+    assert lib.mmv_segscan_sscr(a16, a16, 10, a16 * 2, B.MMV_I8_I32, B.MMV_FLAGS_U8, 0, a16 << 4, 16, None) == WORKSPACE
+    assert lib.mmv_segscan_sscr(a16, a16, 10, a16, B.MMV_I8_I32, B.MMV_FLAGS_U8, 0, a16 << 4, 1 << 20, None) == INVALID
+    assert lib.mmv_spmv_csr(0, 0, 0, None, None, None, None, None, 0, None, 0, None) == OK
+    assert lib.mmv_spmv_csr(4, 4, 4, None, a16, a16, a16, a16, 0, a16 << 4, 1 << 20, None) == NULL
+    assert lib.mmv_spmv_csr(4, 4, 1 << 31, a16, a16, a16, a16, a16, 0, a16 << 4, 1 << 20, None) == INVALID
+    assert lib.mmv_spmv_csr(4, 4, 4, a16, a16, a16, a16, a16, 0, a16 << 4, 16, None) == WORKSPACE
     assert lib.mmv_stream_copy(a16, 24, a16, 32, None) == INVALID
     assert lib.mmv_workspace_status(None, None, None) == NULL
 
