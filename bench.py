@@ -114,6 +114,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--log2n", type=int, default=28, help="vector length of the headline workload")
     ap.add_argument("--variant", default="mfma", choices=["mfma", "shuffle"])
+    ap.add_argument("--input-copies", type=int, default=3,
+                    help="the steps rotate over this many copies of the inputs (3 x 288 MiB is more than the "
+                         "256 MiB memory-side cache, so no step finds its inputs cached from an earlier one)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--report", default=None, help="also time every workload and write JSON lines here")
     ap.add_argument("--copy-only", action="store_true",
@@ -145,11 +148,15 @@ def main() -> int:
     x, f = W.segscan_i8_uniform_len(n)
     xt = torch.from_numpy(x).cuda()
     ft = torch.from_numpy(W.pack_flags(f).view(np.int32)).cuda()
+    copies = [(xt, ft)] + [(xt.clone(), ft.clone()) for _ in range(max(1, args.input_copies) - 1)]
     zt = torch.empty(n, dtype=torch.int32, device="cuda")
     ws = B.new_workspace(B.MMV_OP_SEGSCAN, B.MMV_I8_I32, B.MMV_FLAGS_PACKED32, n)
+    turn = [0]
 
     def step():
-        B.mmv_segscan(xt, ft, n=n, z=zt, variant=args.variant, ws=ws)
+        xk, fk = copies[turn[0] % len(copies)]
+        turn[0] += 1
+        B.mmv_segscan(xk, fk, n=n, z=zt, variant=args.variant, ws=ws)
 
     ms_per_step, kernel_ms = time_steps(step, args.steps, args.warmup, events)
     assert B.mmv_workspace_status(ws) == 0
@@ -173,6 +180,7 @@ def main() -> int:
                         "segment lengths U{1..4096}, bit-packed flags, seed %d"
                         % (args.log2n, W.SEEDS["segscan_i8_uniform_len"]),
             "variant": args.variant,
+            "input_copies_rotated": len(copies),
             "tile_elems": B.mmv_tile_elems(),
             "kernel_ms": kernel_ms,
             "hbm_frac_of_peak_whole_step": algo_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
@@ -196,6 +204,7 @@ def main() -> int:
             "sample": "the whole n=2^%d workload, sequential C loop (gcc -O2), best of 3 runs, "
                       "host has %d logical CPUs" % (args.log2n, os.cpu_count()),
         }
+    del copies[1:]
     if args.report:
         write_report(args, events)
     print(json.dumps(line))
@@ -305,6 +314,109 @@ def write_report(args, events: HipEvents) -> None:
     for variant in ("mfma", "shuffle"):
         run("5 stress segscan f32 n=2^30 " + variant, n, n * 8 + n // 8,
             lambda: B.mmv_segscan(xt, ft, n=n, z=zt, variant=variant, ws=ws), ws, steps=20)
+
+    del xt, ft, zt
+    torch.cuda.empty_cache()
+
+    def call_ms(fn, steps=30, warmup=3):
+        """Whole call (reset kernels included) timed with stream events; mean over `steps`."""
+        for _ in range(warmup):
+            fn()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(steps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / steps
+
+    # unsegmented scan (Algorithm Scan) next to the segmented one, n = 2^28
+    n = 1 << args.log2n
+    x, _ = W.segscan_i8_uniform_len(n)
+    xt = torch.from_numpy(x).cuda()
+    zt = torch.empty(n, dtype=torch.int32, device="cuda")
+    ws = B.new_workspace(B.MMV_OP_SCAN, B.MMV_I8_I32, B.MMV_FLAGS_PACKED32, n)
+    for variant in ("mfma", "shuffle"):
+        run("scan (unsegmented) i8 n=2^%d %s" % (args.log2n, variant), n, n * 5,
+            lambda: B.mmv_scan(xt, n=n, z=zt, variant=variant, ws=ws), ws, steps=30)
+    xh = torch.from_numpy(np.random.default_rng(3).standard_normal(n, dtype=np.float32).astype(np.float16)).cuda()
+    zf = zt.view(torch.float32)
+    wsh = B.new_workspace(B.MMV_OP_SCAN, B.MMV_F16_F32, B.MMV_FLAGS_PACKED32, n)
+    for variant in ("mfma", "shuffle"):
+        run("scan (unsegmented) f16 n=2^%d %s" % (args.log2n, variant), n, n * 6,
+            lambda: B.mmv_scan(xh, n=n, z=zf, variant=variant, ws=wsh), wsh, steps=30)
+    del xh, zf
+
+    # the primitives of Algorithms SCD / SSCR one by one, the un-fused compositions and the fused
+    # calls, on uniformly random flags at the densities the paper's breakdown uses
+    for density in (1e-3, 1e-2):
+        f = W.uniform_density_flags(n, density, 78)
+        fm = np.concatenate([f[1:], np.ones(1, dtype=np.uint8)])
+        nseg = int(f.sum())
+        ft = torch.from_numpy(W.pack_flags(f).view(np.int32)).cuda()
+        fmt = torch.from_numpy(W.pack_flags(fm).view(np.int32)).cuda()
+        f8 = torch.from_numpy(f.view(np.int8)).cuda()
+        xhat = torch.empty(n, dtype=torch.int32, device="cuda")
+        fhat = torch.empty(n, dtype=torch.int32, device="cuda")
+        w = torch.empty(nseg + 16, dtype=torch.int32, device="cuda")
+        cnt = torch.empty(1, dtype=torch.int64, device="cuda")
+        out = torch.empty(nseg + 16, dtype=torch.int32, device="cuda")
+        wsc = B.new_workspace(B.MMV_OP_COMPRESS, B.MMV_I8_I32, B.MMV_FLAGS_PACKED32, n)
+        tag = "n=2^%d i8 density=%g" % (args.log2n, density)
+
+        def prim(name, fn, algo_bytes):
+            ms = call_ms(fn)
+            emit(workload="primitive %s %s" % (name, tag), n=n, ms=ms, gelem_s=n / ms / 1e6, algo_bytes=algo_bytes,
+                 gb_s=algo_bytes / ms / 1e6, frac_of_peak=algo_bytes / ms / 1e6 / HBM_PEAK_GBS)
+            return ms
+
+        t_scan = prim("SCAN(x) int8->int32", lambda: B.mmv_scan(xt, n=n, z=xhat, ws=ws), n * 5)
+        t_scanf = prim("SCAN(f) int8->int32", lambda: B.mmv_scan(f8, n=n, z=fhat, ws=ws), n * 5)
+        t_comp = prim("COMPRESS(xhat, f-)", lambda: B.mmv_compress(xhat, fmt, n, out=w, count=cnt, ws=wsc),
+                      n // 8 + nseg * 8)
+        t_diff = prim("DIFF(w)", lambda: B.mmv_diff(w, n=nseg, z=out), nseg * 8)
+        # SCAN(f) of flags that hold a 1 at position 0 is the count REVERT needs
+        t_rev = prim("REVERT", lambda: B.mmv_revert(xhat, fhat, w, n=n, nw=nseg, z=zt), n * 12)
+        wsd = B.new_workspace(B.MMV_OP_SEGSUM_SCD, B.MMV_I8_I32, B.MMV_FLAGS_PACKED32, n)
+        nsg = torch.empty(1, dtype=torch.int64, device="cuda")
+        t_scd = prim("SCD un-fused (segsum)", lambda: B.mmv_segsum_scd(xt, ft, n=n, out=out, nseg=nsg, ws=wsd),
+                     n + n // 8 + nseg * 4)
+        del wsd
+        wss = B.new_workspace(B.MMV_OP_SEGSUM, B.MMV_I8_I32, B.MMV_FLAGS_PACKED32, n)
+        t_sum = prim("fused mmv_segsum", lambda: B.mmv_segsum(xt, ft, n=n, out=out, nseg=nsg, ws=wss),
+                     n + n // 8 + nseg * 4)
+        wsr = B.new_workspace(B.MMV_OP_SEGSCAN_SSCR, B.MMV_I8_I32, B.MMV_FLAGS_PACKED32, n)
+        t_sscr = prim("SSCR un-fused (segscan)", lambda: B.mmv_segscan_sscr(xt, ft, n=n, z=zt, ws=wsr), n * 5 + n // 8)
+        del wsr
+        wsg = B.new_workspace(B.MMV_OP_SEGSCAN, B.MMV_I8_I32, B.MMV_FLAGS_PACKED32, n)
+        t_seg = prim("fused mmv_segscan", lambda: B.mmv_segscan(xt, ft, n=n, z=zt, ws=wsg), n * 5 + n // 8)
+        emit(workload="fusion summary " + tag, scd_over_fused=t_scd / t_sum, sscr_over_fused=t_sscr / t_seg,
+             compress_share_of_scd=t_comp / (t_scan + t_comp + t_diff),
+             compress_share_of_sscr=t_comp / (t_scan + t_scanf + t_comp + t_rev),
+             revert_share_of_sscr=t_rev / (t_scan + t_scanf + t_comp + t_rev))
+        del ft, fmt, f8, xhat, fhat, w, out
+    del xt, zt
+    torch.cuda.empty_cache()
+
+    # CSR SpMV: workload 4 through its row pointers, and the blocked sparse-attention matrices
+    rowptr = W.csr_rowptr(row, nr)
+    rpt, ct, vt, xvt = (torch.from_numpy(a).cuda() for a in (rowptr, col, val, xv))
+    wsv = torch.empty(B.mmv_spmv_csr_workspace_bytes(nr, nnz), dtype=torch.uint8, device="cuda")
+    ms = call_ms(lambda: B.mmv_spmv_csr(nr, nr, rpt, ct, vt, xvt, y=yt, ws=wsv))
+    emit(workload="4 spmv csr 2^20 x 2^20 nnz=%d zipf(1.5)" % nnz, nnz=nnz, ms=ms, gnnz_s=nnz / ms / 1e6,
+         algo_bytes=nnz * 8 + 3 * nr * 4, gb_s=(nnz * 8 + 3 * nr * 4) / ms / 1e6)
+    del rpt, ct, vt, xvt, wsv
+    na = 1 << 16
+    for block in (2, 4, 16, 64):
+        for n_random in (2, 4, 8):
+            rp, c, v, xa = W.blocked_sparse_attention(na, block=block, n_random=n_random)
+            nz = len(v)
+            rpt, ct, vt, xat = (torch.from_numpy(a).cuda() for a in (rp, c, v, xa))
+            ya = torch.empty(na, dtype=torch.float32, device="cuda")
+            wsv = torch.empty(B.mmv_spmv_csr_workspace_bytes(na, nz), dtype=torch.uint8, device="cuda")
+            ms = call_ms(lambda: B.mmv_spmv_csr(na, na, rpt, ct, vt, xat, y=ya, ws=wsv))
+            emit(workload="spmv csr sparse attention 65536^2 b-%d_r-%d" % (block, n_random), nnz=nz, ms=ms,
+                 gnnz_s=nz / ms / 1e6, algo_bytes=nz * 8 + 3 * na * 4, gb_s=(nz * 8 + 3 * na * 4) / ms / 1e6)
 
     with open(args.report, "w") as fh:
         for r in rows:

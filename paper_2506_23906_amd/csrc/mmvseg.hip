@@ -53,6 +53,9 @@ namespace {
 #ifndef MMV_CPW_SPMV
 #define MMV_CPW_SPMV 1
 #endif
+#ifndef MMV_MIN_WAVES_PER_SIMD
+#define MMV_MIN_WAVES_PER_SIMD 4   // register budget: 512 / 4 = 128 VGPRs per lane
+#endif
 #ifndef MMV_MIN_TILES
 #define MMV_MIN_TILES 512   // workgroups resident at once: 2 per compute unit (LDS)
 #endif
@@ -108,7 +111,9 @@ struct Params {
     float *y;
     uint32_t *hdr;          // workspace header
     uint64_t *desc_v;       // value descriptors, one per tile
-    uint64_t *desc_c;       // count descriptors (sum)
+    uint64_t *desc_c;       // count descriptors (spmv csr)
+    const uint32_t *tile_count;  // sum: segment starts per tile (position 0 not counted), or ...
+    uint32_t count_is_prefix;    // ... their exclusive prefix sums already (long vectors)
     uint32_t num_tiles;
     uint32_t big_tiles;     // tiles [0, big_tiles) have the full number of chunks per wave ...
     uint32_t tail_cpw;      // ... the rest have this many (shorter tiles at the end shorten the tail)
@@ -392,34 +397,35 @@ template <> struct SpecMfma<TF32> {
     // In K-step ks half h supplies positions 16 h + 8 ks .. + 7 (the lane's own words 2 ks, 2 ks + 1).
     static __device__ __forceinline__ void run(const v4u *raw, int lane, float (&acc)[16]) {
         const int c = lane & 31, h = lane >> 5;
-        uint32_t hi[8], mid[8], lo[8];  // packed pairs of consecutive positions
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-#pragma unroll
-            for (int pr = 0; pr < 2; ++pr) {
-                uint32_t ph[2], pm[2], pl[2];
-#pragma unroll
-                for (int e = 0; e < 2; ++e) {
-                    const uint32_t xb = raw[q][2 * pr + e];
-                    ph[e] = xb & 0xFFFF0000u;
-                    const float r1 = from_bits<float>(xb) - from_bits<float>(ph[e]);
-                    pm[e] = to_bits(r1) & 0xFFFF0000u;
-                    pl[e] = to_bits(r1 - from_bits<float>(pm[e]));  // at most 8 significant bits left
-                }
-                hi[2 * q + pr] = __builtin_amdgcn_perm(ph[1], ph[0], 0x07060302u);
-                mid[2 * q + pr] = __builtin_amdgcn_perm(pm[1], pm[0], 0x07060302u);
-                lo[2 * q + pr] = __builtin_amdgcn_perm(pl[1], pl[0], 0x07060302u);
-            }
         v16f r = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
+            // the eight values of this K-step (words 2 ks and 2 ks + 1), split and packed in pairs
+            uint32_t hi[4], mid[4], lo[4];
+#pragma unroll
+            for (int q = 0; q < 2; ++q)
+#pragma unroll
+                for (int pr = 0; pr < 2; ++pr) {
+                    uint32_t ph[2], pm[2], pl[2];
+#pragma unroll
+                    for (int e = 0; e < 2; ++e) {
+                        const uint32_t xb = raw[2 * ks + q][2 * pr + e];
+                        ph[e] = xb & 0xFFFF0000u;
+                        const float r1 = from_bits<float>(xb) - from_bits<float>(ph[e]);
+                        pm[e] = to_bits(r1) & 0xFFFF0000u;
+                        pl[e] = to_bits(r1 - from_bits<float>(pm[e]));  // at most 8 significant bits left
+                    }
+                    hi[2 * q + pr] = __builtin_amdgcn_perm(ph[1], ph[0], 0x07060302u);
+                    mid[2 * q + pr] = __builtin_amdgcn_perm(pm[1], pm[0], 0x07060302u);
+                    lo[2 * q + pr] = __builtin_amdgcn_perm(pl[1], pl[0], 0x07060302u);
+                }
             v8s a;
 #pragma unroll
             for (int j = 0; j < 8; ++j) a[j] = (16 * h + 8 * ks + j <= c) ? (short)0x3F80 : (short)0;  // bf16 1.0
             const v8bf ab = __builtin_bit_cast(v8bf, a);
-            const v4u wl = {lo[4 * ks], lo[4 * ks + 1], lo[4 * ks + 2], lo[4 * ks + 3]};
-            const v4u wm = {mid[4 * ks], mid[4 * ks + 1], mid[4 * ks + 2], mid[4 * ks + 3]};
-            const v4u wh = {hi[4 * ks], hi[4 * ks + 1], hi[4 * ks + 2], hi[4 * ks + 3]};
+            const v4u wl = {lo[0], lo[1], lo[2], lo[3]};
+            const v4u wm = {mid[0], mid[1], mid[2], mid[3]};
+            const v4u wh = {hi[0], hi[1], hi[2], hi[3]};
             r = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ab, __builtin_bit_cast(v8bf, wl), r, 0, 0, 0);
             r = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ab, __builtin_bit_cast(v8bf, wm), r, 0, 0, 0);
             r = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ab, __builtin_bit_cast(v8bf, wh), r, 0, 0, 0);
@@ -612,7 +618,7 @@ template <int N, int M> __device__ __forceinline__ void rotate_rows(v4u (&a)[N][
 }
 
 template <typename TT, int kOp, bool kMfma>
-__global__ __launch_bounds__(TT::kWaves * 64, 4) void seg_kernel(Params P) {
+__global__ __launch_bounds__(TT::kWaves * 64, MMV_MIN_WAVES_PER_SIMD) void seg_kernel(Params P) {
     typedef typename TT::acc_t A;
     typedef typename TT::in_t In;
     constexpr int kWaves = TT::kWaves;
@@ -620,6 +626,10 @@ __global__ __launch_bounds__(TT::kWaves * 64, 4) void seg_kernel(Params P) {
     constexpr int K = 16 / TT::kEpl;             // 128-bit words per lane and 32x32 tile
     constexpr bool kScanLike = kOp == kScan || kOp == kPlainScan;   // every element is an output
     constexpr bool kCounts = kOp == kSum || kOp == kSpmvCsr;        // output index = segment ordinal
+    // where the count of the segments before the tile comes from: a table made by two small
+    // kernels before this one (sum: no chunk has to wait for it), or a second look-back (spmv csr)
+    constexpr bool kCountTable = kOp == kSum;
+    constexpr bool kCountLookback = kOp == kSpmvCsr;
     constexpr bool kProduct = kOp == kSpmv || kOp == kSpmvCsr;      // values are val * x[col]
 
     __shared__ __attribute__((aligned(16))) uint32_t s_rows[kWaves][kRowsPerChunk * kRowStride];
@@ -672,6 +682,21 @@ __global__ __launch_bounds__(TT::kWaves * 64, 4) void seg_kernel(Params P) {
     if constexpr (kOp == kPlainScan && sizeof(In) == 1) {
         // counting segment starts: position 0 always opens a segment (byte 0 of the first word, both layouts)
         if (P.first_one && tile == 0 && tid == 0) raw[0][0][0] = (raw[0][0][0] & ~0xFFu) | 1u;
+    }
+
+    if constexpr (kCountTable) {
+        // number of segment starts before my tile, while the loads are in flight: either the table
+        // holds the prefix sums already, or (few tiles) wave 1 adds up the counts of the tiles before
+        if (wave == 1) {
+            uint32_t c = 0;
+            if (P.count_is_prefix) {
+                c = P.tile_count[tile];
+            } else {
+                for (uint32_t i = lane; i < tile; i += 64) c += P.tile_count[i];
+                c = wave_sum(c);
+            }
+            if (lane == 0) s_carry_c = c;
+        }
     }
 
     // per chunk: exclusive segmented prefix of my row inside the chunk, and of the chunk inside
@@ -800,15 +825,20 @@ __global__ __launch_bounds__(TT::kWaves * 64, 4) void seg_kernel(Params P) {
     }
     wex_f = __builtin_amdgcn_readfirstlane(wex_f);
 
+    if constexpr (kCountTable) {
+        if (!P.count_is_prefix && tile == P.num_tiles - 1 && tid == 0) *P.nseg = (uint64_t)s_carry_c + tagg_c + 1u;
+    }
+
     // ---- step 5c, first half: publish this tile ----
     const bool final_now = tile == 0 || tagg_f;  // carry out does not depend on predecessors
     if (tid == 0) desc_store(P.desc_v + tile, final_now ? kStatusPrefix : kStatusAggregate, to_bits(tagg_v));
-    if (kCounts && tid == 64) desc_store(P.desc_c + tile, tile == 0 ? kStatusPrefix : kStatusAggregate, tagg_c);
+    if (kCountLookback && tid == 64) desc_store(P.desc_c + tile, tile == 0 ? kStatusPrefix : kStatusAggregate, tagg_c);
 
     // carry into my span (used only by rows with no flag before them in the tile); the carry of
     // the predecessor tiles is added once it is known
     A span_carry = wex_v;
     uint32_t count_carry = 0;
+    if constexpr (kCountTable) count_carry = s_carry_c;
 
     // ================= phase B: recompute, revert, add carries, store =================
 #pragma unroll 1
@@ -825,14 +855,13 @@ __global__ __launch_bounds__(TT::kWaves * 64, 4) void seg_kernel(Params P) {
                     __hip_atomic_store(&s_ready, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
                 }
             }
-            if (kCounts) {
+            if (kCountLookback) {
                 if (wave == 1) {
                     uint32_t carry = 0;
                     if (tile > 0) carry = lookback<uint32_t>(P.desc_c, (int)tile, lane, P.hdr);
                     if (lane == 0) {
                         if (tile > 0) desc_store(P.desc_c + tile, kStatusPrefix, carry + tagg_c);
                         s_carry_c = carry;
-                        if (kOp == kSum && tile == P.num_tiles - 1) *P.nseg = (uint64_t)carry + tagg_c + 1u;
                     }
                 }
                 __syncthreads();  // every output index needs the count carry
@@ -849,9 +878,9 @@ __global__ __launch_bounds__(TT::kWaves * 64, 4) void seg_kernel(Params P) {
         }
 #pragma unroll 1
         for (int c = 0; c < kCpw; ++c) {
-            // a chunk is "open" when no flag of the tile precedes it; the segmented sum treats
-            // every chunk as open because all its output indices wait for the count carry
-            const bool chunk_open = kCounts || !(wex_f || __builtin_amdgcn_readfirstlane(pre_f[0]));
+            // a chunk is "open" when no flag of the tile precedes it; with a count look-back
+            // every chunk is open because all its output indices wait for the count carry
+            const bool chunk_open = kCountLookback || !(wex_f || __builtin_amdgcn_readfirstlane(pre_f[0]));
             if (c < cpw_t && chunk_open == (pass == 1)) {
                 const uint64_t cb = wave_base + (uint64_t)c * kChunkElems;
                 const bool chunk_full = cb + kChunkElems <= n;
@@ -983,6 +1012,63 @@ __global__ __launch_bounds__(256) void fill_zero_kernel(uint32_t *a, uint64_t na
     for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < nb; i += stride) b[i] = 0;
 }
 
+// Segmented sum, step "scan of the end markers" of COMPRESS (proof of the SCD / SSCR theorem)
+// at tile granularity: workgroup b counts the segment starts inside tile b (position 0 is not
+// counted: it opens segment 0 whatever its flag says; bits at or beyond n are not counted).  The
+// same launch zeroes the header and the descriptors of the main kernel.
+__global__ __launch_bounds__(256) void count_tiles_kernel(uint32_t *zero, uint64_t zero_words, const uint32_t *fw,
+                                                          uint64_t n, uint32_t big_tiles, uint32_t big_elems,
+                                                          uint32_t tail_elems, uint32_t *cnt) {
+    __shared__ uint32_t s_part[4];
+    const uint32_t b = blockIdx.x, tid = threadIdx.x;
+    for (uint64_t i = (uint64_t)b * 256 + tid; i < zero_words; i += (uint64_t)gridDim.x * 256) zero[i] = 0;
+    const uint64_t base = b < big_tiles ? (uint64_t)b * big_elems
+                                        : (uint64_t)big_tiles * big_elems + (uint64_t)(b - big_tiles) * tail_elems;
+    const uint64_t elems = b < big_tiles ? big_elems : tail_elems;
+    const uint64_t end = base + elems < n ? base + elems : n;
+    uint32_t sum = 0;
+    for (uint64_t w = (base >> 5) + tid; w < ((end + 31) >> 5); w += 256) {   // tiles begin on word borders
+        uint32_t v = fw[w];
+        if (w == 0) v &= ~1u;
+        if ((w + 1) * 32 > n) v &= (1u << (uint32_t)(n - w * 32)) - 1u;
+        sum += __popc(v);
+    }
+    sum = wave_sum(sum);
+    if ((tid & 63) == 0) s_part[tid >> 6] = sum;
+    __syncthreads();
+    if (tid == 0) cnt[b] = s_part[0] + s_part[1] + s_part[2] + s_part[3];
+}
+
+// Exclusive prefix sums of the per-tile counts, in place, by one workgroup; the total (+ 1 for
+// segment 0) is the number of segments.
+__global__ __launch_bounds__(1024) void scan_counts_kernel(uint32_t *cnt, uint32_t num_tiles, uint64_t *nseg) {
+    __shared__ uint32_t s_wave[16];
+    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    uint32_t running = 0;
+    for (uint32_t base = 0; base < num_tiles; base += 1024) {
+        const uint32_t i = base + tid;
+        const uint32_t v = i < num_tiles ? cnt[i] : 0u;
+        uint32_t inc = v;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const uint32_t o = __shfl_up(inc, d);
+            if (lane >= (uint32_t)d) inc += o;
+        }
+        if (lane == 63) s_wave[wave] = inc;
+        __syncthreads();
+        uint32_t before = 0, total = 0;
+#pragma unroll
+        for (uint32_t w = 0; w < 16; ++w) {
+            if (w == wave) before = total;
+            total += s_wave[w];
+        }
+        if (i < num_tiles) cnt[i] = running + before + inc - v;
+        running += total;
+        __syncthreads();
+    }
+    if (tid == 0) *nseg = (uint64_t)running + 1u;
+}
+
 // One byte per element -> one bit per element; a thread builds one 32-bit word.
 __global__ __launch_bounds__(256) void pack_flags_kernel(const uint8_t *f, uint64_t n, uint32_t *words,
                                                          uint64_t nwords) {
@@ -1058,7 +1144,8 @@ __global__ __launch_bounds__(256) void unpack_flags_kernel(const uint32_t *fw, u
 // COMPRESS), found per tile from popcounts and across tiles by decoupled look-back.
 // A wave owns 4096 consecutive positions: lane j holds the 64-bit mask word j, and for every
 // word the wave reads only the selected entries (one coalesced load, skipped when the word is
-// empty) and writes them to consecutive output slots.
+// empty) and writes them to consecutive output slots; a wave with few selected entries lets
+// every lane walk its own word instead.
 constexpr int kCompressWaves = 8;
 constexpr int kCompressTile = kCompressWaves * 4096;
 
@@ -1107,6 +1194,19 @@ __global__ __launch_bounds__(kCompressWaves * 64) void compress_kernel(
     __syncthreads();
     // output index of the first selected entry of word j of my wave (lane j holds it)
     const uint64_t word_base = (uint64_t)s_carry + wave_ex + (inc - cnt);
+    if (__builtin_amdgcn_readlane((int)inc, 63) <= 256) {
+        // few selected entries in my wave's 4096 positions: every lane walks the set bits of its own
+        // word (a handful of independent loads per lane) instead of the wave visiting all 64 words
+        uint64_t mm = m, k = word_base;
+        while (mm) {
+            const uint64_t p = p0 + (uint32_t)__builtin_ctzll((unsigned long long)mm);
+            mm &= mm - 1;
+            const uint32_t v = x ? __builtin_nontemporal_load(x + p) : (uint32_t)p;
+            if (k < out_cap) out[k] = v;
+            ++k;
+        }
+        return;
+    }
     const uint32_t m_lo = (uint32_t)m, m_hi = (uint32_t)(m >> 32);
     const uint32_t base_lo = (uint32_t)word_base, base_hi = (uint32_t)(word_base >> 32);
     const uint64_t lane_below = (1ull << lane) - 1ull;
@@ -1261,7 +1361,14 @@ constexpr uint64_t kResident = MMV_MIN_TILES;   // workgroups resident at once (
 #ifndef MMV_TAIL_ROUNDS
 #define MMV_TAIL_ROUNDS 1
 #endif
-constexpr uint64_t kTailTiles = MMV_TAIL_ROUNDS * kResident;  // short tiles at the end of a long vector
+#ifndef MMV_TAIL_TILES
+#define MMV_TAIL_TILES (MMV_TAIL_ROUNDS * kResident / 2)   // half a round measured best (256, 512, 768 within 1.5 %)
+#endif
+#ifndef MMV_TAIL_CPW
+#define MMV_TAIL_CPW 1
+#endif
+constexpr uint64_t kTailTiles = MMV_TAIL_TILES;  // short tiles at the end of a long vector
+constexpr uint64_t kCountSumTiles = 2048;        // up to this many tiles the segmented sum needs no prefix kernel
 inline bool is_spmv(mmv_op op) { return op == MMV_OP_SPMV_COO || op == MMV_OP_SPMV_CSR; }
 inline int max_cpw(mmv_op op, mmv_dtype dt) {
     if (is_spmv(op)) return TSpmv::kMaxCpw;
@@ -1301,8 +1408,8 @@ inline TilePlan tile_plan(mmv_op op, mmv_dtype dt, uint64_t n) {
         p.tail_cpw = (uint32_t)c;
         p.big_tiles = 0;
     } else {
-        p.tail_cpw = 1;
-        const uint64_t tail = kTailTiles * unit < n ? kTailTiles * unit : n;
+        p.tail_cpw = MMV_TAIL_CPW < cpw ? MMV_TAIL_CPW : cpw;
+        const uint64_t tail = kTailTiles * unit * p.tail_cpw < n ? kTailTiles * unit * p.tail_cpw : n;
         p.big_tiles = (n - tail) / p.big_elems;
     }
     p.tail_elems = (uint32_t)(unit * p.tail_cpw);
@@ -1491,9 +1598,11 @@ mmv_status prepare(mmv_op op, const void *d_x, const void *d_flags, uint64_t n, 
     P.desc_v = (uint64_t *)(ws + L.desc_v);
     P.desc_c = (uint64_t *)(ws + L.desc_c);
     P.num_tiles = (uint32_t)tiles_for(n, op, dt);
-    const uint64_t zero_words = L.packed / 4;  // header + descriptors
-    fill_zero_kernel<<<grid_for(zero_words), 256, 0, s>>>((uint32_t *)ws, zero_words, nullptr, 0);
-    if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
+    if (op != MMV_OP_SEGSUM) {   // the segmented sum zeroes them in its tile-count kernel
+        const uint64_t zero_words = L.packed / 4;  // header + descriptors
+        fill_zero_kernel<<<grid_for(zero_words), 256, 0, s>>>((uint32_t *)ws, zero_words, nullptr, 0);
+        if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
+    }
     if (ff == MMV_FLAGS_U8) {
         const uint64_t nwords = (n + 31) / 32;
         uint32_t *packed = (uint32_t *)(ws + L.packed);
@@ -1650,6 +1759,23 @@ mmv_status mmv_segsum(const void *d_x, const void *d_flags, uint64_t n, void *d_
     P.out = d_out;
     P.out_cap = out_capacity;
     P.nseg = d_nseg;
+    // number of segment starts before every tile: per-tile counts, then their exclusive scan
+    const TilePlan plan = tile_plan(MMV_OP_SEGSUM, dt, n);
+    const WsLayout L = ws_layout(MMV_OP_SEGSUM, dt, ff, n);
+    uint32_t *tile_count = (uint32_t *)((char *)d_ws + L.desc_c);
+    if (plan.tiles() > 0x7fffffffull) return MMV_ERR_INVALID_ARG;
+    count_tiles_kernel<<<(unsigned)plan.tiles(), 256, 0, s>>>((uint32_t *)d_ws, L.desc_c / 4, P.fw, n,
+                                                               (uint32_t)plan.big_tiles, plan.big_elems,
+                                                               plan.tail_elems, tile_count);
+    if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
+    // few tiles: every tile of the main kernel adds up the counts before it; many: one more small kernel
+    // turns the counts into prefix sums first
+    P.count_is_prefix = plan.tiles() > kCountSumTiles ? 1u : 0u;
+    if (P.count_is_prefix) {
+        scan_counts_kernel<<<1, 1024, 0, s>>>(tile_count, (uint32_t)plan.tiles(), d_nseg);
+        if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
+    }
+    P.tile_count = tile_count;
     return launch_dt<kSum>(P, dt, v, s) == hipSuccess ? MMV_OK : MMV_ERR_HIP;
 }
 
