@@ -111,7 +111,6 @@ struct Params {
     float *y;
     uint32_t *hdr;          // workspace header
     uint64_t *desc_v;       // value descriptors, one per tile
-    uint64_t *desc_c;       // count descriptors (spmv csr)
     const uint32_t *tile_count;  // sum: segment starts per tile (position 0 not counted), or ...
     uint32_t count_is_prefix;    // ... their exclusive prefix sums already (long vectors)
     uint32_t num_tiles;
@@ -626,10 +625,8 @@ __global__ __launch_bounds__(TT::kWaves * 64, MMV_MIN_WAVES_PER_SIMD) void seg_k
     constexpr int K = 16 / TT::kEpl;             // 128-bit words per lane and 32x32 tile
     constexpr bool kScanLike = kOp == kScan || kOp == kPlainScan;   // every element is an output
     constexpr bool kCounts = kOp == kSum || kOp == kSpmvCsr;        // output index = segment ordinal
-    // where the count of the segments before the tile comes from: a table made by two small
-    // kernels before this one (sum: no chunk has to wait for it), or a second look-back (spmv csr)
-    constexpr bool kCountTable = kOp == kSum;
-    constexpr bool kCountLookback = kOp == kSpmvCsr;
+    // the count of the segments before the tile comes from a table of per-tile counts made by a
+    // small kernel before this one, so that no chunk has to wait for it
     constexpr bool kProduct = kOp == kSpmv || kOp == kSpmvCsr;      // values are val * x[col]
 
     __shared__ __attribute__((aligned(16))) uint32_t s_rows[kWaves][kRowsPerChunk * kRowStride];
@@ -684,7 +681,7 @@ __global__ __launch_bounds__(TT::kWaves * 64, MMV_MIN_WAVES_PER_SIMD) void seg_k
         if (P.first_one && tile == 0 && tid == 0) raw[0][0][0] = (raw[0][0][0] & ~0xFFu) | 1u;
     }
 
-    if constexpr (kCountTable) {
+    if constexpr (kCounts) {
         // number of segment starts before my tile, while the loads are in flight: either the table
         // holds the prefix sums already, or (few tiles) wave 1 adds up the counts of the tiles before
         if (wave == 1) {
@@ -825,20 +822,19 @@ __global__ __launch_bounds__(TT::kWaves * 64, MMV_MIN_WAVES_PER_SIMD) void seg_k
     }
     wex_f = __builtin_amdgcn_readfirstlane(wex_f);
 
-    if constexpr (kCountTable) {
-        if (!P.count_is_prefix && tile == P.num_tiles - 1 && tid == 0) *P.nseg = (uint64_t)s_carry_c + tagg_c + 1u;
+    if constexpr (kCounts) {
+        if (kOp == kSum && !P.count_is_prefix && tile == P.num_tiles - 1 && tid == 0) *P.nseg = (uint64_t)s_carry_c + tagg_c + 1u;
     }
 
     // ---- step 5c, first half: publish this tile ----
     const bool final_now = tile == 0 || tagg_f;  // carry out does not depend on predecessors
     if (tid == 0) desc_store(P.desc_v + tile, final_now ? kStatusPrefix : kStatusAggregate, to_bits(tagg_v));
-    if (kCountLookback && tid == 64) desc_store(P.desc_c + tile, tile == 0 ? kStatusPrefix : kStatusAggregate, tagg_c);
 
     // carry into my span (used only by rows with no flag before them in the tile); the carry of
     // the predecessor tiles is added once it is known
     A span_carry = wex_v;
     uint32_t count_carry = 0;
-    if constexpr (kCountTable) count_carry = s_carry_c;
+    if constexpr (kCounts) count_carry = s_carry_c;
 
     // ================= phase B: recompute, revert, add carries, store =================
 #pragma unroll 1
@@ -855,19 +851,7 @@ __global__ __launch_bounds__(TT::kWaves * 64, MMV_MIN_WAVES_PER_SIMD) void seg_k
                     __hip_atomic_store(&s_ready, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
                 }
             }
-            if (kCountLookback) {
-                if (wave == 1) {
-                    uint32_t carry = 0;
-                    if (tile > 0) carry = lookback<uint32_t>(P.desc_c, (int)tile, lane, P.hdr);
-                    if (lane == 0) {
-                        if (tile > 0) desc_store(P.desc_c + tile, kStatusPrefix, carry + tagg_c);
-                        s_carry_c = carry;
-                    }
-                }
-                __syncthreads();  // every output index needs the count carry
-                count_carry = s_carry_c;
-                tile_carry = from_bits<A>(s_carry_v);
-            } else if (wave != 0 && !wex_f) {
+            if (wave != 0 && !wex_f) {
                 // my span starts inside a segment that began in an earlier tile: wait for wave 0
                 while (__hip_atomic_load(&s_ready, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) == 0)
                     __builtin_amdgcn_s_sleep(1);
@@ -878,9 +862,8 @@ __global__ __launch_bounds__(TT::kWaves * 64, MMV_MIN_WAVES_PER_SIMD) void seg_k
         }
 #pragma unroll 1
         for (int c = 0; c < kCpw; ++c) {
-            // a chunk is "open" when no flag of the tile precedes it; with a count look-back
-            // every chunk is open because all its output indices wait for the count carry
-            const bool chunk_open = kCountLookback || !(wex_f || __builtin_amdgcn_readfirstlane(pre_f[0]));
+            // a chunk is "open" when no flag of the tile precedes it
+            const bool chunk_open = !(wex_f || __builtin_amdgcn_readfirstlane(pre_f[0]));
             if (c < cpw_t && chunk_open == (pass == 1)) {
                 const uint64_t cb = wave_base + (uint64_t)c * kChunkElems;
                 const bool chunk_full = cb + kChunkElems <= n;
@@ -1596,7 +1579,6 @@ mmv_status prepare(mmv_op op, const void *d_x, const void *d_flags, uint64_t n, 
     P.n = n;
     P.hdr = (uint32_t *)ws;
     P.desc_v = (uint64_t *)(ws + L.desc_v);
-    P.desc_c = (uint64_t *)(ws + L.desc_c);
     P.num_tiles = (uint32_t)tiles_for(n, op, dt);
     if (op != MMV_OP_SEGSUM) {   // the segmented sum zeroes them in its tile-count kernel
         const uint64_t zero_words = L.packed / 4;  // header + descriptors
@@ -1805,7 +1787,6 @@ mmv_status mmv_spmv_coo(uint64_t n_rows, uint64_t n_cols, uint64_t nnz, const in
     P.y = d_y;
     P.hdr = (uint32_t *)ws;
     P.desc_v = (uint64_t *)(ws + L.desc_v);
-    P.desc_c = nullptr;
     P.num_tiles = (uint32_t)tiles_for(nnz, MMV_OP_SPMV_COO, MMV_F32_F32);
     P.fw = (const uint32_t *)(ws + L.packed);
     const uint64_t zero_words = L.packed / 4;  // header + descriptors; the flag words are all written below
@@ -1990,8 +1971,19 @@ mmv_status mmv_spmv_csr(uint64_t n_rows, uint64_t n_cols, uint64_t nnz, const in
     P.out_cap = n_rows;
     P.hdr = (uint32_t *)(ws + C.main_ws);
     P.desc_v = (uint64_t *)(ws + C.main_ws + L.desc_v);
-    P.desc_c = (uint64_t *)(ws + C.main_ws + L.desc_c);
     P.fw = fw;
+    // number of segment starts (rows with entries) before every tile
+    const TilePlan plan = tile_plan(MMV_OP_SPMV_CSR, MMV_F32_F32, nnz);
+    uint32_t *tile_count = (uint32_t *)(ws + C.main_ws + L.desc_c);
+    count_tiles_kernel<<<(unsigned)plan.tiles(), 256, 0, s>>>(nullptr, 0, fw, nnz, (uint32_t)plan.big_tiles, plan.big_elems,
+                                                               plan.tail_elems, tile_count);
+    if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
+    P.count_is_prefix = plan.tiles() > kCountSumTiles ? 1u : 0u;
+    if (P.count_is_prefix) {
+        scan_counts_kernel<<<1, 1024, 0, s>>>(tile_count, (uint32_t)plan.tiles(), (uint64_t *)(ws + C.rowcount));
+        if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
+    }
+    P.tile_count = tile_count;
     return launch_seg<TSpmv, kSpmvCsr>(P, v, s) == hipSuccess ? MMV_OK : MMV_ERR_HIP;
 }
 
