@@ -231,3 +231,41 @@ def test_scd_and_sscr_fp32_error_follows_the_global_prefix():
     ends = np.flatnonzero(np.concatenate([f[1:], [1]]))
     assert int(nseg.item()) == len(ref)
     assert (np.abs(out.cpu().numpy()[:len(ref)].astype(np.float64) - ref) <= 1e-4 * np.maximum(G[ends], 1.0)).all()
+
+
+# ---- the sizes the benchmark report times --------------------------------------------------------------
+
+def test_scan_and_compress_at_2p28():
+    n = 1 << 28
+    x, f = W.segscan_i8_uniform_len(n)
+    z = B.mmv_scan(dev(x))
+    torch.cuda.synchronize()
+    ref = oracle.scan(x)
+    got = z.cpu().numpy()
+    del z
+    step = 1 << 26
+    for a in range(0, n, step):
+        assert np.array_equal(got[a:a + step], ref[a:a + step]), a
+    m = W.uniform_density_flags(n, 0.01, 78)
+    out, count = B.mmv_compress(None, packed_dev(m), n, out=torch.empty(int(m.sum()) + 8, dtype=torch.int32, device="cuda"))
+    pos = np.flatnonzero(m)
+    assert int(count.item()) == len(pos) and np.array_equal(out.cpu().numpy()[:len(pos)], pos.astype(np.int32))
+    # values through the same mask: COMPRESS(scan, mask) picks the scan at the marked positions
+    out, count = B.mmv_compress(dev(ref), packed_dev(m), n, out=torch.empty(len(pos) + 8, dtype=torch.int32, device="cuda"))
+    assert int(count.item()) == len(pos) and np.array_equal(out.cpu().numpy()[:len(pos)], ref[pos])
+
+
+@pytest.mark.parametrize("density", [1e-3, 1e-2])
+def test_scd_and_sscr_at_2p26(density):
+    n = 1 << 26
+    rng = np.random.default_rng(69)
+    x = rng.integers(-8, 9, size=n, dtype=np.int8)
+    f = W.uniform_density_flags(n, density, 78)
+    xt, ft = dev(x), packed_dev(f)
+    z = B.mmv_segscan_sscr(xt, ft)
+    torch.cuda.synchronize()
+    assert np.array_equal(z.cpu().numpy(), oracle.segscan(x, f))
+    del z
+    ref = oracle.segsum(x, f)
+    out, nseg = B.mmv_segsum_scd(xt, ft, out=torch.empty(len(ref) + 8, dtype=torch.int32, device="cuda"))
+    assert int(nseg.item()) == len(ref) and np.array_equal(out.cpu().numpy()[:len(ref)], ref)
