@@ -1,9 +1,10 @@
-// libmmvseg: segmented inclusive scan, segmented sum and row-sorted COO SpMV for
+// libmmvseg: segmented inclusive scan, segmented sum and SpMV (row-sorted COO, CSR) for
 // gfx950 (MI355X), after the block-recursive segmented scan of "Segmented
 // Operations using Matrix Multiplications" (Sec. 4.2 and the appendix algorithm
-// "Block-recursive segmented scan").
+// "Block-recursive segmented scan"); plus the paper's stand-alone primitives
+// (SCAN, COMPRESS, DIFF, REVERT, Sec. 4.1) and its un-fused compositions SCD and SSCR.
 //
-// One kernel launch does the whole operation (single pass over HBM):
+// One kernel launch (seg_kernel) does a whole segmented operation in a single pass over HBM:
 //
 //   step 1  speculative row scans  x-bar = MATMUL(x, U_s), s = 32          MFMA
 //           (computed transposed: Z^T = U_s^T X^T, so that every lane ends up
@@ -18,9 +19,13 @@
 //           row's first flag (folded into step 2 through a per-row slot that
 //           holds the negated carry)
 //
-// Layout of a workgroup tile: 4 waves x 64 rows x 32 elements = 8192 elements.
-// Lane r of a wave owns row r of the wave's 2048-element chunk for steps 3-5;
+// Layout of a workgroup tile: 8 waves x (1 to 4) chunks x 64 rows x 32 elements.
+// Lane r of a wave owns row r of the wave's current 2048-element chunk for steps 3-5;
 // one packed flag word is exactly one row.
+//
+// Small kernels around it: workspace reset, flag packing (bytes, COO row indices, CSR row
+// pointers), per-tile counts of segment starts (the output positions of the segmented sum),
+// COMPRESS, DIFF, REVERT, and a streaming copy as the bandwidth reference.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
