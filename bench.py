@@ -7,7 +7,8 @@ in [1, 4096] and bit-packed flags.  One "step" is one mmv_segscan call on
 inputs that already sit in HBM: workspace reset kernel + the single-pass scan
 kernel.  Prints ONE JSON line with the whole-job throughput (G elements/s), the
 HBM roofline of the scan kernel measured with HIP events inside the timed
-region, and the CPU oracle timed on the host beside it.
+region (on every fourth step: an event pair costs about 5 us of stream time),
+and the CPU oracle timed on the host beside it.
 
 `--report FILE` additionally times all five workloads, both variants (matrix
 cores / shuffle-only ablation) and the streaming-copy reference with the same
@@ -61,18 +62,24 @@ class HipEvents:
         self.made = []
 
 
+EVENTS_EVERY = 1
+
+
 def time_steps(step, steps: int, warmup: int, events: HipEvents | None):
     """Runs warmup + steps calls of step(); returns (wall ms per step, mean kernel ms or None)."""
     import torch
     from paper_2506_23906_amd import binding as B
     for _ in range(warmup):
         step()
-    pairs = [(events.create(), events.create()) for _ in range(steps)] if events else []
+    pairs = [(events.create(), events.create()) for _ in range(0, steps, EVENTS_EVERY)] if events else []
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for k in range(steps):
         if events:
-            B.mmv_set_kernel_events(*pairs[k])
+            if k % EVENTS_EVERY == 0:
+                B.mmv_set_kernel_events(*pairs[k // EVENTS_EVERY])
+            else:
+                B.mmv_set_kernel_events(None, None)
         step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
@@ -117,11 +124,16 @@ def main() -> int:
     ap.add_argument("--input-copies", type=int, default=3,
                     help="the steps rotate over this many copies of the inputs (3 x 288 MiB is more than the "
                          "256 MiB memory-side cache, so no step finds its inputs cached from an earlier one)")
+    ap.add_argument("--events-every", type=int, default=4,
+                    help="record the kernel events on every n-th timed step only (an event pair costs about "
+                         "5 us of stream time, which would otherwise be charged to every step)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--report", default=None, help="also time every workload and write JSON lines here")
     ap.add_argument("--copy-only", action="store_true",
                     help="run only the streaming copy reference (1 GiB in, 1 GiB out), for counter calibration")
     args = ap.parse_args()
+    global EVENTS_EVERY
+    EVENTS_EVERY = max(1, args.events_every)
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (every box has one GPU; see DESIGN.md, "
               "'How the path would shard'); --gpus %d is not supported" % args.gpus, file=sys.stderr)
@@ -181,6 +193,7 @@ def main() -> int:
                         % (args.log2n, W.SEEDS["segscan_i8_uniform_len"]),
             "variant": args.variant,
             "input_copies_rotated": len(copies),
+            "kernel_events_every_nth_step": EVENTS_EVERY,
             "tile_elems": B.mmv_tile_elems(),
             "kernel_ms": kernel_ms,
             "hbm_frac_of_peak_whole_step": algo_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
