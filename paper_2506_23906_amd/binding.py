@@ -125,9 +125,13 @@ def mmv_workspace_bytes(op: int, dt: int, ff: int, n: int) -> int:
     return int(load().mmv_workspace_bytes(op, dt, ff, n))
 
 
+def workspace(nbytes: int, device=None) -> torch.Tensor:
+    """Scratch of at least `nbytes` bytes (torch allocations are 256-byte aligned)."""
+    return torch.empty(max(256, nbytes), dtype=torch.uint8, device=device or "cuda")
+
+
 def new_workspace(op: int, dt: int, ff: int, n: int, device=None) -> torch.Tensor:
-    nbytes = max(256, mmv_workspace_bytes(op, dt, ff, n))
-    return torch.empty(nbytes, dtype=torch.uint8, device=device or "cuda")
+    return workspace(mmv_workspace_bytes(op, dt, ff, n), device)
 
 
 def mmv_segscan(x: torch.Tensor, flags: torch.Tensor, n: int | None = None, z: torch.Tensor | None = None,
@@ -218,7 +222,7 @@ def mmv_spmv_csr(n_rows: int, n_cols: int, rowptr: torch.Tensor, col: torch.Tens
     if y is None:
         y = torch.empty(n_rows, dtype=torch.float32, device=val.device)
     if ws is None:
-        ws = torch.empty(max(256, mmv_spmv_csr_workspace_bytes(n_rows, nnz)), dtype=torch.uint8, device=val.device)
+        ws = workspace(mmv_spmv_csr_workspace_bytes(n_rows, nnz), val.device)
     st = lib.mmv_spmv_csr(n_rows, n_cols, nnz, _dev(rowptr, "rowptr"), _dev(col, "col"), _dev(val, "val"),
                           _dev(x, "x"), _dev(y, "y"), _VARIANTS[variant], _dev(ws, "ws"), ws.numel(),
                           _stream_ptr(stream))

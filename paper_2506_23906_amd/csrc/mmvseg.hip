@@ -1081,17 +1081,34 @@ __global__ __launch_bounds__(256) void pack_flags_kernel(const uint8_t *f, uint6
 }
 
 // Segment-start flags of a row-sorted COO matrix, f(e) = [e == 0 or row(e) != row(e-1)],
-// bit-packed: a wave turns 64 consecutive entries into two words with one ballot.
+// bit-packed.  A lane takes four consecutive entries (one 128-bit load) and the entry before
+// them from the lane below; eight lanes OR their nibbles into one flag word.
 __global__ __launch_bounds__(256) void row_flags_kernel(const int32_t *row, uint64_t nnz, uint32_t *words) {
     const int lane = threadIdx.x & 63;
-    const uint64_t wave0 = ((uint64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * 1024;  // 16 ballots per wave
-#pragma unroll 4
-    for (int j = 0; j < 16; ++j) {
-        const uint64_t e = wave0 + 64u * j + lane;
-        bool f = false;
-        if (e < nnz) f = e == 0 || row[e] != row[e - 1];
-        const uint64_t m = __ballot(f);
-        if (lane == 0 && wave0 + 64u * j < nnz) *reinterpret_cast<uint64_t *>(words + ((wave0 + 64u * j) >> 5)) = m;
+    const uint64_t wave0 = ((uint64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * 1024;  // four rounds of 256 entries
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint64_t e0 = wave0 + 256u * j + 4u * lane;
+        v4i r = {0, 0, 0, 0};
+        if (e0 + 4 <= nnz) {
+            r = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(row + e0));
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (e0 + i < nnz) r[i] = row[e0 + i];
+        }
+        int prev = __shfl_up(r[3], 1);
+        if (lane == 0) prev = (e0 > 0 && e0 - 1 < nnz) ? row[e0 - 1] : r[0];
+        uint32_t nib = (e0 == 0 || r[0] != prev) ? 1u : 0u;
+#pragma unroll
+        for (int i = 1; i < 4; ++i) nib |= (r[i] != r[i - 1] ? 1u : 0u) << i;
+        const uint32_t valid = e0 >= nnz ? 0u : (nnz - e0 >= 4 ? 0xFu : (1u << (uint32_t)(nnz - e0)) - 1u);
+        uint32_t v = (nib & valid) << (4 * (lane & 7));
+        v |= __shfl_xor(v, 1);
+        v |= __shfl_xor(v, 2);
+        v |= __shfl_xor(v, 4);
+        const uint64_t w = ((wave0 + 256u * j) >> 5) + (lane >> 3);
+        if ((lane & 7) == 0 && w * 32 < nnz) words[w] = v;
     }
 }
 
