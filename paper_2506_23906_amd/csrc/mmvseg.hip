@@ -1516,16 +1516,16 @@ struct CsrLayout {
 CsrLayout csr_layout(uint64_t n_rows, uint64_t nnz) {
     CsrLayout L;
     size_t off = 0;
-    L.main_ws = off;
+    L.main_ws = off;   // the two workspaces that hold tickets and descriptors lie next to each other:
     off += round256(ws_layout(MMV_OP_SPMV_CSR, MMV_F32_F32, MMV_FLAGS_PACKED32, nnz).total);
+    L.compress_ws = off;   // one fill clears both (and the flag words between them)
+    off += round256(compress_layout(MMV_FLAGS_PACKED32, n_rows).total);
     L.rowmask = off;
     off += round256(((n_rows + 63) / 64) * 8);
     L.rowmap = off;
     off += round256(n_rows * 4 + 16);
     L.rowcount = off;
     off += 256;
-    L.compress_ws = off;
-    off += round256(compress_layout(MMV_FLAGS_PACKED32, n_rows).total);
     L.total = off;
     return L;
 }
@@ -1650,14 +1650,17 @@ mmv_status scan_impl(const void *d_x, uint64_t n, void *d_z, mmv_dtype dt, mmv_v
 
 // COMPRESS on checked arguments; d_x == nullptr compresses the positions.
 mmv_status compress_impl(const void *d_x, const void *d_mask, uint64_t n, void *d_out, uint64_t out_capacity,
-                         uint64_t *d_count, mmv_flag_fmt ff, void *d_ws, size_t ws_bytes, hipStream_t s) {
+                         uint64_t *d_count, mmv_flag_fmt ff, void *d_ws, size_t ws_bytes, hipStream_t s,
+                         bool ws_is_reset = false) {
     const CompressLayout L = compress_layout(ff, n);
     if (((uintptr_t)d_ws & 255u) != 0 || ws_bytes < L.total) return MMV_ERR_WORKSPACE;
     if (L.tiles > 0x7fffffffull) return MMV_ERR_INVALID_ARG;
     char *ws = (char *)d_ws;
-    const uint64_t zero_words = L.packed / 4;
-    fill_zero_kernel<<<grid_for(zero_words), 256, 0, s>>>((uint32_t *)ws, zero_words, nullptr, 0);
-    if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
+    if (!ws_is_reset) {
+        const uint64_t zero_words = L.packed / 4;
+        fill_zero_kernel<<<grid_for(zero_words), 256, 0, s>>>((uint32_t *)ws, zero_words, nullptr, 0);
+        if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
+    }
     const uint32_t *mw = (const uint32_t *)d_mask;
     if (ff == MMV_FLAGS_U8) {
         const uint64_t nwords = (n + 31) / 32;
@@ -1965,8 +1968,8 @@ mmv_status mmv_spmv_csr(uint64_t n_rows, uint64_t n_cols, uint64_t nnz, const in
     if (((uintptr_t)d_ws & 255u) != 0 || ws_bytes < C.total) return MMV_ERR_WORKSPACE;
     char *ws = (char *)d_ws;
     const WsLayout L = ws_layout(MMV_OP_SPMV_CSR, MMV_F32_F32, MMV_FLAGS_PACKED32, nnz);
-    // zero: the main kernel's header, descriptors and flag words; y
-    const uint64_t zero_words = L.total / 4;
+    // zero: the main kernel's header, descriptors and flag words, the header and descriptors of COMPRESS; y
+    const uint64_t zero_words = (C.compress_ws + compress_layout(MMV_FLAGS_PACKED32, n_rows).packed) / 4;
     fill_zero_kernel<<<grid_for(zero_words > n_rows ? zero_words : n_rows), 256, 0, s>>>((uint32_t *)ws, zero_words,
                                                                                       (uint32_t *)d_y, n_rows);
     if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
@@ -1980,7 +1983,7 @@ mmv_status mmv_spmv_csr(uint64_t n_rows, uint64_t n_cols, uint64_t nnz, const in
         EventsOff quiet;
         const mmv_status st = compress_impl(nullptr, ws + C.rowmask, n_rows, ws + C.rowmap, n_rows,
                                             (uint64_t *)(ws + C.rowcount), MMV_FLAGS_PACKED32, ws + C.compress_ws,
-                                            C.total - C.compress_ws, s);
+                                            C.rowmask - C.compress_ws, s, true);
         if (st != MMV_OK) return st;
     }
     Params P = {};
