@@ -58,6 +58,9 @@ namespace {
 #ifndef MMV_CPW_SPMV
 #define MMV_CPW_SPMV 1
 #endif
+#ifndef MMV_UNROLL_CHUNKS
+#define MMV_UNROLL_CHUNKS 1   // 1: the chunk loops of the sum / SpMV kernels are unrolled (see kUnrollChunks)
+#endif
 #ifndef MMV_MIN_WAVES_PER_SIMD
 #define MMV_MIN_WAVES_PER_SIMD 4   // register budget: 512 / 4 = 128 VGPRs per lane
 #endif
@@ -629,6 +632,12 @@ __global__ __launch_bounds__(TT::kWaves * 64, MMV_MIN_WAVES_PER_SIMD) void seg_k
     constexpr int kCpw = TT::kMaxCpw;            // most chunks a wave takes (register arrays)
     constexpr int K = 16 / TT::kEpl;             // 128-bit words per lane and 32x32 tile
     constexpr bool kScanLike = kOp == kScan || kOp == kPlainScan;   // every element is an output
+    // The chunk loops are either rolled, with the per-chunk registers rotated so that the body always
+    // works on slot 0 (about 45 moves per chunk and phase, small code), or unrolled.  Unrolled, the
+    // scan kernels spill registers (measured: 100 to 700 bytes per lane) and so does the shuffle-only
+    // int8 sum kernel with its four chunks; the other sum / SpMV kernels do not.
+    constexpr bool kUnrollChunks = MMV_UNROLL_CHUNKS != 0 && !kScanLike && (kMfma || kCpw <= 2);
+    constexpr int kChunkUnroll = kUnrollChunks ? kCpw : 1;
     constexpr bool kCounts = kOp == kSum || kOp == kSpmvCsr;        // output index = segment ordinal
     // the count of the segments before the tile comes from a table of per-tile counts made by a
     // small kernel before this one, so that no chunk has to wait for it
@@ -714,13 +723,14 @@ __global__ __launch_bounds__(TT::kWaves * 64, MMV_MIN_WAVES_PER_SIMD) void seg_k
     uint32_t run_f = 0, run_c = 0;
 
     // ================= phase A: aggregates =================
-#pragma unroll 1
+#pragma unroll kChunkUnroll
     for (int c = 0; c < kCpw; ++c) {
+      const int S = kUnrollChunks ? c : 0;   // register slot of this chunk
       if (c < cpw_t) {
         const uint64_t cb = wave_base + (uint64_t)c * kChunkElems;
         const uint64_t row_start = cb + 32u * lane;  // first element of the row this lane owns
         // ---- flags of my row (one 32-bit word = one row); bits beyond n do not count ----
-        if (row_start + 32 > n) F[0] = row_start < n ? (F[0] & ((1u << (uint32_t)(n - row_start)) - 1u)) : 0u;
+        if (row_start + 32 > n) F[S] = row_start < n ? (F[S] & ((1u << (uint32_t)(n - row_start)) - 1u)) : 0u;
         if constexpr (kProduct) {
             // product vector p(i) = val(i) * x(col(i)), in the layout the values were loaded in
 #pragma unroll
@@ -731,30 +741,30 @@ __global__ __launch_bounds__(TT::kWaves * 64, MMV_MIN_WAVES_PER_SIMD) void seg_k
 #pragma unroll
                     for (int k = 0; k < 4; ++k) {
                         const float p =
-                            (e0 + k < n) ? from_bits<float>(raw[0][t * K + i][k]) * P.xv[rawc[0][t * K + i][k]] : 0.0f;
-                        raw[0][t * K + i][k] = to_bits(p);
+                            (e0 + k < n) ? from_bits<float>(raw[S][t * K + i][k]) * P.xv[rawc[S][t * K + i][k]] : 0.0f;
+                        raw[S][t * K + i][k] = to_bits(p);
                     }
                 }
         }
 
         // ---- steps 1-4 for the aggregate of my row: last element after the revert, any flag ----
-        const uint32_t has_flag = F[0] != 0;
+        const uint32_t has_flag = F[S] != 0;
         A agg_v;
         if constexpr (kMfma) {
-            if constexpr (K > 1) to_operand_layout<K>(raw[0], rows, lane);
-            agg_v = RowAgg<TT>::run(raw[0], F[0], lane);
+            if constexpr (K > 1) to_operand_layout<K>(raw[S], rows, lane);
+            agg_v = RowAgg<TT>::run(raw[S], F[S], lane);
         } else {
 #pragma unroll
-            for (int t = 0; t < 2; ++t) spec_shuffle_tile<TT>(raw[0] + t * K, lane, rows, t);
+            for (int t = 0; t < 2; ++t) spec_shuffle_tile<TT>(raw[S] + t * K, lane, rows, t);
             rows[lane * kRowStride + kSlotZero] = 0;
             wave_lds_sync();
             const A last = from_bits<A>(rows[lane * kRowStride + kRowData + 31]);
-            const int slot = kSlotZero + last_flag_pos(F[0]);  // x-bar(start - 1)
+            const int slot = kSlotZero + last_flag_pos(F[S]);  // x-bar(start - 1)
             agg_v = last - from_bits<A>(rows[lane * kRowStride + slot]);
             wave_lds_sync();  // the rows are read before the next chunk overwrites them
         }
         // segment starts in my row, position 0 of the whole vector not counted (sum only)
-        const uint32_t cnt = __popc(row_start == 0 ? (F[0] & ~1u) : F[0]);
+        const uint32_t cnt = __popc(row_start == 0 ? (F[S] & ~1u) : F[S]);
 
         // ---- step 5a: segmented inclusive scan of (value, flag) over the 64 rows of the chunk ----
         A inc_v = agg_v;
@@ -773,15 +783,15 @@ __global__ __launch_bounds__(TT::kWaves * 64, MMV_MIN_WAVES_PER_SIMD) void seg_k
                 if (lane >= d) inc_c += oc;
             }
         }
-        ex_v[0] = from_bits<A>(__shfl_up(to_bits(inc_v), 1));
-        ex_f[0] = __shfl_up(inc_f, 1);
+        ex_v[S] = from_bits<A>(__shfl_up(to_bits(inc_v), 1));
+        ex_f[S] = __shfl_up(inc_f, 1);
         if (lane == 0) {
-            ex_v[0] = A(0);
-            ex_f[0] = 0;
+            ex_v[S] = A(0);
+            ex_f[S] = 0;
         }
-        ex_c[0] = run_c + inc_c - cnt;
-        pre_v[0] = run_v;
-        pre_f[0] = run_f;
+        ex_c[S] = run_c + inc_c - cnt;
+        pre_v[S] = run_v;
+        pre_f[S] = run_f;
         // chunk aggregate = inclusive value of the last row; fold it into the span's running aggregate
         const A ca_v = from_bits<A>(__shfl(to_bits(inc_v), 63));
         const uint32_t ca_f = __shfl(inc_f, 63);
@@ -789,14 +799,16 @@ __global__ __launch_bounds__(TT::kWaves * 64, MMV_MIN_WAVES_PER_SIMD) void seg_k
         run_f |= ca_f;
         if (kCounts) run_c += __shfl(inc_c, 63);
       }
-        rotate(F);
-        rotate_rows(raw);
-        if constexpr (kProduct) rotate_rows(rawc);
-        rotate(ex_v);
-        rotate(ex_f);
-        rotate(pre_v);
-        rotate(pre_f);
-        if (kCounts) rotate(ex_c);
+        if constexpr (!kUnrollChunks) {
+            rotate(F);
+            rotate_rows(raw);
+            if constexpr (kProduct) rotate_rows(rawc);
+            rotate(ex_v);
+            rotate(ex_f);
+            rotate(pre_v);
+            rotate(pre_f);
+            if (kCounts) rotate(ex_c);
+        }
     }
     MMV_STAMP(2);
     if (lane == 0) {
@@ -865,10 +877,11 @@ __global__ __launch_bounds__(TT::kWaves * 64, MMV_MIN_WAVES_PER_SIMD) void seg_k
             if (!wex_f) span_carry = tile_carry + wex_v;
             MMV_STAMP(5);
         }
-#pragma unroll 1
+#pragma unroll kChunkUnroll
         for (int c = 0; c < kCpw; ++c) {
+            const int S = kUnrollChunks ? c : 0;
             // a chunk is "open" when no flag of the tile precedes it
-            const bool chunk_open = !(wex_f || __builtin_amdgcn_readfirstlane(pre_f[0]));
+            const bool chunk_open = !(wex_f || __builtin_amdgcn_readfirstlane(pre_f[S]));
             if (c < cpw_t && chunk_open == (pass == 1)) {
                 const uint64_t cb = wave_base + (uint64_t)c * kChunkElems;
                 const bool chunk_full = cb + kChunkElems <= n;
@@ -877,20 +890,20 @@ __global__ __launch_bounds__(TT::kWaves * 64, MMV_MIN_WAVES_PER_SIMD) void seg_k
                 for (int t = 0; t < 2; ++t) {
                     if (kMfma) {
                         A acc[16];
-                        SpecMfma<TT>::run(raw[0] + t * K, lane, acc);
+                        SpecMfma<TT>::run(raw[S] + t * K, lane, acc);
                         store_spec_rows(rows, t, lane, acc);
                     } else {
-                        spec_shuffle_tile<TT>(raw[0] + t * K, lane, rows, t);
+                        spec_shuffle_tile<TT>(raw[S] + t * K, lane, rows, t);
                     }
                 }
                 // ---- step 6: carry into my row ----
-                const A carry = ex_f[0] ? ex_v[0] : (pre_f[0] ? pre_v[0] + ex_v[0] : (span_carry + pre_v[0]) + ex_v[0]);
+                const A carry = ex_f[S] ? ex_v[S] : (pre_f[S] ? pre_v[S] + ex_v[S] : (span_carry + pre_v[S]) + ex_v[S]);
                 if constexpr (kScanLike) {
                     // stored negated in the slot before x-bar(-1), so that the revert subtracts it
                     rows[lane * kRowStride + kSlotZero] = 0;
-                    rows[lane * kRowStride + kSlotF] = F[0];
+                    rows[lane * kRowStride + kSlotF] = F[S];
                     rows[lane * kRowStride + kSlotNegCarry] = to_bits(A(0) - carry);
-                    const uint64_t row_any = __ballot(F[0] != 0);
+                    const uint64_t row_any = __ballot(F[S] != 0);
                     wave_lds_sync();
 
                     // ---- steps 2 + 6 on every element, then store; a lane owns 4 consecutive positions ----
@@ -932,13 +945,13 @@ __global__ __launch_bounds__(TT::kWaves * 64, MMV_MIN_WAVES_PER_SIMD) void seg_k
                     // ---- sum, spmv: only the segment ends produce output; the lane that owns a row
                     // walks the ends of its row (steps 2 + 6 for those positions only) ----
                     // end mask: bit p set iff position p + 1 starts a segment or p is the last element
-                    uint32_t next0 = __shfl_down(F[0], 1) & 1u;
+                    uint32_t next0 = __shfl_down(F[S], 1) & 1u;
                     if (lane == 63) {
                         const uint64_t en = cb + kChunkElems;
                         next0 = 0;
                         if (en < n) next0 = P.fw[en >> 5] & 1u;
                     }
-                    uint32_t E = (F[0] >> 1) | (next0 << 31);
+                    uint32_t E = (F[S] >> 1) | (next0 << 31);
                     if (row_start < n) {
                         if (row_start + 32 >= n) {
                             const uint32_t last = (uint32_t)(n - 1 - row_start);
@@ -949,12 +962,12 @@ __global__ __launch_bounds__(TT::kWaves * 64, MMV_MIN_WAVES_PER_SIMD) void seg_k
                     }
                     wave_lds_sync();
                     const uint32_t *rp = rows + lane * kRowStride + kRowData;
-                    const uint32_t Fc = row_start == 0 ? (F[0] & ~1u) : F[0];  // position 0 is not counted
-                    const uint64_t count_base = (uint64_t)count_carry + wex_c + ex_c[0];
+                    const uint32_t Fc = row_start == 0 ? (F[S] & ~1u) : F[S];  // position 0 is not counted
+                    const uint64_t count_base = (uint64_t)count_carry + wex_c + ex_c[S];
                     while (E) {
                         const int e = __builtin_ctz(E);
                         E &= E - 1u;
-                        const uint32_t m = F[0] & ((2u << e) - 1u);  // flags at or before the end
+                        const uint32_t m = F[S] & ((2u << e) - 1u);  // flags at or before the end
                         A v = from_bits<A>(rp[e]);
                         if (m) {
                             const int st = 31 - __clz(m);
@@ -975,13 +988,15 @@ __global__ __launch_bounds__(TT::kWaves * 64, MMV_MIN_WAVES_PER_SIMD) void seg_k
                 }
                 wave_lds_sync();  // the rows are read before the next chunk overwrites them
             }
-            rotate(F);
-            rotate_rows(raw);
-            rotate(ex_v);
-            rotate(ex_f);
-            rotate(pre_v);
-            rotate(pre_f);
-            if (kCounts) rotate(ex_c);
+            if constexpr (!kUnrollChunks) {
+                rotate(F);
+                rotate_rows(raw);
+                rotate(ex_v);
+                rotate(ex_f);
+                rotate(pre_v);
+                rotate(pre_f);
+                if (kCounts) rotate(ex_c);
+            }
         }
     }
     MMV_STAMP(6);
