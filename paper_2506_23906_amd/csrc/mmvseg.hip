@@ -886,8 +886,31 @@ __global__ __launch_bounds__(TT::kWaves * 64, MMV_MIN_WAVES_PER_SIMD) void seg_k
                 const uint64_t cb = wave_base + (uint64_t)c * kChunkElems;
                 const bool chunk_full = cb + kChunkElems <= n;
                 const uint64_t row_start = cb + 32u * lane;
+                // sum, spmv: end mask of my row, bit p set iff position p + 1 starts a segment or p is
+                // the last element; a 32x32 tile none of whose rows holds a segment end needs no x-bar
+                uint32_t E = 0;
+                uint64_t rows_with_ends = ~0ull;
+                if constexpr (!kScanLike) {
+                    uint32_t next0 = __shfl_down(F[S], 1) & 1u;
+                    if (lane == 63) {
+                        const uint64_t en = cb + kChunkElems;
+                        next0 = 0;
+                        if (en < n) next0 = P.fw[en >> 5] & 1u;
+                    }
+                    E = (F[S] >> 1) | (next0 << 31);
+                    if (row_start < n) {
+                        if (row_start + 32 >= n) {
+                            const uint32_t last = (uint32_t)(n - 1 - row_start);
+                            E = (E & ((1u << last) - 1u)) | (1u << last);
+                        }
+                    } else {
+                        E = 0;
+                    }
+                    rows_with_ends = __ballot(E != 0);
+                }
 #pragma unroll
                 for (int t = 0; t < 2; ++t) {
+                    if (((rows_with_ends >> (32 * t)) & 0xFFFFFFFFull) == 0) continue;
                     if (kMfma) {
                         A acc[16];
                         SpecMfma<TT>::run(raw[S] + t * K, lane, acc);
@@ -944,22 +967,6 @@ __global__ __launch_bounds__(TT::kWaves * 64, MMV_MIN_WAVES_PER_SIMD) void seg_k
                 } else {
                     // ---- sum, spmv: only the segment ends produce output; the lane that owns a row
                     // walks the ends of its row (steps 2 + 6 for those positions only) ----
-                    // end mask: bit p set iff position p + 1 starts a segment or p is the last element
-                    uint32_t next0 = __shfl_down(F[S], 1) & 1u;
-                    if (lane == 63) {
-                        const uint64_t en = cb + kChunkElems;
-                        next0 = 0;
-                        if (en < n) next0 = P.fw[en >> 5] & 1u;
-                    }
-                    uint32_t E = (F[S] >> 1) | (next0 << 31);
-                    if (row_start < n) {
-                        if (row_start + 32 >= n) {
-                            const uint32_t last = (uint32_t)(n - 1 - row_start);
-                            E = (E & ((1u << last) - 1u)) | (1u << last);
-                        }
-                    } else {
-                        E = 0;
-                    }
                     wave_lds_sync();
                     const uint32_t *rp = rows + lane * kRowStride + kRowData;
                     const uint32_t Fc = row_start == 0 ? (F[S] & ~1u) : F[S];  // position 0 is not counted
