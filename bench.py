@@ -127,6 +127,9 @@ def main() -> int:
     ap.add_argument("--events-every", type=int, default=4,
                     help="record the kernel events on every n-th timed step only (an event pair costs about "
                          "5 us of stream time, which would otherwise be charged to every step)")
+    ap.add_argument("--density", type=float, default=None,
+                    help="uniformly random flags of this density instead of the segment lengths of the workload "
+                         "(for profiling; changes config.workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--report", default=None, help="also time every workload and write JSON lines here")
     ap.add_argument("--copy-only", action="store_true",
@@ -158,6 +161,8 @@ def main() -> int:
 
     n = 1 << args.log2n
     x, f = W.segscan_i8_uniform_len(n)
+    if args.density is not None:
+        f = W.uniform_density_flags(n, args.density, 77)
     xt = torch.from_numpy(x).cuda()
     ft = torch.from_numpy(W.pack_flags(f).view(np.int32)).cuda()
     copies = [(xt, ft)] + [(xt.clone(), ft.clone()) for _ in range(max(1, args.input_copies) - 1)]
@@ -189,8 +194,9 @@ def main() -> int:
         "data": "synthetic",
         "config": {
             "workload": "segscan_i8_uniform_len: segmented inclusive scan, n=2^%d int8 in [-8,8] -> int32, "
-                        "segment lengths U{1..4096}, bit-packed flags, seed %d"
-                        % (args.log2n, W.SEEDS["segscan_i8_uniform_len"]),
+                        "%s, bit-packed flags, seed %d"
+                        % (args.log2n, "segment lengths U{1..4096}" if args.density is None
+                           else "uniformly random flags of density %g" % args.density, W.SEEDS["segscan_i8_uniform_len"]),
             "variant": args.variant,
             "input_copies_rotated": len(copies),
             "kernel_events_every_nth_step": EVENTS_EVERY,

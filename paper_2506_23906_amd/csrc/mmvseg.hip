@@ -29,6 +29,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+#include <vector>
+
 #include "mmvseg.h"
 
 namespace {
@@ -124,6 +127,7 @@ struct Params {
     uint32_t num_tiles;
     uint32_t big_tiles;     // tiles [0, big_tiles) have the full number of chunks per wave ...
     uint32_t tail_cpw;      // ... the rest have this many (shorter tiles at the end shorten the tail)
+    uint32_t ordered;       // the whole grid is resident at once: workgroup b takes tile b, no ticket
 #ifdef MMV_TRACE
     uint64_t *trace;        // 8 timestamps per tile (development builds only)
 #endif
@@ -653,12 +657,16 @@ __global__ __launch_bounds__(TT::kWaves * 64, MMV_MIN_WAVES_PER_SIMD) void seg_k
 #ifdef MMV_TRACE
     const uint64_t t_begin = wall_clock64();
 #endif
+    // Tiles are handed out by an atomic ticket, so that a tile never waits for a predecessor that
+    // has not started (workgroups need not start in index order).  The tickets of the workgroups
+    // that start together are served one after the other (about 11 ns each): a grid that is resident
+    // as a whole cannot block itself that way and skips them.
     if (tid == 0) {
         s_ready = 0;
-        s_tile = __hip_atomic_fetch_add(P.hdr + kHdrTicket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (!P.ordered) s_tile = __hip_atomic_fetch_add(P.hdr + kHdrTicket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    __syncthreads();
-    const uint32_t tile = s_tile;
+    if (!P.ordered) __syncthreads();
+    const uint32_t tile = P.ordered ? blockIdx.x : s_tile;
 #ifdef MMV_TRACE
     if (tid == 0 && P.trace) P.trace[(uint64_t)tile * 8] = t_begin;
 #endif
@@ -1560,10 +1568,35 @@ uint64_t *g_trace = nullptr;
 // right after the main kernel of a call made by this host thread.
 thread_local hipEvent_t tl_ev_start = nullptr, tl_ev_stop = nullptr;
 
+// Workgroups of `kernel` that the current device holds at once (0 when a query fails); asked once
+// per kernel and device.
+uint32_t resident_workgroups(const void *kernel, int threads) {
+    struct Entry {
+        const void *kernel;
+        int device;
+        uint32_t value;
+    };
+    static std::mutex mu;
+    static std::vector<Entry> known;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    std::lock_guard<std::mutex> lock(mu);
+    for (const Entry &e : known)
+        if (e.kernel == kernel && e.device == dev) return e.value;
+    int per_cu = 0, cus = 0;
+    uint32_t value = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, 0) == hipSuccess &&
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && per_cu > 0 && cus > 0)
+        value = (uint32_t)per_cu * (uint32_t)cus;
+    known.push_back({kernel, dev, value});
+    return value;
+}
+
 template <typename TT, int kOp, bool kMfma> hipError_t launch_variant(Params P, hipStream_t s) {
 #ifdef MMV_TRACE
     P.trace = g_trace;
 #endif
+    P.ordered = P.num_tiles <= resident_workgroups((const void *)seg_kernel<TT, kOp, kMfma>, TT::kWaves * 64) ? 1u : 0u;
     seg_kernel<TT, kOp, kMfma><<<P.num_tiles, TT::kWaves * 64, 0, s>>>(P);
     return hipGetLastError();
 }
