@@ -256,6 +256,18 @@ def write_report(args, events: HipEvents) -> None:
         ms = a.elapsed_time(b) / steps
         return (in_bytes + out_bytes) / (ms * 1e-3) / 1e9, ms
 
+    def call_ms(fn, steps=30, warmup=3):
+        """Whole call (reset kernels included) timed with stream events; mean over `steps`."""
+        for _ in range(warmup):
+            fn()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(steps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / steps
+
     def run(name, n, algo_bytes, step, ws, steps=args.steps):
         wall, kern = time_steps(step, steps, args.warmup, events)
         assert B.mmv_workspace_status(ws) == 0
@@ -322,7 +334,12 @@ def write_report(args, events: HipEvents) -> None:
     for variant in ("mfma", "shuffle"):
         run("4 spmv coo 2^20 x 2^20 nnz=%d zipf(1.5) %s" % (nnz, variant), nnz, nnz * 12 + 2 * nr * 4,
             lambda: B.mmv_spmv_coo(nr, nr, rt, ct, vt, xvt, y=yt, variant=variant, ws=ws), ws)
-    del rt, ct, vt, xvt
+    # what the random accesses to x cost on their own (val and col streamed, x[col] gathered, nothing else)
+    part = torch.empty(B.GATHER_REFERENCE_PARTIALS, dtype=torch.float32, device="cuda")
+    ms = call_ms(lambda: B.mmv_gather_reference(vt, ct, xvt, part))
+    emit(workload="4 gather reference val*x[col] nnz=%d" % nnz, nnz=nnz, ms=ms, gnnz_s=nnz / ms / 1e6,
+         algo_bytes=nnz * 8, gb_s=nnz * 8 / ms / 1e6)
+    del rt, ct, vt, xvt, part
 
     # workload 5
     x, f = W.stress_f32_three_regimes(1 << 30)
@@ -336,18 +353,6 @@ def write_report(args, events: HipEvents) -> None:
 
     del xt, ft, zt
     torch.cuda.empty_cache()
-
-    def call_ms(fn, steps=30, warmup=3):
-        """Whole call (reset kernels included) timed with stream events; mean over `steps`."""
-        for _ in range(warmup):
-            fn()
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record()
-        for _ in range(steps):
-            fn()
-        b.record()
-        torch.cuda.synchronize()
-        return a.elapsed_time(b) / steps
 
     # unsegmented scan (Algorithm Scan) next to the segmented one, n = 2^28
     n = 1 << args.log2n
@@ -436,6 +441,11 @@ def write_report(args, events: HipEvents) -> None:
             ms = call_ms(lambda: B.mmv_spmv_csr(na, na, rpt, ct, vt, xat, y=ya, ws=wsv))
             emit(workload="spmv csr sparse attention 65536^2 b-%d_r-%d" % (block, n_random), nnz=nz, ms=ms,
                  gnnz_s=nz / ms / 1e6, algo_bytes=nz * 8 + 3 * na * 4, gb_s=(nz * 8 + 3 * na * 4) / ms / 1e6)
+            if n_random == 8:
+                part = torch.empty(B.GATHER_REFERENCE_PARTIALS, dtype=torch.float32, device="cuda")
+                ms = call_ms(lambda: B.mmv_gather_reference(vt, ct, xat, part))
+                emit(workload="gather reference sparse attention 65536^2 b-%d_r-%d" % (block, n_random), nnz=nz, ms=ms,
+                     gnnz_s=nz / ms / 1e6, algo_bytes=nz * 8, gb_s=nz * 8 / ms / 1e6)
 
     with open(args.report, "w") as fh:
         for r in rows:

@@ -218,6 +218,17 @@ mmv_status mmv_workspace_status(const void *d_ws, void *hip_stream, uint32_t *h_
 mmv_status mmv_stream_copy(const void *d_src, size_t in_bytes, void *d_dst, size_t out_bytes,
                            void *hip_stream);
 
+/* Random-access reference for SpMV (the product vector val(i) * x(col(i)) of Sec. 4.3
+ * without the segmented sum that follows it): streams the first nnz - nnz % 4 entries
+ * of d_val and d_col (16-byte aligned), gathers x[col] from the n_cols entries of d_x
+ * and leaves one partial sum per thread in d_partial, which must hold
+ * MMV_GATHER_REFERENCE_PARTIALS floats.  Its time is what the random accesses to x
+ * cost on their own; mmv_spmv_coo / mmv_spmv_csr cannot be faster.  A column index
+ * outside [0, n_cols) reads x[0]. */
+#define MMV_GATHER_REFERENCE_PARTIALS (8192 * 256)
+mmv_status mmv_gather_reference(uint64_t nnz, const float *d_val, const int32_t *d_col, uint64_t n_cols,
+                                const float *d_x, float *d_partial, void *hip_stream);
+
 /* Instrumentation for benchmarks: from now on, every mmv_segscan / mmv_segsum /
  * mmv_spmv_coo call made by the calling host thread records `ev_start` (a
  * hipEvent_t passed as void*) on the call's stream immediately before its main

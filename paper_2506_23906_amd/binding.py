@@ -26,7 +26,7 @@ MMV_ELEM_I32, MMV_ELEM_F32 = 0, 1
 
 EXPORTS = [
     "mmv_workspace_bytes", "mmv_segscan", "mmv_segsum", "mmv_spmv_coo", "mmv_workspace_status",
-    "mmv_stream_copy", "mmv_status_string", "mmv_tile_elems", "mmv_set_kernel_events",
+    "mmv_stream_copy", "mmv_gather_reference", "mmv_status_string", "mmv_tile_elems", "mmv_set_kernel_events",
     "mmv_spmv_csr_workspace_bytes", "mmv_spmv_csr", "mmv_scan", "mmv_compress", "mmv_diff", "mmv_revert",
     "mmv_segsum_scd", "mmv_segscan_sscr",
 ]
@@ -66,6 +66,8 @@ def load() -> ctypes.CDLL:
     lib.mmv_workspace_status.restype = i32
     lib.mmv_stream_copy.argtypes = [vp, sz, vp, sz, vp]
     lib.mmv_stream_copy.restype = i32
+    lib.mmv_gather_reference.argtypes = [u64, vp, vp, u64, vp, vp, vp]
+    lib.mmv_gather_reference.restype = i32
     lib.mmv_status_string.argtypes = [i32]
     lib.mmv_status_string.restype = ctypes.c_char_p
     lib.mmv_set_kernel_events.argtypes = [vp, vp]
@@ -197,6 +199,18 @@ def mmv_stream_copy(src: torch.Tensor, dst: torch.Tensor, in_bytes: int | None =
     ob = dst.numel() * dst.element_size() if out_bytes is None else out_bytes
     _check(load().mmv_stream_copy(_dev(src, "src"), ib, _dev(dst, "dst"), ob, _stream_ptr(stream)),
            "mmv_stream_copy")
+
+
+GATHER_REFERENCE_PARTIALS = 8192 * 256
+
+
+def mmv_gather_reference(val: torch.Tensor, col: torch.Tensor, x: torch.Tensor, partial: torch.Tensor,
+                         nnz: int | None = None, stream=None) -> None:
+    if partial.numel() < GATHER_REFERENCE_PARTIALS:
+        raise MmvError("mmv_gather_reference: partial needs %d floats" % GATHER_REFERENCE_PARTIALS)
+    _check(load().mmv_gather_reference(val.numel() if nnz is None else nnz, _dev(val, "val"), _dev(col, "col"),
+                                       x.numel(), _dev(x, "x"), _dev(partial, "partial"), _stream_ptr(stream)),
+           "mmv_gather_reference")
 
 
 def mmv_set_kernel_events(ev_start: int | None, ev_stop: int | None) -> None:

@@ -112,6 +112,10 @@ def test_argument_errors_are_caught_on_the_host(libmmvseg_path):
     assert lib.mmv_spmv_csr(4, 4, 4, a16, a16, a16, a16, a16, 0, a16 << 4, 16, None) == WORKSPACE
     assert lib.mmv_stream_copy(a16, 24, a16, 32, None) == INVALID
     assert lib.mmv_workspace_status(None, None, None) == NULL
+    assert lib.mmv_gather_reference(0, None, None, 0, None, None, None) == OK
+    assert lib.mmv_gather_reference(8, None, a16, 4, a16, a16, None) == NULL
+    assert lib.mmv_gather_reference(8, a16 + 4, a16, 4, a16, a16, None) == INVALID
+    assert lib.mmv_gather_reference(8, a16, a16, 0, a16, a16, None) == INVALID
 
 
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):

@@ -94,3 +94,19 @@ def test_csr_blocked_sparse_attention_full_size():
     rowptr, col, val, x = W.blocked_sparse_attention(n, block=64, n_random=2)
     y = run_csr(n, n, rowptr, col, val, x)
     check_csr(y, n, n, rowptr, col, val, x)
+
+
+def test_gather_reference_sums_the_product_vector():
+    """The random-access reference of the benchmark report: its partial sums add up to sum(val * x[col])
+    (integer-valued data, so the check is exact); the entries past the last multiple of four are left out."""
+    rng = np.random.default_rng(2390611)
+    nnz, n_cols = 100003, 4099
+    val = rng.integers(-3, 4, size=nnz).astype(np.float32)
+    col = rng.integers(0, n_cols, size=nnz, dtype=np.int32)
+    x = rng.integers(-3, 4, size=n_cols).astype(np.float32)
+    part = torch.empty(B.GATHER_REFERENCE_PARTIALS, dtype=torch.float32, device="cuda")
+    B.mmv_gather_reference(dev(val), dev(col), dev(x), part)
+    torch.cuda.synchronize()
+    used = nnz - nnz % 4
+    want = float(np.dot(val[:used].astype(np.float64), x[col[:used]].astype(np.float64)))
+    assert float(part.double().sum().item()) == want
