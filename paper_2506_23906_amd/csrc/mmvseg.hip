@@ -85,6 +85,8 @@ constexpr int kRowData = 4;
 
 constexpr uint32_t kHdrTicket = 0;              // workspace header words
 constexpr uint32_t kHdrError = 1;
+constexpr uint32_t kHdrEmptyRows = 32;          // CSR SpMV: set when some row of the matrix has no entries (a cache
+                                                // line of its own: the line of the ticket is busy with atomics)
 constexpr size_t kHdrBytes = 256;
 
 constexpr uint64_t kStatusInvalid = 0;          // descriptor not written yet
@@ -714,6 +716,9 @@ __global__ __launch_bounds__(TT::kWaves * 64, MMV_MIN_WAVES_PER_SIMD) void seg_k
         if (P.first_one && tile == 0 && tid == 0) raw[0][0][0] = (raw[0][0][0] & ~0xFFu) | 1u;
     }
 
+    // CSR SpMV: without empty rows the k-th segment is row k and the row map was not made
+    bool rows_dense = false;
+    if constexpr (kOp == kSpmvCsr) rows_dense = P.hdr[kHdrEmptyRows] == 0;   // first needed when the ends are written
     if constexpr (kCounts) {
         // number of segment starts before my tile, while the loads are in flight: either the table
         // holds the prefix sums already, or (few tiles) wave 1 adds up the counts of the tiles before
@@ -1006,7 +1011,7 @@ __global__ __launch_bounds__(TT::kWaves * 64, MMV_MIN_WAVES_PER_SIMD) void seg_k
                             if (k < P.out_cap) ((A *)P.out)[k] = v;
                         } else if (kOp == kSpmvCsr) {
                             const uint64_t k = count_base + __popc(Fc & ((2u << e) - 1u));
-                            if (k < P.out_cap) P.y[P.rowmap[k]] = from_bits<float>(to_bits(v));
+                            if (k < P.out_cap) P.y[rows_dense ? (uint32_t)k : P.rowmap[k]] = from_bits<float>(to_bits(v));
                         } else {
                             P.y[P.row[row_start + e]] = from_bits<float>(to_bits(v));
                         }
@@ -1197,9 +1202,11 @@ constexpr int kCompressTile = kCompressWaves * 4096;
 
 __global__ __launch_bounds__(kCompressWaves * 64) void compress_kernel(
     const uint32_t *__restrict__ x, const uint32_t *__restrict__ mw, uint64_t n, uint32_t *__restrict__ out,
-    uint64_t out_cap, uint64_t *__restrict__ count, uint32_t *hdr, uint64_t *desc, uint32_t num_tiles) {
+    uint64_t out_cap, uint64_t *__restrict__ count, uint32_t *hdr, uint64_t *desc, uint32_t num_tiles,
+    const uint32_t *needed) {
     __shared__ uint32_t s_tile, s_wave[kCompressWaves], s_carry;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (needed && *needed == 0) return;   // CSR SpMV without empty rows: nobody reads the row map
     if (tid == 0) s_tile = __hip_atomic_fetch_add(hdr + kHdrTicket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
     const uint32_t tile = s_tile;
@@ -1355,18 +1362,38 @@ __global__ __launch_bounds__(256) void revert_kernel(const uint32_t *xhat, const
 
 // Row pointers of a CSR matrix -> (a) bit-packed segment-start flags over the non-zeros (a row
 // with entries sets the bit of its first entry; rows that share a word meet in an atomic OR on
-// a zeroed word) and (b) the bit-packed mask of rows that have entries (one ballot per 64 rows).
+// a zeroed word), (b) the bit-packed mask of rows that have entries (one ballot per 64 rows),
+// (c) the number of segment starts inside every tile of the main kernel (position 0 not counted,
+// as in count_tiles_kernel; the rows of a wave that start in the same tile share one atomic add
+// on a zeroed table) and (d) the mark that some row is empty.
 __global__ __launch_bounds__(256) void csr_flags_kernel(const int32_t *rowptr, uint64_t n_rows, uint32_t *fw,
-                                                        uint32_t *rowmask) {
+                                                        uint32_t *rowmask, uint32_t *hdr, uint32_t big_tiles,
+                                                        uint32_t big_elems, uint32_t tail_elems, uint32_t *tile_count) {
     const int lane = threadIdx.x & 63;
     const uint64_t r = (uint64_t)blockIdx.x * 256 + threadIdx.x;
     bool nonempty = false;
+    uint32_t tile = 0xFFFFFFFFu;   // tile of the first entry of a row that is counted
     if (r < n_rows) {
         const int32_t a = rowptr[r], b = rowptr[r + 1];
         nonempty = b > a;
-        if (nonempty) atomicOr(fw + ((uint32_t)a >> 5), 1u << ((uint32_t)a & 31u));
+        if (nonempty) {
+            atomicOr(fw + ((uint32_t)a >> 5), 1u << ((uint32_t)a & 31u));
+            const uint64_t big_total = (uint64_t)big_tiles * big_elems;
+            if (a > 0) tile = (uint32_t)a < big_total ? (uint32_t)a / big_elems
+                                                      : big_tiles + (uint32_t)(((uint32_t)a - big_total) / tail_elems);
+        }
     }
     const uint64_t m = __ballot(nonempty);
+    // a matrix none of whose rows is empty needs no row map: segment k is row k
+    if (__ballot(r < n_rows && !nonempty) != 0 && lane == 0) hdr[kHdrEmptyRows] = 1u;
+    uint64_t todo = __ballot(tile != 0xFFFFFFFFu);
+    while (todo) {   // one round per distinct tile among the rows of the wave
+        const int first = __ffsll((unsigned long long)todo) - 1;
+        const uint32_t t = __shfl(tile, first);
+        const uint64_t same = __ballot(tile == t);
+        if (lane == first) atomicAdd(tile_count + t, (uint32_t)__popcll((unsigned long long)same));
+        todo &= ~same;
+    }
     const uint64_t r0 = r - lane;
     if (lane == 0 && r0 < n_rows) {
         rowmask[r0 >> 5] = (uint32_t)m;
@@ -1735,7 +1762,7 @@ mmv_status scan_impl(const void *d_x, uint64_t n, void *d_z, mmv_dtype dt, mmv_v
 // COMPRESS on checked arguments; d_x == nullptr compresses the positions.
 mmv_status compress_impl(const void *d_x, const void *d_mask, uint64_t n, void *d_out, uint64_t out_capacity,
                          uint64_t *d_count, mmv_flag_fmt ff, void *d_ws, size_t ws_bytes, hipStream_t s,
-                         bool ws_is_reset = false) {
+                         bool ws_is_reset = false, const uint32_t *d_needed = nullptr) {
     const CompressLayout L = compress_layout(ff, n);
     if (((uintptr_t)d_ws & 255u) != 0 || ws_bytes < L.total) return MMV_ERR_WORKSPACE;
     if (L.tiles > 0x7fffffffull) return MMV_ERR_INVALID_ARG;
@@ -1756,7 +1783,7 @@ mmv_status compress_impl(const void *d_x, const void *d_mask, uint64_t n, void *
     if (tl_ev_start && hipEventRecord(tl_ev_start, s) != hipSuccess) return MMV_ERR_HIP;
     compress_kernel<<<(unsigned)L.tiles, kCompressWaves * 64, 0, s>>>(
         (const uint32_t *)d_x, mw, n, (uint32_t *)d_out, out_capacity, d_count, (uint32_t *)ws,
-        (uint64_t *)(ws + L.desc), (uint32_t)L.tiles);
+        (uint64_t *)(ws + L.desc), (uint32_t)L.tiles, d_needed);
     const hipError_t e = hipGetLastError();
     if (tl_ev_stop && hipEventRecord(tl_ev_stop, s) != hipSuccess) return MMV_ERR_HIP;
     return e == hipSuccess ? MMV_OK : MMV_ERR_HIP;
@@ -2057,17 +2084,23 @@ mmv_status mmv_spmv_csr(uint64_t n_rows, uint64_t n_cols, uint64_t nnz, const in
     fill_zero_kernel<<<grid_for(zero_words > n_rows ? zero_words : n_rows), 256, 0, s>>>((uint32_t *)ws, zero_words,
                                                                                       (uint32_t *)d_y, n_rows);
     if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
-    // segment-start flags over the non-zeros and the mask of rows that have entries
+    // segment-start flags over the non-zeros, their number per tile of the main kernel, and the mask of
+    // rows that have entries
+    const TilePlan plan = tile_plan(MMV_OP_SPMV_CSR, MMV_F32_F32, nnz);
     uint32_t *fw = (uint32_t *)(ws + C.main_ws + L.packed);
+    uint32_t *tile_count = (uint32_t *)(ws + C.main_ws + L.desc_c);
     const uint64_t row_blocks = (n_rows + 255) / 256;
-    csr_flags_kernel<<<(unsigned)row_blocks, 256, 0, s>>>(d_rowptr, n_rows, fw, (uint32_t *)(ws + C.rowmask));
+    csr_flags_kernel<<<(unsigned)row_blocks, 256, 0, s>>>(d_rowptr, n_rows, fw, (uint32_t *)(ws + C.rowmask),
+                                                          (uint32_t *)(ws + C.main_ws), (uint32_t)plan.big_tiles,
+                                                          plan.big_elems, plan.tail_elems, tile_count);
     if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
     // rowmap = COMPRESS(0 .. n_rows - 1, rowmask): the k-th segment belongs to row rowmap[k]
     {
         EventsOff quiet;
         const mmv_status st = compress_impl(nullptr, ws + C.rowmask, n_rows, ws + C.rowmap, n_rows,
                                             (uint64_t *)(ws + C.rowcount), MMV_FLAGS_PACKED32, ws + C.compress_ws,
-                                            C.rowmask - C.compress_ws, s, true);
+                                            C.rowmask - C.compress_ws, s, true,
+                                            (const uint32_t *)(ws + C.main_ws) + kHdrEmptyRows);
         if (st != MMV_OK) return st;
     }
     Params P = {};
@@ -2081,12 +2114,6 @@ mmv_status mmv_spmv_csr(uint64_t n_rows, uint64_t n_cols, uint64_t nnz, const in
     P.hdr = (uint32_t *)(ws + C.main_ws);
     P.desc_v = (uint64_t *)(ws + C.main_ws + L.desc_v);
     P.fw = fw;
-    // number of segment starts (rows with entries) before every tile
-    const TilePlan plan = tile_plan(MMV_OP_SPMV_CSR, MMV_F32_F32, nnz);
-    uint32_t *tile_count = (uint32_t *)(ws + C.main_ws + L.desc_c);
-    count_tiles_kernel<<<(unsigned)plan.tiles(), 256, 0, s>>>(nullptr, 0, fw, nnz, (uint32_t)plan.big_tiles, plan.big_elems,
-                                                               plan.tail_elems, tile_count);
-    if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
     P.count_is_prefix = plan.tiles() > kCountSumTiles ? 1u : 0u;
     if (P.count_is_prefix) {
         scan_counts_kernel<<<1, 1024, 0, s>>>(tile_count, (uint32_t)plan.tiles(), (uint64_t *)(ws + C.rowcount));
