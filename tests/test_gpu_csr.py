@@ -96,6 +96,34 @@ def test_csr_blocked_sparse_attention_full_size():
     check_csr(y, n, n, rowptr, col, val, x)
 
 
+def test_csr_one_workspace_for_matrices_with_and_without_empty_rows():
+    """A matrix none of whose rows is empty takes a path of its own (segment k is row k, no row map);
+    the same workspace serves both kinds in turn, so the mark of the earlier call must not survive."""
+    n = 5000
+    rng = np.random.default_rng(74)
+    lengths = rng.integers(1, 40, size=n)
+    dense = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int32)          # every row has entries
+    holes = lengths.copy()
+    holes[rng.random(n) < 0.3] = 0
+    holes[0] = holes[-1] = 0
+    sparse = np.concatenate([[0], np.cumsum(holes)]).astype(np.int32)           # 30 % of the rows empty
+    x = rng.integers(-4, 5, size=n).astype(np.float32)
+    mats = []
+    for rowptr in (dense, sparse):
+        nnz = int(rowptr[-1])
+        mats.append((rowptr, rng.integers(0, n, size=nnz, dtype=np.int32), rng.integers(-4, 5, size=nnz).astype(np.float32)))
+    ws = torch.empty(max(B.mmv_spmv_csr_workspace_bytes(n, len(m[2])) for m in mats), dtype=torch.uint8, device="cuda")
+    ws.fill_(0xA5)
+    y = torch.empty(n, dtype=torch.float32, device="cuda")
+    for which in (0, 1, 0, 0, 1, 1, 0):
+        rowptr, col, val = mats[which]
+        y.fill_(77.0)
+        B.mmv_spmv_csr(n, n, dev(rowptr), dev(col), dev(val), dev(x), y=y, ws=ws)
+        torch.cuda.synchronize()
+        assert B.mmv_workspace_status(ws) == 0
+        assert np.array_equal(y.cpu().numpy().astype(np.float64), oracle.spmv_csr(n, n, rowptr, col, val, x)), which
+
+
 def test_gather_reference_sums_the_product_vector():
     """The random-access reference of the benchmark report: its partial sums add up to sum(val * x[col])
     (integer-valued data, so the check is exact); the entries past the last multiple of four are left out."""
