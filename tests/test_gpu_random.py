@@ -73,6 +73,30 @@ def test_random_cases_against_the_oracle():
             assert int(count.item()) == len(ref) and np.array_equal(out.cpu().numpy()[:len(ref)], ref), tag
 
 
+def test_random_cases_longer_than_one_round_of_workgroups():
+    """Vectors that need more tiles than the device holds workgroups at once take their tiles by atomic
+    ticket and end in short tiles; shorter ones (all cases above) take tile = workgroup index."""
+    rng = np.random.default_rng(20260625)
+    one_round = {np.int8: 512 * 65536, np.float16: 512 * 32768, np.float32: 512 * 16384}
+    for case in range(12):
+        dtype = [np.int8, np.float16, np.float32][case % 3]
+        assert one_round[dtype] == 512 * B.mmv_tile_elems(B.MMV_OP_SEGSCAN, B._DTYPES[torch.from_numpy(np.zeros(1, dtype)).dtype], 1 << 40)
+        n = one_round[dtype] + int(rng.integers(1, 3_000_000))
+        variant = ["mfma", "shuffle"][rng.integers(0, 2)]
+        x = random_values(rng, n, dtype)
+        f = _random_flags(rng, n)
+        what = (case // 3) % 3
+        if what == 0:
+            check_scan(run_segscan(x, f, variant, True), x, f)
+        elif what == 1:
+            out, nseg = run_segsum(x, f, variant, True)
+            check_sum(out, nseg, x, f)
+        else:
+            z = B.mmv_scan(dev(x), n=n, variant=variant)
+            torch.cuda.synchronize()
+            check_scan(z.cpu().numpy(), x, np.zeros(n, dtype=np.uint8))
+
+
 def test_random_csr_matrices():
     rng = np.random.default_rng(20260624)
     for case in range(30):
