@@ -88,6 +88,8 @@ constexpr int kRowData = 4;
 
 constexpr uint32_t kHdrTicket = 0;              // workspace header words
 constexpr uint32_t kHdrError = 1;
+constexpr uint32_t kHdrHints = 32;              // first of the words the SpMV kernels read as hints:
+constexpr uint32_t kHdrColumnRuns = 33;         // SpMV: set when neighbouring entries mostly have consecutive columns
 constexpr uint32_t kHdrEmptyRows = 32;          // CSR SpMV: set when some row of the matrix has no entries (a cache
                                                 // line of its own: the line of the ticket is busy with atomics)
 constexpr size_t kHdrBytes = 256;
@@ -638,8 +640,18 @@ template <int N, int M> __device__ __forceinline__ void rotate_rows(v4u (&a)[N][
     }
 }
 
-template <typename TT, int kOp, bool kMfma>
-__global__ __launch_bounds__(TT::kWaves * 64, MMV_MIN_WAVES_PER_SIMD) void seg_kernel(Params P) {
+// LDS of one workgroup: the row buffers of the waves and the words the waves exchange.
+template <int kWaves> struct SegShared {
+    __attribute__((aligned(16))) uint32_t rows[kWaves][kRowsPerChunk * kRowStride];
+    uint32_t wave_v[kWaves], wave_f[kWaves], wave_c[kWaves];
+    uint32_t tile, carry_v, carry_c, ready;
+};
+
+// One tile, from the loads on.  kLateVal (SpMV only): the values are loaded behind the gathers of
+// x[col] instead of beside the columns.
+template <typename TT, int kOp, bool kMfma, bool kLateVal>
+__device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__restrict__ hints, SegShared<TT::kWaves> &sm,
+                                         const uint32_t tile) {
     typedef typename TT::acc_t A;
     typedef typename TT::in_t In;
     constexpr int kWaves = TT::kWaves;
@@ -657,43 +669,9 @@ __global__ __launch_bounds__(TT::kWaves * 64, MMV_MIN_WAVES_PER_SIMD) void seg_k
     // small kernel before this one, so that no chunk has to wait for it
     constexpr bool kProduct = kOp == kSpmv || kOp == kSpmvCsr;      // values are val * x[col]
 
-    __shared__ __attribute__((aligned(16))) uint32_t s_rows[kWaves][kRowsPerChunk * kRowStride];
-    __shared__ uint32_t s_wave_v[kWaves], s_wave_f[kWaves], s_wave_c[kWaves];
-    __shared__ uint32_t s_tile, s_carry_v, s_carry_c, s_ready;
-
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const uint64_t n = P.n;
-    uint32_t *rows = s_rows[wave];
-#ifdef MMV_TRACE
-    const uint64_t t_begin = wall_clock64();
-#endif
-    // A workgroup that starts competes with the ones in the middle of their arithmetic: its ticket
-    // and its loads go first (measured: 2 to 3 % on the long scans)
-#if MMV_LOAD_PRIO
-    __builtin_amdgcn_s_setprio(MMV_LOAD_PRIO);
-#endif
-    // Tiles are handed out by an atomic ticket, so that a tile never waits for a predecessor that
-    // has not started (workgroups need not start in index order).  The tickets of the workgroups
-    // that start together are served one after the other (about 11 ns each): a grid that is resident
-    // as a whole cannot block itself that way and skips them.
-    if (tid == 0) {
-        s_ready = 0;
-        if (!P.ordered) {
-            if (blockIdx.x < P.stagger_wgs) {
-                // low-discrepancy spread of the start times: fraction of blockIdx * golden ratio
-                const uint32_t frac = blockIdx.x * 2654435769u;
-                const uint64_t wait = ((uint64_t)frac * P.stagger_ticks) >> 32;
-                const uint64_t t0 = wall_clock64();
-                while (wall_clock64() - t0 < wait) __builtin_amdgcn_s_sleep(8);
-            }
-            s_tile = __hip_atomic_fetch_add(P.hdr + kHdrTicket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-    }
-    if (!P.ordered) __syncthreads();
-    const uint32_t tile = P.ordered ? blockIdx.x : s_tile;
-#ifdef MMV_TRACE
-    if (tid == 0 && P.trace) P.trace[(uint64_t)tile * 8] = t_begin;
-#endif
+    uint32_t *rows = sm.rows[wave];
     MMV_STAMP(1);
     // tiles at the end of the vector are shorter (fewer chunks per wave)
     const bool big_tile = tile < P.big_tiles;
@@ -718,7 +696,7 @@ __global__ __launch_bounds__(TT::kWaves * 64, MMV_MIN_WAVES_PER_SIMD) void seg_k
                 if (rs < n) F[c] = __builtin_nontemporal_load(P.fw + (rs >> 5));
             }
             if constexpr (kProduct) load_raw<TInt, kMfma>(P.col, cb, n, lane, rawc[c]);
-            load_raw<TT, kMfma>((const In *)P.x, cb, n, lane, raw[c]);
+            if constexpr (!kProduct || !kLateVal) load_raw<TT, kMfma>((const In *)P.x, cb, n, lane, raw[c]);
         }
     }
 
@@ -732,7 +710,7 @@ __global__ __launch_bounds__(TT::kWaves * 64, MMV_MIN_WAVES_PER_SIMD) void seg_k
 
     // CSR SpMV: without empty rows the k-th segment is row k and the row map was not made
     bool rows_dense = false;
-    if constexpr (kOp == kSpmvCsr) rows_dense = P.hdr[kHdrEmptyRows] == 0;   // first needed when the ends are written
+    if constexpr (kOp == kSpmvCsr) rows_dense = hints[kHdrEmptyRows - kHdrHints] == 0;
     if constexpr (kCounts) {
         // number of segment starts before my tile, while the loads are in flight: either the table
         // holds the prefix sums already, or (few tiles) wave 1 adds up the counts of the tiles before
@@ -744,7 +722,7 @@ __global__ __launch_bounds__(TT::kWaves * 64, MMV_MIN_WAVES_PER_SIMD) void seg_k
                 for (uint32_t i = lane; i < tile; i += 64) c += P.tile_count[i];
                 c = wave_sum(c);
             }
-            if (lane == 0) s_carry_c = c;
+            if (lane == 0) sm.carry_c = c;
         }
     }
 
@@ -769,7 +747,25 @@ __global__ __launch_bounds__(TT::kWaves * 64, MMV_MIN_WAVES_PER_SIMD) void seg_k
         const uint64_t row_start = cb + 32u * lane;  // first element of the row this lane owns
         // ---- flags of my row (one 32-bit word = one row); bits beyond n do not count ----
         if (row_start + 32 > n) F[S] = row_start < n ? (F[S] & ((1u << (uint32_t)(n - row_start)) - 1u)) : 0u;
-        if constexpr (kProduct) {
+        if constexpr (kProduct && kLateVal) {
+            // product vector p(i) = val(i) * x(col(i)), in the layout the columns were loaded in: the
+            // gathers go out as soon as the columns are there, the loads of the values right behind them
+            float xg[2 * K][4];
+#pragma unroll
+            for (int i = 0; i < 2 * K; ++i)
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const uint64_t e = cb + 1024u * (i / K) + raw_offset<TT, kMfma>(i % K, lane) + k;
+                    xg[i][k] = e < n ? P.xv[rawc[S][i][k]] : 0.0f;
+                }
+            __builtin_amdgcn_sched_barrier(0);
+            load_raw<TT, kMfma>((const In *)P.x, cb, n, lane, raw[S]);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < 2 * K; ++i)
+#pragma unroll
+                for (int k = 0; k < 4; ++k) raw[S][i][k] = to_bits(from_bits<float>(raw[S][i][k]) * xg[i][k]);
+        } else if constexpr (kProduct) {
             // product vector p(i) = val(i) * x(col(i)), in the layout the values were loaded in
 #pragma unroll
             for (int t = 0; t < 2; ++t)
@@ -850,9 +846,9 @@ __global__ __launch_bounds__(TT::kWaves * 64, MMV_MIN_WAVES_PER_SIMD) void seg_k
     }
     MMV_STAMP(2);
     if (lane == 0) {
-        s_wave_v[wave] = to_bits(run_v);
-        s_wave_f[wave] = run_f;
-        s_wave_c[wave] = run_c;
+        sm.wave_v[wave] = to_bits(run_v);
+        sm.wave_f[wave] = run_f;
+        sm.wave_c[wave] = run_c;
     }
     __syncthreads();
     MMV_STAMP(3);
@@ -869,16 +865,16 @@ __global__ __launch_bounds__(TT::kWaves * 64, MMV_MIN_WAVES_PER_SIMD) void seg_k
             wex_f = tagg_f;
             wex_c = tagg_c;
         }
-        const A wv = from_bits<A>(s_wave_v[w]);
-        const uint32_t wf = s_wave_f[w];
+        const A wv = from_bits<A>(sm.wave_v[w]);
+        const uint32_t wf = sm.wave_f[w];
         tagg_v = wf ? wv : tagg_v + wv;
         tagg_f |= wf;
-        tagg_c += s_wave_c[w];
+        tagg_c += sm.wave_c[w];
     }
     wex_f = __builtin_amdgcn_readfirstlane(wex_f);
 
     if constexpr (kCounts) {
-        if (kOp == kSum && !P.count_is_prefix && tile == P.num_tiles - 1 && tid == 0) *P.nseg = (uint64_t)s_carry_c + tagg_c + 1u;
+        if (kOp == kSum && !P.count_is_prefix && tile == P.num_tiles - 1 && tid == 0) *P.nseg = (uint64_t)sm.carry_c + tagg_c + 1u;
     }
 
     // ---- step 5c, first half: publish this tile ----
@@ -889,7 +885,7 @@ __global__ __launch_bounds__(TT::kWaves * 64, MMV_MIN_WAVES_PER_SIMD) void seg_k
     // the predecessor tiles is added once it is known
     A span_carry = wex_v;
     uint32_t count_carry = 0;
-    if constexpr (kCounts) count_carry = s_carry_c;
+    if constexpr (kCounts) count_carry = sm.carry_c;
 
     // ================= phase B: recompute, revert, add carries, store =================
 #pragma unroll 1
@@ -902,15 +898,15 @@ __global__ __launch_bounds__(TT::kWaves * 64, MMV_MIN_WAVES_PER_SIMD) void seg_k
                 MMV_STAMP(4);
                 if (lane == 0) {
                     if (!final_now) desc_store(P.desc_v + tile, kStatusPrefix, to_bits(tile_carry + tagg_v));
-                    s_carry_v = to_bits(tile_carry);
-                    __hip_atomic_store(&s_ready, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    sm.carry_v = to_bits(tile_carry);
+                    __hip_atomic_store(&sm.ready, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
                 }
             }
             if (wave != 0 && !wex_f) {
                 // my span starts inside a segment that began in an earlier tile: wait for wave 0
-                while (__hip_atomic_load(&s_ready, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) == 0)
+                while (__hip_atomic_load(&sm.ready, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) == 0)
                     __builtin_amdgcn_s_sleep(1);
-                tile_carry = from_bits<A>(s_carry_v);
+                tile_carry = from_bits<A>(sm.carry_v);
             }
             if (!wex_f) span_carry = tile_carry + wex_v;
             MMV_STAMP(5);
@@ -1051,6 +1047,56 @@ __global__ __launch_bounds__(TT::kWaves * 64, MMV_MIN_WAVES_PER_SIMD) void seg_k
 #endif
 }
 
+template <typename TT, int kOp, bool kMfma>
+__global__ __launch_bounds__(TT::kWaves * 64, MMV_MIN_WAVES_PER_SIMD) void seg_kernel(Params P, const uint32_t *__restrict__ hints) {
+    __shared__ SegShared<TT::kWaves> sm;
+    constexpr bool kProduct = kOp == kSpmv || kOp == kSpmvCsr;
+    const int tid = threadIdx.x;
+#ifdef MMV_TRACE
+    const uint64_t t_begin = wall_clock64();
+#endif
+    // A workgroup that starts competes with the ones in the middle of their arithmetic: its ticket
+    // and its loads go first (measured: 2 to 3 % on the long scans)
+#if MMV_LOAD_PRIO
+    __builtin_amdgcn_s_setprio(MMV_LOAD_PRIO);
+#endif
+    // SpMV, where neighbouring entries mostly sit in consecutive columns (blocked, banded matrices): the
+    // gathers are cheap and the memory pipe is the limit, so the values are loaded behind the gathers
+    // instead of beside the columns: half the burst at the start of the tile, the columns arrive
+    // sooner (measured 11-15 % on the blocked sparse-attention matrices).  With scattered columns the
+    // gathers are the limit and values loaded that late only add to their burst (4-8 % slower).
+    // Uniform words, written by the kernel that makes the flags.
+    bool late_val = false;
+    if constexpr (kProduct) late_val = hints[kHdrColumnRuns - kHdrHints] != 0;
+
+    // Tiles are handed out by an atomic ticket, so that a tile never waits for a predecessor that
+    // has not started (workgroups need not start in index order).  The tickets of the workgroups
+    // that start together are served one after the other (about 11 ns each): a grid that is resident
+    // as a whole cannot block itself that way and skips them.
+    if (tid == 0) {
+        sm.ready = 0;
+        if (!P.ordered) {
+            if (blockIdx.x < P.stagger_wgs) {
+                // low-discrepancy spread of the start times: fraction of blockIdx * golden ratio
+                const uint32_t frac = blockIdx.x * 2654435769u;
+                const uint64_t wait = ((uint64_t)frac * P.stagger_ticks) >> 32;
+                const uint64_t t0 = wall_clock64();
+                while (wall_clock64() - t0 < wait) __builtin_amdgcn_s_sleep(8);
+            }
+            sm.tile = __hip_atomic_fetch_add(P.hdr + kHdrTicket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+    if (!P.ordered) __syncthreads();
+    const uint32_t tile = P.ordered ? blockIdx.x : sm.tile;
+#ifdef MMV_TRACE
+    if (tid == 0 && P.trace) P.trace[(uint64_t)tile * 8] = t_begin;
+#endif
+    if (kProduct && late_val)
+        seg_tile<TT, kOp, kMfma, kProduct>(P, hints, sm, tile);
+    else
+        seg_tile<TT, kOp, kMfma, false>(P, hints, sm, tile);
+}
+
 // ---- auxiliary kernels -------------------------------------------------------------------------------------
 
 // Zero fills two ranges (workspace words and, for SpMV, y) with 32-bit stores.
@@ -1140,11 +1186,31 @@ __global__ __launch_bounds__(256) void pack_flags_kernel(const uint8_t *f, uint6
     }
 }
 
+// One wave looks at 512 pairs of neighbouring column indices spread over the matrix and notes in the
+// (zeroed) workspace header whether most of them are consecutive, as in blocked and banded matrices.
+__device__ __forceinline__ void sample_column_runs(const int32_t *col, uint64_t nnz, uint32_t *hdr, int lane) {
+    const uint64_t stride = nnz / 512 > 0 ? nnz / 512 : 1;
+    uint32_t runs = 0, pairs = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const uint64_t p = (uint64_t)(lane * 8 + j) * stride;
+        if (p + 1 < nnz) {
+            ++pairs;
+            runs += col[p + 1] == col[p] + 1 ? 1u : 0u;
+        }
+    }
+    runs = wave_sum(runs);
+    pairs = wave_sum(pairs);
+    if (lane == 0 && 2 * runs > pairs) hdr[kHdrColumnRuns] = 1u;
+}
+
 // Segment-start flags of a row-sorted COO matrix, f(e) = [e == 0 or row(e) != row(e-1)],
 // bit-packed.  A lane takes four consecutive entries (one 128-bit load) and the entry before
 // them from the lane below; eight lanes OR their nibbles into one flag word.
-__global__ __launch_bounds__(256) void row_flags_kernel(const int32_t *row, uint64_t nnz, uint32_t *words) {
+__global__ __launch_bounds__(256) void row_flags_kernel(const int32_t *row, uint64_t nnz, uint32_t *words,
+                                                        const int32_t *col, uint32_t *hdr) {
     const int lane = threadIdx.x & 63;
+    if (blockIdx.x == 0 && threadIdx.x < 64) sample_column_runs(col, nnz, hdr, lane);
     const uint64_t wave0 = ((uint64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * 1024;  // four rounds of 256 entries
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -1382,8 +1448,10 @@ __global__ __launch_bounds__(256) void revert_kernel(const uint32_t *xhat, const
 // on a zeroed table) and (d) the mark that some row is empty.
 __global__ __launch_bounds__(256) void csr_flags_kernel(const int32_t *rowptr, uint64_t n_rows, uint32_t *fw,
                                                         uint32_t *rowmask, uint32_t *hdr, uint32_t big_tiles,
-                                                        uint32_t big_elems, uint32_t tail_elems, uint32_t *tile_count) {
+                                                        uint32_t big_elems, uint32_t tail_elems, uint32_t *tile_count,
+                                                        const int32_t *col, uint64_t nnz) {
     const int lane = threadIdx.x & 63;
+    if (blockIdx.x == 0 && threadIdx.x < 64) sample_column_runs(col, nnz, hdr, lane);
     const uint64_t r = (uint64_t)blockIdx.x * 256 + threadIdx.x;
     bool nonempty = false;
     uint32_t tile = 0xFFFFFFFFu;   // tile of the first entry of a row that is counted
@@ -1673,7 +1741,7 @@ template <typename TT, int kOp, bool kMfma> hipError_t launch_variant(Params P, 
     // time; measured 4 to 7 % on the long SpMV kernels, nothing on the scans.
     P.stagger_wgs = resident;
     P.stagger_ticks = (kOp == kSpmv || kOp == kSpmvCsr) ? MMV_SPMV_STAGGER_US * 100u : 0u;
-    seg_kernel<TT, kOp, kMfma><<<P.num_tiles, TT::kWaves * 64, 0, s>>>(P);
+    seg_kernel<TT, kOp, kMfma><<<P.num_tiles, TT::kWaves * 64, 0, s>>>(P, P.hdr + kHdrHints);
     return hipGetLastError();
 }
 
@@ -1951,7 +2019,7 @@ mmv_status mmv_spmv_coo(uint64_t n_rows, uint64_t n_cols, uint64_t nnz, const in
     if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
     const uint64_t flag_blocks = (nnz + 4095) / 4096;
     if (flag_blocks > 0x7fffffffull) return MMV_ERR_INVALID_ARG;
-    row_flags_kernel<<<(unsigned)flag_blocks, 256, 0, s>>>(d_row, nnz, (uint32_t *)(ws + L.packed));
+    row_flags_kernel<<<(unsigned)flag_blocks, 256, 0, s>>>(d_row, nnz, (uint32_t *)(ws + L.packed), d_col, (uint32_t *)ws);
     if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
     return launch_seg<TSpmv, kSpmv>(P, v, s) == hipSuccess ? MMV_OK : MMV_ERR_HIP;
 }
@@ -2112,7 +2180,7 @@ mmv_status mmv_spmv_csr(uint64_t n_rows, uint64_t n_cols, uint64_t nnz, const in
     const uint64_t row_blocks = (n_rows + 255) / 256;
     csr_flags_kernel<<<(unsigned)row_blocks, 256, 0, s>>>(d_rowptr, n_rows, fw, (uint32_t *)(ws + C.rowmask),
                                                           (uint32_t *)(ws + C.main_ws), (uint32_t)plan.big_tiles,
-                                                          plan.big_elems, plan.tail_elems, tile_count);
+                                                          plan.big_elems, plan.tail_elems, tile_count, d_col, nnz);
     if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
     // rowmap = COMPRESS(0 .. n_rows - 1, rowmask): the k-th segment belongs to row rowmap[k]
     {
