@@ -70,6 +70,9 @@ namespace {
 #ifndef MMV_SPMV_STAGGER_US
 #define MMV_SPMV_STAGGER_US 15   // SpMV: start times of the first round spread over this many microseconds
 #endif
+#ifndef MMV_KEEP_ROWS
+#define MMV_KEEP_ROWS 1
+#endif
 #ifndef MMV_LOAD_PRIO
 #define MMV_LOAD_PRIO 1   // wave priority while a workgroup takes its ticket and issues its loads (0: off)
 #endif
@@ -664,6 +667,9 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
     // int8 sum kernel with its four chunks; the other sum / SpMV kernels do not.
     constexpr bool kUnrollChunks = MMV_UNROLL_CHUNKS != 0 && !kScanLike && (kMfma || kCpw <= 2);
     constexpr int kChunkUnroll = kUnrollChunks ? kCpw : 1;
+    // A wave with a single chunk (fp32, SpMV) keeps the row scans of phase A in its LDS rows for
+    // phase B instead of making them a second time; with more chunks LDS holds only the last one made.
+    constexpr bool kKeepRows = MMV_KEEP_ROWS != 0 && kCpw == 1 && kMfma;
     constexpr bool kCounts = kOp == kSum || kOp == kSpmvCsr;        // output index = segment ordinal
     // the count of the segments before the tile comes from a table of per-tile counts made by a
     // small kernel before this one, so that no chunk has to wait for it
@@ -784,7 +790,21 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
         // ---- steps 1-4 for the aggregate of my row: last element after the revert, any flag ----
         const uint32_t has_flag = F[S] != 0;
         A agg_v;
-        if constexpr (kMfma) {
+        if constexpr (kMfma && kKeepRows) {
+            // one chunk per wave: the row scans made here stay in the wave's LDS rows until phase B
+            if constexpr (K > 1) to_operand_layout<K>(raw[S], rows, lane);
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                A acc[16];
+                SpecMfma<TT>::run(raw[S] + t * K, lane, acc);
+                store_spec_rows(rows, t, lane, acc);
+            }
+            rows[lane * kRowStride + kSlotZero] = 0;
+            wave_lds_sync();
+            const A last = from_bits<A>(rows[lane * kRowStride + kRowData + 31]);
+            const int slot = kSlotZero + last_flag_pos(F[S]);  // x-bar(start - 1)
+            agg_v = last - from_bits<A>(rows[lane * kRowStride + slot]);
+        } else if constexpr (kMfma) {
             if constexpr (K > 1) to_operand_layout<K>(raw[S], rows, lane);
             agg_v = RowAgg<TT>::run(raw[S], F[S], lane);
         } else {
@@ -795,7 +815,7 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
             const A last = from_bits<A>(rows[lane * kRowStride + kRowData + 31]);
             const int slot = kSlotZero + last_flag_pos(F[S]);  // x-bar(start - 1)
             agg_v = last - from_bits<A>(rows[lane * kRowStride + slot]);
-            wave_lds_sync();  // the rows are read before the next chunk overwrites them
+            if constexpr (!kKeepRows) wave_lds_sync();  // the rows are read before the next chunk overwrites them
         }
         // segment starts in my row, position 0 of the whole vector not counted (sum only)
         const uint32_t cnt = __popc(row_start == 0 ? (F[S] & ~1u) : F[S]);
@@ -944,6 +964,7 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
                 }
 #pragma unroll
                 for (int t = 0; t < 2; ++t) {
+                    if (kKeepRows) continue;   // still there from phase A
                     if (((rows_with_ends >> (32 * t)) & 0xFFFFFFFFull) == 0) continue;
                     if (kMfma) {
                         A acc[16];
