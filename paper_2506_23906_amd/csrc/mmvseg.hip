@@ -25,7 +25,8 @@
 //
 // Small kernels around it: workspace reset, flag packing (bytes, COO row indices, CSR row
 // pointers), per-tile counts of segment starts (the output positions of the segmented sum),
-// COMPRESS, DIFF, REVERT, and a streaming copy as the bandwidth reference.
+// COMPRESS, DIFF, REVERT, and two reference kernels for the benchmark: a streaming copy
+// (bandwidth) and a gather of x[col] (what the random accesses of SpMV cost on their own).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -71,7 +72,7 @@ namespace {
 #define MMV_SPMV_STAGGER_US 15   // SpMV: start times of the first round spread over this many microseconds
 #endif
 #ifndef MMV_KEEP_ROWS
-#define MMV_KEEP_ROWS 1
+#define MMV_KEEP_ROWS 1   // 1: single-chunk waves of the matrix-core variant keep their row scans in LDS (see kKeepRows)
 #endif
 #ifndef MMV_LOAD_PRIO
 #define MMV_LOAD_PRIO 1   // wave priority while a workgroup takes its ticket and issues its loads (0: off)
@@ -91,10 +92,10 @@ constexpr int kRowData = 4;
 
 constexpr uint32_t kHdrTicket = 0;              // workspace header words
 constexpr uint32_t kHdrError = 1;
-constexpr uint32_t kHdrHints = 32;              // first of the words the SpMV kernels read as hints:
+constexpr uint32_t kHdrHints = 32;              // first of the words the SpMV kernels read as hints (a cache line of
+                                                // their own: the line of the ticket is busy with atomics):
+constexpr uint32_t kHdrEmptyRows = 32;          // CSR SpMV: set when some row of the matrix has no entries
 constexpr uint32_t kHdrColumnRuns = 33;         // SpMV: set when neighbouring entries mostly have consecutive columns
-constexpr uint32_t kHdrEmptyRows = 32;          // CSR SpMV: set when some row of the matrix has no entries (a cache
-                                                // line of its own: the line of the ticket is busy with atomics)
 constexpr size_t kHdrBytes = 256;
 
 constexpr uint64_t kStatusInvalid = 0;          // descriptor not written yet
@@ -669,6 +670,8 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
     constexpr int kChunkUnroll = kUnrollChunks ? kCpw : 1;
     // A wave with a single chunk (fp32, SpMV) keeps the row scans of phase A in its LDS rows for
     // phase B instead of making them a second time; with more chunks LDS holds only the last one made.
+    // Matrix-core variant only: there it saves the second 3-way split and 50 registers (fp32 scan
+    // 4-5 % faster); in the shuffle variant the same change was measured 3 % slower.
     constexpr bool kKeepRows = MMV_KEEP_ROWS != 0 && kCpw == 1 && kMfma;
     constexpr bool kCounts = kOp == kSum || kOp == kSpmvCsr;        // output index = segment ordinal
     // the count of the segments before the tile comes from a table of per-tile counts made by a
