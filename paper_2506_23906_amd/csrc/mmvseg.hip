@@ -74,6 +74,9 @@ namespace {
 #ifndef MMV_KEEP_ROWS
 #define MMV_KEEP_ROWS 1   // 1: single-chunk waves of the matrix-core variant keep their row scans in LDS (see kKeepRows)
 #endif
+#ifndef MMV_DPP_SCAN
+#define MMV_DPP_SCAN 1   // 1: the 64-lane scan of the row aggregates uses DPP moves, 0: lane shuffles through LDS hardware
+#endif
 #ifndef MMV_LOAD_PRIO
 #define MMV_LOAD_PRIO 1   // wave priority while a workgroup takes its ticket and issues its loads (0: off)
 #endif
@@ -176,6 +179,13 @@ __device__ __forceinline__ uint64_t desc_load(const uint64_t *p) {
 }
 __device__ __forceinline__ void desc_store(uint64_t *p, uint64_t status, uint32_t payload) {
     __hip_atomic_store(p, (status << 62) | payload, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Data-parallel-primitive move: every lane reads the lane the control word names (row_shr n = 0x110 + n
+// inside rows of 16 lanes, row_bcast 15 / 31 = 0x142 / 0x143, wave_shr 1 = 0x138); a lane that has
+// no source, or whose row of lanes is not in kRowMask, reads 0.
+template <int kCtrl, int kRowMask> __device__ __forceinline__ uint32_t dpp_or_zero(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, kCtrl, kRowMask, 0xF, false);
 }
 
 template <typename T> __device__ __forceinline__ T wave_sum(T v) {
@@ -836,6 +846,37 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
         A inc_v = agg_v;
         uint32_t inc_f = has_flag;
         uint32_t inc_c = cnt;
+#if MMV_DPP_SCAN
+        // Kogge-Stone inside the rows of 16 lanes (row_shr 1, 2, 4, 8), then the total of a row of lanes
+        // to the next one (row_bcast 15 into lane rows 1 and 3) and of the first 32 lanes to the last 32
+        // (row_bcast 31 into lane rows 2 and 3).  A lane without a source gets (0, no flag, 0).
+#define MMV_SCAN_STEP(CTRL, ROWS)                                                                  \
+        {                                                                                          \
+            const A ov = from_bits<A>(dpp_or_zero<CTRL, ROWS>(to_bits(inc_v)));                    \
+            const uint32_t of = dpp_or_zero<CTRL, ROWS>(inc_f);                                    \
+            if (kCounts) inc_c += dpp_or_zero<CTRL, ROWS>(inc_c);                                  \
+            if (!inc_f) inc_v = ov + inc_v;                                                        \
+            inc_f |= of;                                                                           \
+        }
+        MMV_SCAN_STEP(0x111, 0xF)
+        MMV_SCAN_STEP(0x112, 0xF)
+        MMV_SCAN_STEP(0x114, 0xF)
+        MMV_SCAN_STEP(0x118, 0xF)
+        MMV_SCAN_STEP(0x142, 0xA)
+        MMV_SCAN_STEP(0x143, 0xC)
+#undef MMV_SCAN_STEP
+        ex_v[S] = from_bits<A>(dpp_or_zero<0x138, 0xF>(to_bits(inc_v)));   // wave_shr 1: lane 0 gets 0
+        ex_f[S] = dpp_or_zero<0x138, 0xF>(inc_f);
+        ex_c[S] = run_c + inc_c - cnt;
+        pre_v[S] = run_v;
+        pre_f[S] = run_f;
+        // chunk aggregate = inclusive value of the last row; fold it into the span's running aggregate
+        const A ca_v = from_bits<A>((uint32_t)__builtin_amdgcn_readlane((int)to_bits(inc_v), 63));
+        const uint32_t ca_f = (uint32_t)__builtin_amdgcn_readlane((int)inc_f, 63);
+        run_v = ca_f ? ca_v : run_v + ca_v;
+        run_f |= ca_f;
+        if (kCounts) run_c += (uint32_t)__builtin_amdgcn_readlane((int)inc_c, 63);
+#else
 #pragma unroll
         for (int d = 1; d < 64; d <<= 1) {
             const A ov = from_bits<A>(__shfl_up(to_bits(inc_v), d));
@@ -864,6 +905,7 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
         run_v = ca_f ? ca_v : run_v + ca_v;
         run_f |= ca_f;
         if (kCounts) run_c += __shfl(inc_c, 63);
+#endif
       }
         if constexpr (!kUnrollChunks) {
             rotate(F);
