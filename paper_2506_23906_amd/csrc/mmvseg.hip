@@ -188,10 +188,26 @@ template <int kCtrl, int kRowMask> __device__ __forceinline__ uint32_t dpp_or_ze
     return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, kCtrl, kRowMask, 0xF, false);
 }
 
+// Both halves of the wave, each broadcast to all 64 lanes: lo[l] = v[l mod 32], hi[l] = v[32 + l mod 32]
+// (one v_permlane32_swap, no LDS hardware).
+struct Halves {
+    uint32_t lo, hi;
+};
+__device__ __forceinline__ Halves wave_halves(uint32_t v) {
+    const auto r = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+    return {(uint32_t)r[0], (uint32_t)r[1]};
+}
+
+// Sum over the 64 lanes, the same value in every lane: DPP adds inside the rows of 16 lanes, row totals
+// passed on with row_bcast 15 / 31, the total read from lane 63.
 template <typename T> __device__ __forceinline__ T wave_sum(T v) {
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) v += from_bits<T>(__shfl_xor(to_bits(v), d));
-    return v;
+    v += from_bits<T>(dpp_or_zero<0x111, 0xF>(to_bits(v)));
+    v += from_bits<T>(dpp_or_zero<0x112, 0xF>(to_bits(v)));
+    v += from_bits<T>(dpp_or_zero<0x114, 0xF>(to_bits(v)));
+    v += from_bits<T>(dpp_or_zero<0x118, 0xF>(to_bits(v)));
+    v += from_bits<T>(dpp_or_zero<0x142, 0xA>(to_bits(v)));
+    v += from_bits<T>(dpp_or_zero<0x143, 0xC>(to_bits(v)));
+    return from_bits<T>((uint32_t)__builtin_amdgcn_readlane((int)to_bits(v), 63));
 }
 
 // Sum of the payloads of the predecessor tiles back to (and including) the first
@@ -487,11 +503,12 @@ __device__ __forceinline__ int last_flag_pos(uint32_t f) { return f ? 31 - __clz
 
 template <> struct RowAgg<TI8> {
     static __device__ __forceinline__ uint32_t run(const v4u *raw, uint32_t F, int lane) {
-        const int c = lane & 31, h = lane >> 5;
+        const int h = lane >> 5;
+        const Halves Fh = wave_halves(F);   // flag words of rows c and 32 + c
         uint32_t tot[2];
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
-            const int st = last_flag_pos(__shfl(F, 32 * t + c));
+            const int st = last_flag_pos(t ? Fh.hi : Fh.lo);
             int part = 0;
 #pragma unroll
             for (int d = 0; d < 4; ++d) {  // bytes of this word = positions 16h+4d .. +3; keep those >= st
@@ -500,7 +517,8 @@ template <> struct RowAgg<TI8> {
                 const uint32_t mask = nv == 0 ? 0u : (0x01010101u << (8 * (4 - nv)));
                 part = __builtin_amdgcn_sdot4((int)raw[t][d], (int)mask, part, false);
             }
-            tot[t] = (uint32_t)part + (uint32_t)__shfl_xor(part, 32);
+            const Halves ph = wave_halves((uint32_t)part);
+            tot[t] = ph.lo + ph.hi;
         }
         return lane < 32 ? tot[0] : tot[1];
     }
@@ -511,11 +529,12 @@ template <bool kBf16> struct RowAggHalf {
         typedef _Float16 v2h __attribute__((ext_vector_type(2)));
         typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
         constexpr uint32_t kOne = kBf16 ? 0x3F80u : 0x3C00u;
-        const int c = lane & 31, h = lane >> 5;
+        const int h = lane >> 5;
+        const Halves Fh = wave_halves(F);   // flag words of rows c and 32 + c
         float tot[2];
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
-            const int st = last_flag_pos(__shfl(F, 32 * t + c));
+            const int st = last_flag_pos(t ? Fh.hi : Fh.lo);
             float part = 0.0f;
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks)
@@ -531,7 +550,8 @@ template <bool kBf16> struct RowAggHalf {
                         part = __builtin_amdgcn_fdot2(__builtin_bit_cast(v2h, pair), __builtin_bit_cast(v2h, mask),
                                                       part, false);
                 }
-            tot[t] = part + __shfl_xor(part, 32);
+            const Halves ph = wave_halves(to_bits(part));
+            tot[t] = from_bits<float>(ph.lo) + from_bits<float>(ph.hi);
         }
         return lane < 32 ? tot[0] : tot[1];
     }
@@ -541,18 +561,20 @@ template <> struct RowAgg<TBF16> : RowAggHalf<true> {};
 
 template <> struct RowAgg<TF32> {
     static __device__ __forceinline__ float run(const v4u *raw, uint32_t F, int lane) {
-        const int c = lane & 31, h = lane >> 5;
+        const int h = lane >> 5;
+        const Halves Fh = wave_halves(F);   // flag words of rows c and 32 + c
         float tot[2];
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
-            const int st = last_flag_pos(__shfl(F, 32 * t + c));
+            const int st = last_flag_pos(t ? Fh.hi : Fh.lo);
             float part = 0.0f;
 #pragma unroll
             for (int q = 0; q < 4; ++q)
 #pragma unroll
                 for (int i = 0; i < 4; ++i)  // position 16h+4q+i
                     part += (16 * h + 4 * q + i >= st) ? from_bits<float>(raw[4 * t + q][i]) : 0.0f;
-            tot[t] = part + __shfl_xor(part, 32);
+            const Halves ph = wave_halves(to_bits(part));
+            tot[t] = from_bits<float>(ph.lo) + from_bits<float>(ph.hi);
         }
         return lane < 32 ? tot[0] : tot[1];
     }
@@ -603,10 +625,19 @@ __device__ __forceinline__ void spec_shuffle_tile(const v4u *raw, int lane, uint
 #pragma unroll
         for (int i = 1; i < kEpl; ++i) p[i] = p[i - 1] + raw_elem<TT>(raw[ld], i);
         A inc = p[kEpl - 1];
-#pragma unroll
-        for (int d = 1; d < kLpr; d <<= 1) {
-            const A o = from_bits<A>(__shfl_up(to_bits(inc), d));
-            if ((lane & (kLpr - 1)) >= d) inc += o;
+        // prefix over the kLpr lanes of a row (DPP row_shr moves; a lane whose source lies in another
+        // row does not add)
+        if constexpr (kLpr > 1) {
+            const A o = from_bits<A>(dpp_or_zero<0x111, 0xF>(to_bits(inc)));
+            if ((lane & (kLpr - 1)) >= 1) inc += o;
+        }
+        if constexpr (kLpr > 2) {
+            const A o = from_bits<A>(dpp_or_zero<0x112, 0xF>(to_bits(inc)));
+            if ((lane & (kLpr - 1)) >= 2) inc += o;
+        }
+        if constexpr (kLpr > 4) {
+            const A o = from_bits<A>(dpp_or_zero<0x114, 0xF>(to_bits(inc)));
+            if ((lane & (kLpr - 1)) >= 4) inc += o;
         }
         const A ex = inc - p[kEpl - 1];
         uint32_t *rp = rows + (32 * t + kRowsPerLoad * ld + lane / kLpr) * kRowStride + kRowData + kEpl * (lane % kLpr);
@@ -999,7 +1030,7 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
                 uint32_t E = 0;
                 uint64_t rows_with_ends = ~0ull;
                 if constexpr (!kScanLike) {
-                    uint32_t next0 = __shfl_down(F[S], 1) & 1u;
+                    uint32_t next0 = dpp_or_zero<0x130, 0xF>(F[S]) & 1u;   // wave_shl 1: the word of the next row
                     if (lane == 63) {
                         const uint64_t en = cb + kChunkElems;
                         next0 = 0;
