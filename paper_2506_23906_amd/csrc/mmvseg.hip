@@ -509,14 +509,18 @@ template <> struct RowAgg<TI8> {
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
             const int st = last_flag_pos(t ? Fh.hi : Fh.lo);
+            // my 16 bytes are positions 16h .. 16h+15; the first k of them lie before the start and
+            // get weight 0, the others weight 1: two 64-bit shifts of a word of ones
+            int k = st - 16 * h;
+            k = k < 0 ? 0 : (k > 16 ? 16 : k);
+            const uint64_t ones = 0x0101010101010101ull;
+            const uint64_t m_lo = k >= 8 ? 0ull : ones << (8 * k);
+            const uint64_t m_hi = k >= 16 ? 0ull : ones << (8 * (k > 8 ? k - 8 : 0));
             int part = 0;
-#pragma unroll
-            for (int d = 0; d < 4; ++d) {  // bytes of this word = positions 16h+4d .. +3; keep those >= st
-                int nv = 16 * h + 4 * d + 4 - st;
-                nv = nv < 0 ? 0 : (nv > 4 ? 4 : nv);
-                const uint32_t mask = nv == 0 ? 0u : (0x01010101u << (8 * (4 - nv)));
-                part = __builtin_amdgcn_sdot4((int)raw[t][d], (int)mask, part, false);
-            }
+            part = __builtin_amdgcn_sdot4((int)raw[t][0], (int)(uint32_t)m_lo, part, false);
+            part = __builtin_amdgcn_sdot4((int)raw[t][1], (int)(uint32_t)(m_lo >> 32), part, false);
+            part = __builtin_amdgcn_sdot4((int)raw[t][2], (int)(uint32_t)m_hi, part, false);
+            part = __builtin_amdgcn_sdot4((int)raw[t][3], (int)(uint32_t)(m_hi >> 32), part, false);
             const Halves ph = wave_halves((uint32_t)part);
             tot[t] = ph.lo + ph.hi;
         }
