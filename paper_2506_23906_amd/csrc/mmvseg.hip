@@ -75,7 +75,7 @@ namespace {
 #define MMV_KEEP_ROWS 1   // 1: single-chunk waves of the matrix-core variant keep their row scans in LDS (see kKeepRows)
 #endif
 #ifndef MMV_DPP_SCAN
-#define MMV_DPP_SCAN 1   // 1: the 64-lane scan of the row aggregates uses DPP moves, 0: lane shuffles through LDS hardware
+#define MMV_DPP_SCAN 1   // 1: the sum-type kernels exchange lanes with DPP moves and v_permlane32_swap, 0: with lane shuffles through the LDS hardware
 #endif
 #ifndef MMV_LOAD_PRIO
 #define MMV_LOAD_PRIO 1   // wave priority while a workgroup takes its ticket and issues its loads (0: off)
@@ -190,17 +190,32 @@ template <int kCtrl, int kRowMask> __device__ __forceinline__ uint32_t dpp_or_ze
 
 // Both halves of the wave, each broadcast to all 64 lanes: lo[l] = v[l mod 32], hi[l] = v[32 + l mod 32]
 // (one v_permlane32_swap, no LDS hardware).
+// Lane exchanges come in two forms: through the vector ALU (DPP moves, v_permlane32_swap) or through
+// the LDS hardware (ds_bpermute: what __shfl compiles to).  The ALU form has a tenth of the latency and
+// made the segmented sum 10 % faster; the scan kernels, which wait for memory anyway, ran 0.9 % slower
+// with it (the extra ALU instructions compete with the address arithmetic of the stores) and keep the
+// LDS form.  kAlu selects.
 struct Halves {
     uint32_t lo, hi;
 };
-__device__ __forceinline__ Halves wave_halves(uint32_t v) {
-    const auto r = __builtin_amdgcn_permlane32_swap(v, v, false, false);
-    return {(uint32_t)r[0], (uint32_t)r[1]};
+template <bool kAlu> __device__ __forceinline__ Halves wave_halves(uint32_t v, int lane) {
+    if constexpr (kAlu) {
+        const auto r = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+        return {(uint32_t)r[0], (uint32_t)r[1]};
+    } else {
+        const uint32_t o = __shfl_xor(v, 32);
+        return {lane < 32 ? v : o, lane < 32 ? o : v};
+    }
 }
 
 // Sum over the 64 lanes, the same value in every lane: DPP adds inside the rows of 16 lanes, row totals
 // passed on with row_bcast 15 / 31, the total read from lane 63.
-template <typename T> __device__ __forceinline__ T wave_sum(T v) {
+template <typename T, bool kAlu = true> __device__ __forceinline__ T wave_sum(T v) {
+    if constexpr (!kAlu) {
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) v += from_bits<T>(__shfl_xor(to_bits(v), d));
+        return v;
+    }
     v += from_bits<T>(dpp_or_zero<0x111, 0xF>(to_bits(v)));
     v += from_bits<T>(dpp_or_zero<0x112, 0xF>(to_bits(v)));
     v += from_bits<T>(dpp_or_zero<0x114, 0xF>(to_bits(v)));
@@ -216,7 +231,7 @@ template <typename T> __device__ __forceinline__ T wave_sum(T v) {
 // (Polling 128 or 256 descriptors per round trip was measured 3-9 % slower on long
 // chains: the polls are served by the memory side and compete with the streams,
 // and in steady state the nearest "prefix" is within 64 tiles anyway.)
-template <typename T>
+template <typename T, bool kAlu = true>
 __device__ T lookback(const uint64_t *desc, int tile, int lane, uint32_t *hdr) {
     T carry = T(0);
     int pos = tile - 1;
@@ -238,7 +253,7 @@ __device__ T lookback(const uint64_t *desc, int tile, int lane, uint32_t *hdr) {
             continue;
         }
         const T v = lane <= first_stop ? from_bits<T>((uint32_t)d) : T(0);
-        carry += wave_sum(v);
+        carry += wave_sum<T, kAlu>(v);
         if (stop) break;
         pos -= 64;
     }
@@ -502,9 +517,9 @@ template <typename TT> struct RowAgg;
 __device__ __forceinline__ int last_flag_pos(uint32_t f) { return f ? 31 - __clz(f) : 0; }
 
 template <> struct RowAgg<TI8> {
-    static __device__ __forceinline__ uint32_t run(const v4u *raw, uint32_t F, int lane) {
+    template <bool kAlu> static __device__ __forceinline__ uint32_t run(const v4u *raw, uint32_t F, int lane) {
         const int h = lane >> 5;
-        const Halves Fh = wave_halves(F);   // flag words of rows c and 32 + c
+        const Halves Fh = wave_halves<kAlu>(F, lane);   // flag words of rows c and 32 + c
         uint32_t tot[2];
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
@@ -521,7 +536,7 @@ template <> struct RowAgg<TI8> {
             part = __builtin_amdgcn_sdot4((int)raw[t][1], (int)(uint32_t)(m_lo >> 32), part, false);
             part = __builtin_amdgcn_sdot4((int)raw[t][2], (int)(uint32_t)m_hi, part, false);
             part = __builtin_amdgcn_sdot4((int)raw[t][3], (int)(uint32_t)(m_hi >> 32), part, false);
-            const Halves ph = wave_halves((uint32_t)part);
+            const Halves ph = wave_halves<kAlu>((uint32_t)part, lane);
             tot[t] = ph.lo + ph.hi;
         }
         return lane < 32 ? tot[0] : tot[1];
@@ -529,12 +544,12 @@ template <> struct RowAgg<TI8> {
 };
 
 template <bool kBf16> struct RowAggHalf {
-    static __device__ __forceinline__ float run(const v4u *raw, uint32_t F, int lane) {
+    template <bool kAlu> static __device__ __forceinline__ float run(const v4u *raw, uint32_t F, int lane) {
         typedef _Float16 v2h __attribute__((ext_vector_type(2)));
         typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
         constexpr uint32_t kOne = kBf16 ? 0x3F80u : 0x3C00u;
         const int h = lane >> 5;
-        const Halves Fh = wave_halves(F);   // flag words of rows c and 32 + c
+        const Halves Fh = wave_halves<kAlu>(F, lane);   // flag words of rows c and 32 + c
         float tot[2];
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
@@ -554,7 +569,7 @@ template <bool kBf16> struct RowAggHalf {
                         part = __builtin_amdgcn_fdot2(__builtin_bit_cast(v2h, pair), __builtin_bit_cast(v2h, mask),
                                                       part, false);
                 }
-            const Halves ph = wave_halves(to_bits(part));
+            const Halves ph = wave_halves<kAlu>(to_bits(part), lane);
             tot[t] = from_bits<float>(ph.lo) + from_bits<float>(ph.hi);
         }
         return lane < 32 ? tot[0] : tot[1];
@@ -564,9 +579,9 @@ template <> struct RowAgg<TF16> : RowAggHalf<false> {};
 template <> struct RowAgg<TBF16> : RowAggHalf<true> {};
 
 template <> struct RowAgg<TF32> {
-    static __device__ __forceinline__ float run(const v4u *raw, uint32_t F, int lane) {
+    template <bool kAlu> static __device__ __forceinline__ float run(const v4u *raw, uint32_t F, int lane) {
         const int h = lane >> 5;
-        const Halves Fh = wave_halves(F);   // flag words of rows c and 32 + c
+        const Halves Fh = wave_halves<kAlu>(F, lane);   // flag words of rows c and 32 + c
         float tot[2];
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
@@ -577,7 +592,7 @@ template <> struct RowAgg<TF32> {
 #pragma unroll
                 for (int i = 0; i < 4; ++i)  // position 16h+4q+i
                     part += (16 * h + 4 * q + i >= st) ? from_bits<float>(raw[4 * t + q][i]) : 0.0f;
-            const Halves ph = wave_halves(to_bits(part));
+            const Halves ph = wave_halves<kAlu>(to_bits(part), lane);
             tot[t] = from_bits<float>(ph.lo) + from_bits<float>(ph.hi);
         }
         return lane < 32 ? tot[0] : tot[1];
@@ -615,7 +630,7 @@ template <> __device__ __forceinline__ float raw_elem<TBF16>(const v4u &w, int i
 template <> __device__ __forceinline__ float raw_elem<TF32>(const v4u &w, int i) { return from_bits<float>(w[i]); }
 template <> __device__ __forceinline__ float raw_elem<TSpmv>(const v4u &w, int i) { return from_bits<float>(w[i]); }
 
-template <typename TT>
+template <typename TT, bool kAlu>
 __device__ __forceinline__ void spec_shuffle_tile(const v4u *raw, int lane, uint32_t *rows, int t) {
     typedef typename TT::acc_t A;
     constexpr int kEpl = TT::kEpl;
@@ -629,8 +644,14 @@ __device__ __forceinline__ void spec_shuffle_tile(const v4u *raw, int lane, uint
 #pragma unroll
         for (int i = 1; i < kEpl; ++i) p[i] = p[i - 1] + raw_elem<TT>(raw[ld], i);
         A inc = p[kEpl - 1];
-        // prefix over the kLpr lanes of a row (DPP row_shr moves; a lane whose source lies in another
-        // row does not add)
+        // prefix over the kLpr lanes of a row (a lane whose source lies in another row does not add)
+        if constexpr (!kAlu) {
+#pragma unroll
+            for (int d = 1; d < kLpr; d <<= 1) {
+                const A o = from_bits<A>(__shfl_up(to_bits(inc), d));
+                if ((lane & (kLpr - 1)) >= d) inc += o;
+            }
+        } else {
         if constexpr (kLpr > 1) {
             const A o = from_bits<A>(dpp_or_zero<0x111, 0xF>(to_bits(inc)));
             if ((lane & (kLpr - 1)) >= 1) inc += o;
@@ -642,6 +663,7 @@ __device__ __forceinline__ void spec_shuffle_tile(const v4u *raw, int lane, uint
         if constexpr (kLpr > 4) {
             const A o = from_bits<A>(dpp_or_zero<0x114, 0xF>(to_bits(inc)));
             if ((lane & (kLpr - 1)) >= 4) inc += o;
+        }
         }
         const A ex = inc - p[kEpl - 1];
         uint32_t *rp = rows + (32 * t + kRowsPerLoad * ld + lane / kLpr) * kRowStride + kRowData + kEpl * (lane % kLpr);
@@ -718,6 +740,9 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
     // Matrix-core variant only: there it saves the second 3-way split and 50 registers (fp32 scan
     // 4-5 % faster); in the shuffle variant the same change was measured 3 % slower.
     constexpr bool kKeepRows = MMV_KEEP_ROWS != 0 && kCpw == 1 && kMfma;
+    // lane exchanges through the vector ALU for the sum-type kernels and the 16-bit scans (measured 2 %
+    // faster), through the LDS hardware for the int8 and fp32 scans (0.9 % faster / no difference)
+    constexpr bool kAluLanes = MMV_DPP_SCAN != 0 && (!kScanLike || TT::kEpl == 8);
     constexpr bool kCounts = kOp == kSum || kOp == kSpmvCsr;        // output index = segment ordinal
     // the count of the segments before the tile comes from a table of per-tile counts made by a
     // small kernel before this one, so that no chunk has to wait for it
@@ -774,7 +799,7 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
                 c = P.tile_count[tile];
             } else {
                 for (uint32_t i = lane; i < tile; i += 64) c += P.tile_count[i];
-                c = wave_sum(c);
+                c = wave_sum<uint32_t, kAluLanes>(c);
             }
             if (lane == 0) sm.carry_c = c;
         }
@@ -863,10 +888,10 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
             agg_v = last - from_bits<A>(rows[lane * kRowStride + slot]);
         } else if constexpr (kMfma) {
             if constexpr (K > 1) to_operand_layout<K>(raw[S], rows, lane);
-            agg_v = RowAgg<TT>::run(raw[S], F[S], lane);
+            agg_v = RowAgg<TT>::template run<kAluLanes>(raw[S], F[S], lane);
         } else {
 #pragma unroll
-            for (int t = 0; t < 2; ++t) spec_shuffle_tile<TT>(raw[S] + t * K, lane, rows, t);
+            for (int t = 0; t < 2; ++t) spec_shuffle_tile<TT, kAluLanes>(raw[S] + t * K, lane, rows, t);
             rows[lane * kRowStride + kSlotZero] = 0;
             wave_lds_sync();
             const A last = from_bits<A>(rows[lane * kRowStride + kRowData + 31]);
@@ -881,7 +906,7 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
         A inc_v = agg_v;
         uint32_t inc_f = has_flag;
         uint32_t inc_c = cnt;
-#if MMV_DPP_SCAN
+      if constexpr (kAluLanes) {
         // Kogge-Stone inside the rows of 16 lanes (row_shr 1, 2, 4, 8), then the total of a row of lanes
         // to the next one (row_bcast 15 into lane rows 1 and 3) and of the first 32 lanes to the last 32
         // (row_bcast 31 into lane rows 2 and 3).  A lane without a source gets (0, no flag, 0).
@@ -911,7 +936,7 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
         run_v = ca_f ? ca_v : run_v + ca_v;
         run_f |= ca_f;
         if (kCounts) run_c += (uint32_t)__builtin_amdgcn_readlane((int)inc_c, 63);
-#else
+      } else {
 #pragma unroll
         for (int d = 1; d < 64; d <<= 1) {
             const A ov = from_bits<A>(__shfl_up(to_bits(inc_v), d));
@@ -940,7 +965,7 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
         run_v = ca_f ? ca_v : run_v + ca_v;
         run_f |= ca_f;
         if (kCounts) run_c += __shfl(inc_c, 63);
-#endif
+      }
       }
         if constexpr (!kUnrollChunks) {
             rotate(F);
@@ -1003,7 +1028,7 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
             // ---- step 5c, second half: carry of the predecessor tiles by decoupled look-back ----
             A tile_carry = A(0);
             if (wave == 0) {
-                if (tile > 0) tile_carry = lookback<A>(P.desc_v, (int)tile, lane, P.hdr);
+                if (tile > 0) tile_carry = lookback<A, kAluLanes>(P.desc_v, (int)tile, lane, P.hdr);
                 MMV_STAMP(4);
                 if (lane == 0) {
                     if (!final_now) desc_store(P.desc_v + tile, kStatusPrefix, to_bits(tile_carry + tagg_v));
@@ -1060,7 +1085,7 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
                         SpecMfma<TT>::run(raw[S] + t * K, lane, acc);
                         store_spec_rows(rows, t, lane, acc);
                     } else {
-                        spec_shuffle_tile<TT>(raw[S] + t * K, lane, rows, t);
+                        spec_shuffle_tile<TT, kAluLanes>(raw[S] + t * K, lane, rows, t);
                     }
                 }
                 // ---- step 6: carry into my row ----
