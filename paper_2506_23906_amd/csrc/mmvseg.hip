@@ -77,6 +77,9 @@ namespace {
 #ifndef MMV_DPP_SCAN
 #define MMV_DPP_SCAN 1   // 1: the sum-type kernels exchange lanes with DPP moves and v_permlane32_swap, 0: with lane shuffles through the LDS hardware
 #endif
+#ifndef MMV_ROLL_STEP
+#define MMV_ROLL_STEP 2
+#endif
 #ifndef MMV_LOAD_PRIO
 #define MMV_LOAD_PRIO 1   // wave priority while a workgroup takes its ticket and issues its loads (0: off)
 #endif
@@ -734,7 +737,9 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
     // scan kernels spill registers (measured: 100 to 700 bytes per lane) and so does the shuffle-only
     // int8 sum kernel with its four chunks; the other sum / SpMV kernels do not.
     constexpr bool kUnrollChunks = MMV_UNROLL_CHUNKS != 0 && !kScanLike && (kMfma || kCpw <= 2);
-    constexpr int kChunkUnroll = kUnrollChunks ? kCpw : 1;
+    // chunks per iteration of the chunk loops: all (unrolled), or MMV_ROLL_STEP with the registers
+    // rotated by as many slots afterwards (the moves of a rotation do not depend on the distance)
+    constexpr int kStep = kUnrollChunks ? kCpw : (kCpw >= 2 * MMV_ROLL_STEP && kCpw % MMV_ROLL_STEP == 0 ? MMV_ROLL_STEP : 1);
     // A wave with a single chunk (fp32, SpMV) keeps the row scans of phase A in its LDS rows for
     // phase B instead of making them a second time; with more chunks LDS holds only the last one made.
     // Matrix-core variant only: there it saves the second 3-way split and 50 registers (fp32 scan
@@ -818,9 +823,12 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
     uint32_t run_f = 0, run_c = 0;
 
     // ================= phase A: aggregates =================
-#pragma unroll kChunkUnroll
-    for (int c = 0; c < kCpw; ++c) {
-      const int S = kUnrollChunks ? c : 0;   // register slot of this chunk
+#pragma unroll 1
+    for (int c0 = 0; c0 < kCpw; c0 += kStep) {
+#pragma unroll
+     for (int u = 0; u < kStep; ++u) {
+      const int c = c0 + u;
+      const int S = kUnrollChunks ? c : u;   // register slot of this chunk
       if (c < cpw_t) {
         const uint64_t cb = wave_base + (uint64_t)c * kChunkElems;
         const uint64_t row_start = cb + 32u * lane;  // first element of the row this lane owns
@@ -967,15 +975,19 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
         if (kCounts) run_c += __shfl(inc_c, 63);
       }
       }
+     }
         if constexpr (!kUnrollChunks) {
-            rotate(F);
-            rotate_rows(raw);
-            if constexpr (kProduct) rotate_rows(rawc);
-            rotate(ex_v);
-            rotate(ex_f);
-            rotate(pre_v);
-            rotate(pre_f);
-            if (kCounts) rotate(ex_c);
+#pragma unroll
+            for (int r = 0; r < kStep; ++r) {
+                rotate(F);
+                rotate_rows(raw);
+                if constexpr (kProduct) rotate_rows(rawc);
+                rotate(ex_v);
+                rotate(ex_f);
+                rotate(pre_v);
+                rotate(pre_f);
+                if (kCounts) rotate(ex_c);
+            }
         }
     }
     MMV_STAMP(2);
@@ -1045,9 +1057,12 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
             if (!wex_f) span_carry = tile_carry + wex_v;
             MMV_STAMP(5);
         }
-#pragma unroll kChunkUnroll
-        for (int c = 0; c < kCpw; ++c) {
-            const int S = kUnrollChunks ? c : 0;
+#pragma unroll 1
+        for (int c0 = 0; c0 < kCpw; c0 += kStep) {
+#pragma unroll
+          for (int u = 0; u < kStep; ++u) {
+            const int c = c0 + u;
+            const int S = kUnrollChunks ? c : u;
             // a chunk is "open" when no flag of the tile precedes it
             const bool chunk_open = !(wex_f || __builtin_amdgcn_readfirstlane(pre_f[S]));
             if (c < cpw_t && chunk_open == (pass == 1)) {
@@ -1164,14 +1179,18 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
                 }
                 wave_lds_sync();  // the rows are read before the next chunk overwrites them
             }
+          }
             if constexpr (!kUnrollChunks) {
-                rotate(F);
-                rotate_rows(raw);
-                rotate(ex_v);
-                rotate(ex_f);
-                rotate(pre_v);
-                rotate(pre_f);
-                if (kCounts) rotate(ex_c);
+#pragma unroll
+                for (int r = 0; r < kStep; ++r) {
+                    rotate(F);
+                    rotate_rows(raw);
+                    rotate(ex_v);
+                    rotate(ex_f);
+                    rotate(pre_v);
+                    rotate(pre_f);
+                    if (kCounts) rotate(ex_c);
+                }
             }
         }
     }
