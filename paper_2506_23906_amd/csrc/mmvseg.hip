@@ -753,7 +753,10 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
     // small kernel before this one, so that no chunk has to wait for it
     constexpr bool kProduct = kOp == kSpmv || kOp == kSpmvCsr;      // values are val * x[col]
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // the wave index as a scalar: everything derived from it (the wave's span, chunk bases, the
+    // "whole chunk inside the vector" tests, base addresses of loads and stores) then lives in scalar
+    // registers and costs no vector instructions
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const uint64_t n = P.n;
     uint32_t *rows = sm.rows[wave];
     MMV_STAMP(1);
@@ -1241,7 +1244,7 @@ __global__ __launch_bounds__(TT::kWaves * 64, MMV_MIN_WAVES_PER_SIMD) void seg_k
         }
     }
     if (!P.ordered) __syncthreads();
-    const uint32_t tile = P.ordered ? blockIdx.x : sm.tile;
+    const uint32_t tile = __builtin_amdgcn_readfirstlane(P.ordered ? blockIdx.x : sm.tile);   // a scalar, like the wave index
 #ifdef MMV_TRACE
     if (tid == 0 && P.trace) P.trace[(uint64_t)tile * 8] = t_begin;
 #endif
