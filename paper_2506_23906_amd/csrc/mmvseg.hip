@@ -695,8 +695,8 @@ __device__ __forceinline__ void spec_shuffle_tile(const v4u *raw, int lane, uint
 //      the carries and stores.  Chunks that start after a flag of the tile go first;
 //      chunks that continue a segment of an earlier tile go last, after wave 0 has
 //      looked back for the carry of the predecessor tiles.
-// The chunk loops are rolled: the per-chunk registers are rotated so that the loop
-// body always works on slot 0 (keeps the code small).
+// The chunk loops of the scan kernels are rolled: the per-chunk registers are rotated so that
+// the loop body always works on the first slots (unrolled, these kernels spill).
 
 template <typename T, int N> __device__ __forceinline__ void rotate(T (&a)[N]) {
     const T first = a[0];
@@ -733,7 +733,7 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
     constexpr int K = 16 / TT::kEpl;             // 128-bit words per lane and 32x32 tile
     constexpr bool kScanLike = kOp == kScan || kOp == kPlainScan;   // every element is an output
     // The chunk loops are either rolled, with the per-chunk registers rotated so that the body always
-    // works on slot 0 (about 45 moves per chunk and phase, small code), or unrolled.  Unrolled, the
+    // works on the first slot(s) (about 45 moves per rotation and phase, small code), or unrolled.  Unrolled, the
     // scan kernels spill registers (measured: 100 to 700 bytes per lane) and so does the shuffle-only
     // int8 sum kernel with its four chunks; the other sum / SpMV kernels do not.
     constexpr bool kUnrollChunks = MMV_UNROLL_CHUNKS != 0 && !kScanLike && (kMfma || kCpw <= 2);
