@@ -1430,13 +1430,18 @@ __global__ __launch_bounds__(256) void unpack_flags_kernel(const uint32_t *fw, u
 // x == nullptr the positions themselves are compressed.  The mask is bit-packed; the output
 // index of an entry is the number of set bits before it (the scan of the mask in the paper's
 // COMPRESS), found per tile from popcounts and across tiles by decoupled look-back.
-// A wave owns 4096 consecutive positions: lane j holds the 64-bit mask word j, and for every
-// word the wave reads only the selected entries (one coalesced load, skipped when the word is
-// empty) and writes them to consecutive output slots; a wave with few selected entries lets
-// every lane walk its own word instead.
+// A wave owns 64 * kWords consecutive positions (kWords = 64 or 16): lane j < kWords holds the
+// 64-bit mask word j, and for every word the wave reads only the selected entries (one coalesced
+// load, skipped when the word is empty) and writes them to consecutive output slots; a wave with
+// few selected entries lets every lane walk its own word instead.  Short masks take the short
+// spans: four times the waves, a quarter of the words each wave visits one after the other.
 constexpr int kCompressWaves = 8;
 constexpr int kCompressTile = kCompressWaves * 4096;
+constexpr uint64_t kCompressShortN = 1ull << 22;   // masks up to this length take 16 words per wave
+inline int compress_words(uint64_t n) { return n <= kCompressShortN ? 16 : 64; }
+inline uint64_t compress_tile(uint64_t n) { return (uint64_t)kCompressWaves * 64u * compress_words(n); }
 
+template <int kWords>
 __global__ __launch_bounds__(kCompressWaves * 64) void compress_kernel(
     const uint32_t *__restrict__ x, const uint32_t *__restrict__ mw, uint64_t n, uint32_t *__restrict__ out,
     uint64_t out_cap, uint64_t *__restrict__ count, uint32_t *hdr, uint64_t *desc, uint32_t num_tiles,
@@ -1447,10 +1452,11 @@ __global__ __launch_bounds__(kCompressWaves * 64) void compress_kernel(
     if (tid == 0) s_tile = __hip_atomic_fetch_add(hdr + kHdrTicket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
     const uint32_t tile = s_tile;
-    const uint64_t span = (uint64_t)tile * kCompressTile + (uint64_t)wave * 4096;  // first position of my wave
+    constexpr uint32_t kSpan = 64u * kWords;                                        // positions of a wave
+    const uint64_t span = ((uint64_t)tile * kCompressWaves + wave) * kSpan;          // first position of my wave
     const uint64_t p0 = span + 64u * lane;                                          // first position of my word
     uint64_t m = 0;
-    if (p0 < n) {
+    if (lane < kWords && p0 < n) {
         const uint64_t wi = p0 >> 5;
         m = mw[wi];
         if (p0 + 32 < n) m |= (uint64_t)mw[wi + 1] << 32;
@@ -1484,8 +1490,8 @@ __global__ __launch_bounds__(kCompressWaves * 64) void compress_kernel(
     __syncthreads();
     // output index of the first selected entry of word j of my wave (lane j holds it)
     const uint64_t word_base = (uint64_t)s_carry + wave_ex + (inc - cnt);
-    if (__builtin_amdgcn_readlane((int)inc, 63) <= 256) {
-        // few selected entries in my wave's 4096 positions: every lane walks the set bits of its own
+    if (__builtin_amdgcn_readlane((int)inc, 63) <= 4 * kWords) {
+        // few selected entries in my wave's positions: every lane walks the set bits of its own
         // word (a handful of independent loads per lane) instead of the wave visiting all 64 words
         uint64_t mm = m, k = word_base;
         while (mm) {
@@ -1501,7 +1507,7 @@ __global__ __launch_bounds__(kCompressWaves * 64) void compress_kernel(
     const uint32_t base_lo = (uint32_t)word_base, base_hi = (uint32_t)(word_base >> 32);
     const uint64_t lane_below = (1ull << lane) - 1ull;
 #pragma unroll 8
-    for (int j = 0; j < 64; ++j) {
+    for (int j = 0; j < kWords; ++j) {
         const uint64_t mj = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)m_hi, j) << 32) |
                             (uint32_t)__builtin_amdgcn_readlane((int)m_lo, j);
         const uint64_t bj = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)base_hi, j) << 32) |
@@ -1775,7 +1781,7 @@ struct CompressLayout {
 };
 CompressLayout compress_layout(mmv_flag_fmt ff, uint64_t n) {
     CompressLayout L;
-    L.tiles = (n + kCompressTile - 1) / kCompressTile;
+    L.tiles = (n + compress_tile(n) - 1) / compress_tile(n);
     size_t off = kHdrBytes;
     L.desc = off;
     off += round256(L.tiles * 8);
@@ -2026,9 +2032,14 @@ mmv_status compress_impl(const void *d_x, const void *d_mask, uint64_t n, void *
         mw = packed;
     }
     if (tl_ev_start && hipEventRecord(tl_ev_start, s) != hipSuccess) return MMV_ERR_HIP;
-    compress_kernel<<<(unsigned)L.tiles, kCompressWaves * 64, 0, s>>>(
-        (const uint32_t *)d_x, mw, n, (uint32_t *)d_out, out_capacity, d_count, (uint32_t *)ws,
-        (uint64_t *)(ws + L.desc), (uint32_t)L.tiles, d_needed);
+    if (compress_words(n) == 16)
+        compress_kernel<16><<<(unsigned)L.tiles, kCompressWaves * 64, 0, s>>>(
+            (const uint32_t *)d_x, mw, n, (uint32_t *)d_out, out_capacity, d_count, (uint32_t *)ws,
+            (uint64_t *)(ws + L.desc), (uint32_t)L.tiles, d_needed);
+    else
+        compress_kernel<64><<<(unsigned)L.tiles, kCompressWaves * 64, 0, s>>>(
+            (const uint32_t *)d_x, mw, n, (uint32_t *)d_out, out_capacity, d_count, (uint32_t *)ws,
+            (uint64_t *)(ws + L.desc), (uint32_t)L.tiles, d_needed);
     const hipError_t e = hipGetLastError();
     if (tl_ev_stop && hipEventRecord(tl_ev_stop, s) != hipSuccess) return MMV_ERR_HIP;
     return e == hipSuccess ? MMV_OK : MMV_ERR_HIP;
@@ -2442,7 +2453,7 @@ const char *mmv_status_string(mmv_status s) {
 
 uint32_t mmv_tile_elems(mmv_op op, mmv_dtype dt, uint64_t n) {
     if (!valid_dtype(dt)) return 0;
-    if (op == MMV_OP_COMPRESS) return kCompressTile;
+    if (op == MMV_OP_COMPRESS) return (uint32_t)compress_tile(n);
     if (op != MMV_OP_SEGSCAN && op != MMV_OP_SEGSUM && op != MMV_OP_SCAN && !is_spmv(op)) return 0;
     const TilePlan p = tile_plan(op, is_spmv(op) ? MMV_F32_F32 : dt, n);
     return p.big_tiles ? p.big_elems : p.tail_elems;
