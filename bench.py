@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the segmented-operation hot path on one MI355X.
 
-Default run (the contract line): workload 3 of the benchmark spec, the segmented
+Default run (the contract line): the headline workload, the segmented
 inclusive scan of n = 2^28 int8 values into int32 with segment lengths uniform
 in [1, 4096] and bit-packed flags.  One "step" is one mmv_segscan call on
 inputs that already sit in HBM: workspace reset kernel + the single-pass scan
@@ -138,8 +138,8 @@ def main() -> int:
     global EVENTS_EVERY
     EVENTS_EVERY = max(1, args.events_every)
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (every box has one GPU; see DESIGN.md, "
-              "'How the path would shard'); --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (the path would shard by contiguous ranges with one "
+              "exchange of per-GPU carries; that is design only); --gpus %d is not supported" % args.gpus, file=sys.stderr)
         return 2
 
     import torch
