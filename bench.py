@@ -317,6 +317,13 @@ def write_report(args, events: HipEvents) -> None:
     for variant in ("mfma", "shuffle"):
         run("3 segscan i8 n=2^%d U{1..4096} %s" % (args.log2n, variant), n, n * 5 + n // 8,
             lambda: B.mmv_segscan(xt, ft, n=n, z=zt, variant=variant, ws=ws), ws)
+    # the same call with one flag byte per element (the paper's flag format): a packing kernel runs first
+    f8 = torch.from_numpy(f).cuda()
+    ws8 = B.new_workspace(B.MMV_OP_SEGSCAN, B.MMV_I8_I32, B.MMV_FLAGS_U8, n)
+    ms = call_ms(lambda: B.mmv_segscan(xt, f8, n=n, z=zt, ws=ws8))
+    emit(workload="3 segscan i8 n=2^%d U{1..4096}, one flag byte per element (whole call)" % args.log2n, n=n, ms=ms,
+         gelem_s=n / ms / 1e6, gb_s=n * 6 / ms / 1e6, frac_of_peak=n * 6 / ms / 1e6 / HBM_PEAK_GBS)
+    del f8, ws8
     for density in (0.0, 1e-4, 1e-3, 3e-3, 1e-2, 0.1, 1.0):
         fd = torch.from_numpy(W.pack_flags(W.uniform_density_flags(n, density, 77)).view(np.int32)).cuda()
         for variant in ("mfma", "shuffle"):
