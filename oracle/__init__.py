@@ -37,14 +37,24 @@ _LIB = os.path.join(_HERE, "libmmvseg_oracle.so")
 _lib = None
 
 
-def build(force: bool = False) -> str:
-    """Compile the C oracle (-O2, no fast-math, single thread)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        tmp = _LIB + ".tmp.%d" % os.getpid()
+_HOST_SRC = os.path.join(_HERE, "host_threads.c")
+_HOST_LIB = os.path.join(_HERE, "libmmvseg_host_threads.so")
+_host_lib = None
+
+
+def _compile(src: str, lib: str, force: bool, extra=()) -> str:
+    if force or not os.path.exists(lib) or os.path.getmtime(lib) < os.path.getmtime(src):
+        tmp = lib + ".tmp.%d" % os.getpid()
         subprocess.check_call(["gcc", "-O2", "-std=c11", "-Wall", "-Wextra", "-fPIC", "-shared",
-                               "-fno-fast-math", "-o", tmp, _SRC])
-        os.replace(tmp, _LIB)
-    return _LIB
+                               "-fno-fast-math", *extra, "-o", tmp, src])
+        os.replace(tmp, lib)
+    return lib
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle (-O2, no fast-math, single thread) and the threaded host baseline beside it."""
+    _compile(_HOST_SRC, _HOST_LIB, force, ("-pthread",))
+    return _compile(_SRC, _LIB, force)
 
 
 def _load():
@@ -253,3 +263,26 @@ def spmv_csr(n_rows: int, n_cols: int, rowptr, col, val, x) -> np.ndarray:
     if bad:
         raise ValueError("row pointers not monotone or column index out of range")
     return y
+
+
+def host_threads_segscan(x, f, threads: int) -> np.ndarray:
+    """NOT the oracle: the chunked segmented scan on `threads` host threads (host_threads.c), int8 -> int32,
+    the all-cores baseline of the benchmark.  Checked against `segscan` in tests/test_host_threads.py."""
+    global _host_lib
+    x = np.ascontiguousarray(x)
+    if x.dtype != np.int8:
+        raise TypeError("the threaded host baseline takes int8 values")
+    n = x.shape[0]
+    f = _flags_u8(f, n)
+    if _host_lib is None:
+        build()
+        lib = ctypes.CDLL(_HOST_LIB)
+        lib.host_threads_segscan_i8.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64, ctypes.c_void_p,
+                                                ctypes.c_int]
+        lib.host_threads_segscan_i8.restype = ctypes.c_int
+        _host_lib = lib
+    z = np.empty(n, dtype=np.int32)
+    used = _host_lib.host_threads_segscan_i8(_ptr(x), _ptr(f), n, _ptr(z), int(threads))
+    if used < 0:
+        raise RuntimeError("host_threads_segscan_i8 failed (threads=%r)" % (threads,))
+    return z
