@@ -1,0 +1,230 @@
+// libmmvseg, part of the one translation unit mmvseg.hip (included there, in order).
+// The small kernels around the single-pass kernel: workspace reset, per-tile counts, flag packing from
+// bytes / COO rows / CSR row pointers, and the benchmark's reference kernels (streaming copy, gather).
+#pragma once
+
+namespace {
+
+// ---- auxiliary kernels -------------------------------------------------------------------------------------
+
+// Zero fills two ranges (workspace words and, for SpMV, y) with 32-bit stores.
+__global__ __launch_bounds__(256) void fill_zero_kernel(uint32_t *a, uint64_t na, uint32_t *b, uint64_t nb) {
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < na; i += stride) a[i] = 0;
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < nb; i += stride) b[i] = 0;
+}
+
+// Segmented sum, step "scan of the end markers" of COMPRESS (proof of the SCD / SSCR theorem)
+// at tile granularity: workgroup b counts the segment starts inside tile b (position 0 is not
+// counted: it opens segment 0 whatever its flag says; bits at or beyond n are not counted).  The
+// same launch zeroes the header and the descriptors of the main kernel.
+__global__ __launch_bounds__(256) void count_tiles_kernel(uint32_t *zero, uint64_t zero_words, const uint32_t *fw,
+                                                          uint64_t n, uint32_t big_tiles, uint32_t big_elems,
+                                                          uint32_t tail_elems, uint32_t *cnt) {
+    __shared__ uint32_t s_part[4];
+    const uint32_t b = blockIdx.x, tid = threadIdx.x;
+    for (uint64_t i = (uint64_t)b * 256 + tid; i < zero_words; i += (uint64_t)gridDim.x * 256) zero[i] = 0;
+    const uint64_t base = b < big_tiles ? (uint64_t)b * big_elems
+                                        : (uint64_t)big_tiles * big_elems + (uint64_t)(b - big_tiles) * tail_elems;
+    const uint64_t elems = b < big_tiles ? big_elems : tail_elems;
+    const uint64_t end = base + elems < n ? base + elems : n;
+    uint32_t sum = 0;
+    for (uint64_t w = (base >> 5) + tid; w < ((end + 31) >> 5); w += 256) {   // tiles begin on word borders
+        uint32_t v = fw[w];
+        if (w == 0) v &= ~1u;
+        if ((w + 1) * 32 > n) v &= (1u << (uint32_t)(n - w * 32)) - 1u;
+        sum += __popc(v);
+    }
+    sum = wave_sum(sum);
+    if ((tid & 63) == 0) s_part[tid >> 6] = sum;
+    __syncthreads();
+    if (tid == 0) cnt[b] = s_part[0] + s_part[1] + s_part[2] + s_part[3];
+}
+
+// Exclusive prefix sums of the per-tile counts, in place, by one workgroup; the total (+ 1 for
+// segment 0) is the number of segments.
+__global__ __launch_bounds__(1024) void scan_counts_kernel(uint32_t *cnt, uint32_t num_tiles, uint64_t *nseg) {
+    __shared__ uint32_t s_wave[16];
+    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    uint32_t running = 0;
+    for (uint32_t base = 0; base < num_tiles; base += 1024) {
+        const uint32_t i = base + tid;
+        const uint32_t v = i < num_tiles ? cnt[i] : 0u;
+        uint32_t inc = v;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const uint32_t o = __shfl_up(inc, d);
+            if (lane >= (uint32_t)d) inc += o;
+        }
+        if (lane == 63) s_wave[wave] = inc;
+        __syncthreads();
+        uint32_t before = 0, total = 0;
+#pragma unroll
+        for (uint32_t w = 0; w < 16; ++w) {
+            if (w == wave) before = total;
+            total += s_wave[w];
+        }
+        if (i < num_tiles) cnt[i] = running + before + inc - v;
+        running += total;
+        __syncthreads();
+    }
+    if (tid == 0) *nseg = (uint64_t)running + 1u;
+}
+
+// One byte per element -> one bit per element; a thread builds one 32-bit word.
+__global__ __launch_bounds__(256) void pack_flags_kernel(const uint8_t *f, uint64_t n, uint32_t *words,
+                                                         uint64_t nwords) {
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t w = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; w < nwords; w += stride) {
+        uint32_t bits = 0;
+        const uint64_t e0 = w * 32;
+        if (e0 + 32 <= n) {
+            const v4u a = *reinterpret_cast<const v4u *>(f + e0), b = *reinterpret_cast<const v4u *>(f + e0 + 16);
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    bits |= (((a[k] >> (8 * j)) & 0xFFu) ? 1u : 0u) << (4 * k + j);
+                    bits |= (((b[k] >> (8 * j)) & 0xFFu) ? 1u : 0u) << (16 + 4 * k + j);
+                }
+        } else {
+            for (int i = 0; i < 32 && e0 + i < n; ++i) bits |= (f[e0 + i] ? 1u : 0u) << i;
+        }
+        words[w] = bits;
+    }
+}
+
+// One wave looks at 512 pairs of neighbouring column indices spread over the matrix and notes in the
+// (zeroed) workspace header whether most of them are consecutive, as in blocked and banded matrices.
+__device__ __forceinline__ void sample_column_runs(const int32_t *col, uint64_t nnz, uint32_t *hdr, int lane) {
+    const uint64_t stride = nnz / 512 > 0 ? nnz / 512 : 1;
+    uint32_t runs = 0, pairs = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const uint64_t p = (uint64_t)(lane * 8 + j) * stride;
+        if (p + 1 < nnz) {
+            ++pairs;
+            runs += col[p + 1] == col[p] + 1 ? 1u : 0u;
+        }
+    }
+    runs = wave_sum(runs);
+    pairs = wave_sum(pairs);
+    if (lane == 0 && 2 * runs > pairs) hdr[kHdrColumnRuns] = 1u;
+}
+
+// Segment-start flags of a row-sorted COO matrix, f(e) = [e == 0 or row(e) != row(e-1)],
+// bit-packed.  A lane takes four consecutive entries (one 128-bit load) and the entry before
+// them from the lane below; eight lanes OR their nibbles into one flag word.
+__global__ __launch_bounds__(256) void row_flags_kernel(const int32_t *row, uint64_t nnz, uint32_t *words,
+                                                        const int32_t *col, uint32_t *hdr) {
+    const int lane = threadIdx.x & 63;
+    if (blockIdx.x == 0 && threadIdx.x < 64) sample_column_runs(col, nnz, hdr, lane);
+    const uint64_t wave0 = ((uint64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * 1024;  // four rounds of 256 entries
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint64_t e0 = wave0 + 256u * j + 4u * lane;
+        v4i r = {0, 0, 0, 0};
+        if (e0 + 4 <= nnz) {
+            r = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(row + e0));
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (e0 + i < nnz) r[i] = row[e0 + i];
+        }
+        int prev = __shfl_up(r[3], 1);
+        if (lane == 0) prev = (e0 > 0 && e0 - 1 < nnz) ? row[e0 - 1] : r[0];
+        uint32_t nib = (e0 == 0 || r[0] != prev) ? 1u : 0u;
+#pragma unroll
+        for (int i = 1; i < 4; ++i) nib |= (r[i] != r[i - 1] ? 1u : 0u) << i;
+        const uint32_t valid = e0 >= nnz ? 0u : (nnz - e0 >= 4 ? 0xFu : (1u << (uint32_t)(nnz - e0)) - 1u);
+        uint32_t v = (nib & valid) << (4 * (lane & 7));
+        v |= __shfl_xor(v, 1);
+        v |= __shfl_xor(v, 2);
+        v |= __shfl_xor(v, 4);
+        const uint64_t w = ((wave0 + 256u * j) >> 5) + (lane >> 3);
+        if ((lane & 7) == 0 && w * 32 < nnz) words[w] = v;
+    }
+}
+
+// Row pointers of a CSR matrix -> (a) bit-packed segment-start flags over the non-zeros (a row
+// with entries sets the bit of its first entry; rows that share a word meet in an atomic OR on
+// a zeroed word), (b) the bit-packed mask of rows that have entries (one ballot per 64 rows),
+// (c) the number of segment starts inside every tile of the main kernel (position 0 not counted,
+// as in count_tiles_kernel; the rows of a wave that start in the same tile share one atomic add
+// on a zeroed table) and (d) the mark that some row is empty.
+__global__ __launch_bounds__(256) void csr_flags_kernel(const int32_t *rowptr, uint64_t n_rows, uint32_t *fw,
+                                                        uint32_t *rowmask, uint32_t *hdr, uint32_t big_tiles,
+                                                        uint32_t big_elems, uint32_t tail_elems, uint32_t *tile_count,
+                                                        const int32_t *col, uint64_t nnz) {
+    const int lane = threadIdx.x & 63;
+    if (blockIdx.x == 0 && threadIdx.x < 64) sample_column_runs(col, nnz, hdr, lane);
+    const uint64_t r = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    bool nonempty = false;
+    uint32_t tile = 0xFFFFFFFFu;   // tile of the first entry of a row that is counted
+    if (r < n_rows) {
+        const int32_t a = rowptr[r], b = rowptr[r + 1];
+        nonempty = b > a;
+        if (nonempty) {
+            atomicOr(fw + ((uint32_t)a >> 5), 1u << ((uint32_t)a & 31u));
+            const uint64_t big_total = (uint64_t)big_tiles * big_elems;
+            if (a > 0) tile = (uint32_t)a < big_total ? (uint32_t)a / big_elems
+                                                      : big_tiles + (uint32_t)(((uint32_t)a - big_total) / tail_elems);
+        }
+    }
+    const uint64_t m = __ballot(nonempty);
+    // a matrix none of whose rows is empty needs no row map: segment k is row k
+    if (__ballot(r < n_rows && !nonempty) != 0 && lane == 0) hdr[kHdrEmptyRows] = 1u;
+    uint64_t todo = __ballot(tile != 0xFFFFFFFFu);
+    while (todo) {   // one round per distinct tile among the rows of the wave
+        const int first = __ffsll((unsigned long long)todo) - 1;
+        const uint32_t t = __shfl(tile, first);
+        const uint64_t same = __ballot(tile == t);
+        if (lane == first) atomicAdd(tile_count + t, (uint32_t)__popcll((unsigned long long)same));
+        todo &= ~same;
+    }
+    const uint64_t r0 = r - lane;
+    if (lane == 0 && r0 < n_rows) {
+        rowmask[r0 >> 5] = (uint32_t)m;
+        if (r0 + 32 < n_rows) rowmask[(r0 >> 5) + 1] = (uint32_t)(m >> 32);
+    }
+}
+
+// Random-access reference for SpMV: streams val and col with 128-bit loads, gathers x[col] and
+// keeps one partial sum per thread: everything the product vector of SpMV costs, and nothing of
+// the segmented sum.  A column index at or beyond n_cols reads x[0] instead (no access out of bounds).
+constexpr int kGatherRefBlocks = 8192;
+__global__ __launch_bounds__(256) void gather_reference_kernel(const v4u *val, const v4u *col, uint64_t quads,
+                                                               uint32_t n_cols, const float *x, float *partial) {
+    float acc = 0.0f;
+    const uint64_t stride = (uint64_t)gridDim.x * 256;
+    for (uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x; i < quads; i += stride) {
+        const v4u v = __builtin_nontemporal_load(val + i);
+        const v4u c = __builtin_nontemporal_load(col + i);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) acc += from_bits<float>(v[k]) * x[c[k] < n_cols ? c[k] : 0u];
+    }
+    partial[(uint64_t)blockIdx.x * 256 + threadIdx.x] = acc;
+}
+
+// Streaming reference: 128-bit non-temporal reads and writes, kIn input chunks and kOut
+// output chunks per thread, both striped across the workgroup; one workgroup per 256
+// units (measured faster than a persistent grid-stride loop on this chip).
+template <int kIn, int kOut>
+__global__ __launch_bounds__(256) void stream_copy_kernel(const v4u *src, v4u *dst, uint64_t units) {
+    const uint64_t u0 = (uint64_t)blockIdx.x * 256;
+    v4u acc = {0, 0, 0, 0};
+#pragma unroll
+    for (int i = 0; i < kIn; ++i) {
+        const uint64_t idx = u0 * kIn + (uint64_t)i * 256 + threadIdx.x;
+        if (idx < units * kIn) acc ^= __builtin_nontemporal_load(src + idx);
+    }
+#pragma unroll
+    for (int i = 0; i < kOut; ++i) {
+        const uint64_t idx = u0 * kOut + (uint64_t)i * 256 + threadIdx.x;
+        if (idx < units * kOut) __builtin_nontemporal_store(acc + (unsigned)i, dst + idx);
+    }
+    if (kOut == 0 && acc[0] == 0x9E3779B9u && acc[1] == 0x7F4A7C15u && acc[2] == 1u && acc[3] == 2u)
+        dst[0] = acc;  // keeps the reads alive; practically never taken
+}
+
+}  // namespace

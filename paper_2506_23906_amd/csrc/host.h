@@ -1,0 +1,398 @@
+// libmmvseg, part of the one translation unit mmvseg.hip (included there, in order).
+// Host side: argument checks, workspace layouts, tile plans and the launch sequences behind the C ABI.
+#pragma once
+
+namespace {
+
+// ---- host side -------------------------------------------------------------------------------------------------
+
+inline size_t round256(size_t b) { return (b + 255) & ~(size_t)255; }
+// Tile plan.  A tile costs one ticket (about 11 ns, serialised), so tiles are as large as the
+// registers allow: kMaxCpw chunks of 2048 elements per wave.  The workgroups of the last round
+// would leave most of the chip idle while they finish, so the end of the vector is cut into
+// shorter tiles (one chunk per wave); inputs that fit into one round of resident workgroups
+// get equal tiles of just the size that gives every workgroup one.
+constexpr uint64_t kResident = MMV_MIN_TILES;   // workgroups resident at once (2 per compute unit)
+#ifndef MMV_TAIL_ROUNDS
+#define MMV_TAIL_ROUNDS 1
+#endif
+#ifndef MMV_TAIL_TILES
+#define MMV_TAIL_TILES (MMV_TAIL_ROUNDS * kResident / 2)   // half a round measured best (256, 512, 768 within 1.5 %)
+#endif
+#ifndef MMV_TAIL_CPW
+#define MMV_TAIL_CPW 1
+#endif
+constexpr uint64_t kTailTiles = MMV_TAIL_TILES;  // short tiles at the end of a long vector
+constexpr uint64_t kCountSumTiles = 2048;        // up to this many tiles the segmented sum needs no prefix kernel
+inline bool is_spmv(mmv_op op) { return op == MMV_OP_SPMV_COO || op == MMV_OP_SPMV_CSR; }
+inline int max_cpw(mmv_op op, mmv_dtype dt) {
+    if (is_spmv(op)) return TSpmv::kMaxCpw;
+    switch (dt) {
+        case MMV_F32_F32: return TF32::kMaxCpw;
+        case MMV_F16_F32: return TF16::kMaxCpw;
+        case MMV_BF16_F32: return TBF16::kMaxCpw;
+        case MMV_I8_I32: return TI8::kMaxCpw;
+    }
+    return 1;
+}
+inline int waves_of(mmv_op op, mmv_dtype dt) {
+    if (is_spmv(op)) return TSpmv::kWaves;
+    switch (dt) {
+        case MMV_F32_F32: return TF32::kWaves;
+        case MMV_F16_F32: return TF16::kWaves;
+        case MMV_BF16_F32: return TBF16::kWaves;
+        case MMV_I8_I32: return TI8::kWaves;
+    }
+    return 1;
+}
+struct TilePlan {
+    uint64_t big_tiles, tail_tiles;
+    uint32_t big_elems, tail_cpw, tail_elems;
+    uint64_t tiles() const { return big_tiles + tail_tiles; }
+};
+inline TilePlan tile_plan(mmv_op op, mmv_dtype dt, uint64_t n) {
+    TilePlan p;
+    const uint64_t unit = (uint64_t)waves_of(op, dt) * kChunkElems;  // one chunk per wave
+    const int cpw = max_cpw(op, dt);
+    p.big_elems = (uint32_t)(unit * cpw);
+    if (n <= kResident * p.big_elems) {
+        // one round: equal tiles, as small as gives every resident workgroup at most one
+        uint64_t c = (n + kResident * unit - 1) / (kResident * unit);
+        if (c < 1) c = 1;
+        if (c > (uint64_t)cpw) c = cpw;
+        p.tail_cpw = (uint32_t)c;
+        p.big_tiles = 0;
+    } else {
+        p.tail_cpw = MMV_TAIL_CPW < cpw ? MMV_TAIL_CPW : cpw;
+        const uint64_t tail = kTailTiles * unit * p.tail_cpw < n ? kTailTiles * unit * p.tail_cpw : n;
+        p.big_tiles = (n - tail) / p.big_elems;
+    }
+    p.tail_elems = (uint32_t)(unit * p.tail_cpw);
+    const uint64_t rest = n - p.big_tiles * p.big_elems;
+    p.tail_tiles = (rest + p.tail_elems - 1) / p.tail_elems;
+    return p;
+}
+inline uint64_t tiles_for(uint64_t n, mmv_op op, mmv_dtype dt) { return tile_plan(op, dt, n).tiles(); }
+inline bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
+inline bool aligned4(const void *p) { return ((uintptr_t)p & 3u) == 0; }
+
+struct WsLayout {
+    size_t desc_v, desc_c, packed, total;
+};
+
+WsLayout ws_layout(mmv_op op, mmv_dtype dt, mmv_flag_fmt ff, uint64_t n) {
+    WsLayout L;
+    const uint64_t t = tiles_for(n, op, dt);
+    size_t off = kHdrBytes;
+    L.desc_v = off;
+    off += round256(t * 8);
+    L.desc_c = off;
+    if (op == MMV_OP_SEGSUM || op == MMV_OP_SPMV_CSR) off += round256(t * 8);
+    L.packed = off;
+    if (is_spmv(op) || (ff == MMV_FLAGS_U8 && op != MMV_OP_SCAN)) off += round256(((n + 63) / 64) * 8);
+    L.total = off;
+    return L;
+}
+
+// Workspace of COMPRESS: header, one count descriptor per tile, packed mask if the caller gave bytes.
+struct CompressLayout {
+    size_t desc, packed, total;
+    uint64_t tiles;
+};
+CompressLayout compress_layout(mmv_flag_fmt ff, uint64_t n) {
+    CompressLayout L;
+    L.tiles = (n + compress_tile(n) - 1) / compress_tile(n);
+    size_t off = kHdrBytes;
+    L.desc = off;
+    off += round256(L.tiles * 8);
+    L.packed = off;
+    if (ff == MMV_FLAGS_U8) off += round256(((n + 63) / 64) * 8);
+    L.total = off;
+    return L;
+}
+
+// Workspaces of the un-fused compositions: the sub-workspaces of the primitives they call and
+// their intermediate vectors, one after the other (every offset a multiple of 256).
+struct ScdLayout {
+    size_t scan_ws, xhat, packed, fminus, compress_ws, w, total;
+};
+ScdLayout scd_layout(mmv_dtype dt, mmv_flag_fmt ff, uint64_t n, uint64_t cap) {
+    ScdLayout L;
+    size_t off = 0;
+    L.scan_ws = off;
+    off += round256(ws_layout(MMV_OP_SCAN, dt, MMV_FLAGS_PACKED32, n).total);
+    L.xhat = off;
+    off += round256(n * 4);
+    L.packed = off;
+    if (ff == MMV_FLAGS_U8) off += round256(((n + 63) / 64) * 8);
+    L.fminus = off;
+    off += round256(((n + 63) / 64) * 8);
+    L.compress_ws = off;
+    off += round256(compress_layout(MMV_FLAGS_PACKED32, n).total);
+    L.w = off;
+    off += round256((cap < n ? cap : n) * 4 + 16);
+    L.total = off;
+    return L;
+}
+struct SscrLayout {
+    size_t scan_ws_x, scan_ws_f, fhat, f8, packed, fminus, compress_ws, w, total;
+};
+SscrLayout sscr_layout(mmv_dtype dt, mmv_flag_fmt ff, uint64_t n) {
+    SscrLayout L;
+    size_t off = 0;
+    L.scan_ws_x = off;
+    off += round256(ws_layout(MMV_OP_SCAN, dt, MMV_FLAGS_PACKED32, n).total);
+    L.scan_ws_f = off;
+    off += round256(ws_layout(MMV_OP_SCAN, MMV_I8_I32, MMV_FLAGS_PACKED32, n).total);
+    L.fhat = off;
+    off += round256(n * 4);
+    L.f8 = off;
+    off += round256(n + 16);   // flags as one 0 / 1 byte per element for SCAN(f)
+    L.packed = off;
+    if (ff == MMV_FLAGS_U8) off += round256(((n + 63) / 64) * 8);
+    L.fminus = off;
+    off += round256(((n + 63) / 64) * 8);
+    L.compress_ws = off;
+    off += round256(compress_layout(MMV_FLAGS_PACKED32, n).total);
+    L.w = off;
+    off += round256(n * 4 + 16);   // one entry per segment, at most n
+    L.total = off;
+    return L;
+}
+// CSR SpMV: the main kernel's workspace (flags over the non-zeros included), the mask of rows
+// with entries, their indices (rowmap) and the workspace of the COMPRESS that makes them.
+struct CsrLayout {
+    size_t main_ws, rowmask, rowmap, rowcount, compress_ws, total;
+};
+CsrLayout csr_layout(uint64_t n_rows, uint64_t nnz) {
+    CsrLayout L;
+    size_t off = 0;
+    L.main_ws = off;   // the two workspaces that hold tickets and descriptors lie next to each other:
+    off += round256(ws_layout(MMV_OP_SPMV_CSR, MMV_F32_F32, MMV_FLAGS_PACKED32, nnz).total);
+    L.compress_ws = off;   // one fill clears both (and the flag words between them)
+    off += round256(compress_layout(MMV_FLAGS_PACKED32, n_rows).total);
+    L.rowmask = off;
+    off += round256(((n_rows + 63) / 64) * 8);
+    L.rowmap = off;
+    off += round256(n_rows * 4 + 16);
+    L.rowcount = off;
+    off += 256;
+    L.total = off;
+    return L;
+}
+
+#ifdef MMV_TRACE
+uint64_t *g_trace = nullptr;
+#endif
+
+// Optional instrumentation (mmv_set_kernel_events): events recorded right before and
+// right after the main kernel of a call made by this host thread.
+thread_local hipEvent_t tl_ev_start = nullptr, tl_ev_stop = nullptr;
+
+// Workgroups of `kernel` that the current device holds at once (0 when a query fails); asked once
+// per kernel and device.
+uint32_t resident_workgroups(const void *kernel, int threads) {
+    struct Entry {
+        const void *kernel;
+        int device;
+        uint32_t value;
+    };
+    static std::mutex mu;
+    static std::vector<Entry> known;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    std::lock_guard<std::mutex> lock(mu);
+    for (const Entry &e : known)
+        if (e.kernel == kernel && e.device == dev) return e.value;
+    int per_cu = 0, cus = 0;
+    uint32_t value = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, 0) == hipSuccess &&
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && per_cu > 0 && cus > 0)
+        value = (uint32_t)per_cu * (uint32_t)cus;
+    known.push_back({kernel, dev, value});
+    return value;
+}
+
+template <typename TT, int kOp, bool kMfma> hipError_t launch_variant(Params P, hipStream_t s) {
+#ifdef MMV_TRACE
+    P.trace = g_trace;
+#endif
+    const uint32_t resident = resident_workgroups((const void *)seg_kernel<TT, kOp, kMfma>, TT::kWaves * 64);
+    P.ordered = P.num_tiles <= resident ? 1u : 0u;
+    // SpMV: the workgroups of the first round start spread over about one tile time.  Started together
+    // they stay in step (load, gather, compute all at the same time) and the memory pipe idles half the
+    // time; measured 4 to 7 % on the long SpMV kernels, nothing on the scans.
+    P.stagger_wgs = resident;
+    P.stagger_ticks = (kOp == kSpmv || kOp == kSpmvCsr) ? MMV_SPMV_STAGGER_US * 100u : 0u;
+    seg_kernel<TT, kOp, kMfma><<<P.num_tiles, TT::kWaves * 64, 0, s>>>(P, P.hdr + kHdrHints);
+    return hipGetLastError();
+}
+
+template <typename TT, int kOp>
+hipError_t launch_seg(Params P, mmv_variant v, hipStream_t s) {
+    const TilePlan plan = tile_plan((mmv_op)kOp, TT::kDtype, P.n);
+    if (plan.tiles() > 0x7fffffffull) return hipErrorInvalidValue;
+    P.num_tiles = (uint32_t)plan.tiles();
+    P.big_tiles = (uint32_t)plan.big_tiles;
+    P.tail_cpw = plan.tail_cpw;
+    if (tl_ev_start && hipEventRecord(tl_ev_start, s) != hipSuccess) return hipErrorUnknown;
+    if (v == MMV_VARIANT_MFMA) {
+        if (launch_variant<TT, kOp, true>(P, s) != hipSuccess) return hipErrorUnknown;
+    } else {
+        if (launch_variant<TT, kOp, false>(P, s) != hipSuccess) return hipErrorUnknown;
+    }
+    const hipError_t e = hipGetLastError();
+    if (tl_ev_stop && hipEventRecord(tl_ev_stop, s) != hipSuccess) return hipErrorUnknown;
+    return e;
+}
+
+template <int kOp> hipError_t launch_dt(const Params &P, mmv_dtype dt, mmv_variant v, hipStream_t s) {
+    switch (dt) {
+        case MMV_F32_F32: return launch_seg<TF32, kOp>(P, v, s);
+        case MMV_F16_F32: return launch_seg<TF16, kOp>(P, v, s);
+        case MMV_BF16_F32: return launch_seg<TBF16, kOp>(P, v, s);
+        case MMV_I8_I32: return launch_seg<TI8, kOp>(P, v, s);
+    }
+    return hipErrorInvalidValue;
+}
+
+int grid_for(uint64_t items_per_thread_total) {
+    uint64_t blocks = (items_per_thread_total + 255) / 256;
+    if (blocks < 1) blocks = 1;
+    if (blocks > 2048) blocks = 2048;
+    return (int)blocks;
+}
+
+bool valid_dtype(int dt) { return dt >= 0 && dt <= 3; }
+bool valid_ff(int ff) { return ff == 0 || ff == 1; }
+bool valid_variant(int v) { return v == 0 || v == 1; }
+bool valid_elem(int et) { return et == 0 || et == 1; }
+constexpr uint64_t kMaxN = 1ull << 40;
+
+// Common part of scan and sum: checks, workspace reset, flag packing.
+mmv_status prepare(mmv_op op, const void *d_x, const void *d_flags, uint64_t n, mmv_dtype dt, mmv_flag_fmt ff,
+                   mmv_variant v, void *d_ws, size_t ws_bytes, hipStream_t s, Params &P) {
+    if (!valid_dtype(dt) || !valid_ff(ff) || !valid_variant(v) || n > kMaxN) return MMV_ERR_INVALID_ARG;
+    if (!d_x || !d_flags) return MMV_ERR_NULL;
+    if (!aligned16(d_x) || !aligned16(d_flags)) return MMV_ERR_INVALID_ARG;
+    if (!d_ws) return MMV_ERR_NULL;
+    const WsLayout L = ws_layout(op, dt, ff, n);
+    if (((uintptr_t)d_ws & 255u) != 0 || ws_bytes < L.total) return MMV_ERR_WORKSPACE;
+    char *ws = (char *)d_ws;
+    P.x = d_x;
+    P.n = n;
+    P.hdr = (uint32_t *)ws;
+    P.desc_v = (uint64_t *)(ws + L.desc_v);
+    P.num_tiles = (uint32_t)tiles_for(n, op, dt);
+    if (op != MMV_OP_SEGSUM) {   // the segmented sum zeroes them in its tile-count kernel
+        const uint64_t zero_words = L.packed / 4;  // header + descriptors
+        fill_zero_kernel<<<grid_for(zero_words), 256, 0, s>>>((uint32_t *)ws, zero_words, nullptr, 0);
+        if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
+    }
+    if (ff == MMV_FLAGS_U8) {
+        const uint64_t nwords = (n + 31) / 32;
+        uint32_t *packed = (uint32_t *)(ws + L.packed);
+        pack_flags_kernel<<<grid_for(nwords), 256, 0, s>>>((const uint8_t *)d_flags, n, packed, nwords);
+        if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
+        P.fw = packed;
+    } else {
+        P.fw = (const uint32_t *)d_flags;
+    }
+    return MMV_OK;
+}
+
+// Turns timing events off for the sub-calls of a composition (each would re-record them).
+struct EventsOff {
+    hipEvent_t a, b;
+    EventsOff() : a(tl_ev_start), b(tl_ev_stop) { tl_ev_start = tl_ev_stop = nullptr; }
+    ~EventsOff() {
+        tl_ev_start = a;
+        tl_ev_stop = b;
+    }
+};
+
+// SCAN on an input that is already checked; first_one makes element 0 count as 1 (flag bytes).
+mmv_status scan_impl(const void *d_x, uint64_t n, void *d_z, mmv_dtype dt, mmv_variant v, void *d_ws,
+                     size_t ws_bytes, hipStream_t s, bool first_one) {
+    const WsLayout L = ws_layout(MMV_OP_SCAN, dt, MMV_FLAGS_PACKED32, n);
+    if (((uintptr_t)d_ws & 255u) != 0 || ws_bytes < L.total) return MMV_ERR_WORKSPACE;
+    char *ws = (char *)d_ws;
+    Params P = {};
+    P.x = d_x;
+    P.n = n;
+    P.z = d_z;
+    P.hdr = (uint32_t *)ws;
+    P.desc_v = (uint64_t *)(ws + L.desc_v);
+    P.first_one = first_one ? 1u : 0u;
+    const uint64_t zero_words = L.total / 4;
+    fill_zero_kernel<<<grid_for(zero_words), 256, 0, s>>>((uint32_t *)ws, zero_words, nullptr, 0);
+    if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
+    return launch_dt<kPlainScan>(P, dt, v, s) == hipSuccess ? MMV_OK : MMV_ERR_HIP;
+}
+
+// COMPRESS on checked arguments; d_x == nullptr compresses the positions.
+mmv_status compress_impl(const void *d_x, const void *d_mask, uint64_t n, void *d_out, uint64_t out_capacity,
+                         uint64_t *d_count, mmv_flag_fmt ff, void *d_ws, size_t ws_bytes, hipStream_t s,
+                         bool ws_is_reset = false, const uint32_t *d_needed = nullptr) {
+    const CompressLayout L = compress_layout(ff, n);
+    if (((uintptr_t)d_ws & 255u) != 0 || ws_bytes < L.total) return MMV_ERR_WORKSPACE;
+    if (L.tiles > 0x7fffffffull) return MMV_ERR_INVALID_ARG;
+    char *ws = (char *)d_ws;
+    if (!ws_is_reset) {
+        const uint64_t zero_words = L.packed / 4;
+        fill_zero_kernel<<<grid_for(zero_words), 256, 0, s>>>((uint32_t *)ws, zero_words, nullptr, 0);
+        if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
+    }
+    const uint32_t *mw = (const uint32_t *)d_mask;
+    if (ff == MMV_FLAGS_U8) {
+        const uint64_t nwords = (n + 31) / 32;
+        uint32_t *packed = (uint32_t *)(ws + L.packed);
+        pack_flags_kernel<<<grid_for(nwords), 256, 0, s>>>((const uint8_t *)d_mask, n, packed, nwords);
+        if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
+        mw = packed;
+    }
+    if (tl_ev_start && hipEventRecord(tl_ev_start, s) != hipSuccess) return MMV_ERR_HIP;
+    if (compress_words(n) == 16)
+        compress_kernel<16><<<(unsigned)L.tiles, kCompressWaves * 64, 0, s>>>(
+            (const uint32_t *)d_x, mw, n, (uint32_t *)d_out, out_capacity, d_count, (uint32_t *)ws,
+            (uint64_t *)(ws + L.desc), (uint32_t)L.tiles, d_needed);
+    else
+        compress_kernel<64><<<(unsigned)L.tiles, kCompressWaves * 64, 0, s>>>(
+            (const uint32_t *)d_x, mw, n, (uint32_t *)d_out, out_capacity, d_count, (uint32_t *)ws,
+            (uint64_t *)(ws + L.desc), (uint32_t)L.tiles, d_needed);
+    const hipError_t e = hipGetLastError();
+    if (tl_ev_stop && hipEventRecord(tl_ev_stop, s) != hipSuccess) return MMV_ERR_HIP;
+    return e == hipSuccess ? MMV_OK : MMV_ERR_HIP;
+}
+
+mmv_status diff_impl(const void *d_x, uint64_t n, void *d_z, mmv_elem et, hipStream_t s,
+                     const uint64_t *d_limit = nullptr) {
+    const uint64_t blocks = (n + 1023) / 1024;
+    if (blocks > 0x7fffffffull) return MMV_ERR_INVALID_ARG;
+    if (tl_ev_start && hipEventRecord(tl_ev_start, s) != hipSuccess) return MMV_ERR_HIP;
+    if (et == MMV_ELEM_I32)
+        diff_kernel<uint32_t><<<(unsigned)blocks, 256, 0, s>>>((const uint32_t *)d_x, n, (uint32_t *)d_z, d_limit);
+    else
+        diff_kernel<float><<<(unsigned)blocks, 256, 0, s>>>((const uint32_t *)d_x, n, (uint32_t *)d_z, d_limit);
+    const hipError_t e = hipGetLastError();
+    if (tl_ev_stop && hipEventRecord(tl_ev_stop, s) != hipSuccess) return MMV_ERR_HIP;
+    return e == hipSuccess ? MMV_OK : MMV_ERR_HIP;
+}
+
+mmv_status revert_impl(const void *d_xhat, const int32_t *d_fhat, const void *d_w, uint64_t n, uint64_t nw,
+                       void *d_z, mmv_elem et, hipStream_t s) {
+    const uint64_t blocks = (n + 1023) / 1024;
+    if (blocks > 0x7fffffffull) return MMV_ERR_INVALID_ARG;
+    if (tl_ev_start && hipEventRecord(tl_ev_start, s) != hipSuccess) return MMV_ERR_HIP;
+    if (et == MMV_ELEM_I32)
+        revert_kernel<uint32_t><<<(unsigned)blocks, 256, 0, s>>>((const uint32_t *)d_xhat, d_fhat, (const uint32_t *)d_w,
+                                                                  n, nw, (uint32_t *)d_z, nullptr);
+    else
+        revert_kernel<float><<<(unsigned)blocks, 256, 0, s>>>((const uint32_t *)d_xhat, d_fhat, (const uint32_t *)d_w, n,
+                                                               nw, (uint32_t *)d_z, nullptr);
+    const hipError_t e = hipGetLastError();
+    if (tl_ev_stop && hipEventRecord(tl_ev_stop, s) != hipSuccess) return MMV_ERR_HIP;
+    return e == hipSuccess ? MMV_OK : MMV_ERR_HIP;
+}
+
+}  // namespace

@@ -1,0 +1,135 @@
+// libmmvseg, part of the one translation unit mmvseg.hip (included there, in order).
+// Build-time tunables, constants of the tile layout and of the workspace, and the parameter block of the
+// single-pass kernel.
+#pragma once
+
+namespace {
+
+// Tunables (the defaults are the measured best on MI355X; -D overrides are for experiments).
+#ifndef MMV_WAVES
+#define MMV_WAVES 8      // waves per workgroup (int8)
+#endif
+#ifndef MMV_WAVES_F16
+#define MMV_WAVES_F16 8
+#endif
+#ifndef MMV_WAVES_F32
+#define MMV_WAVES_F32 8
+#endif
+#ifndef MMV_WAVES_SPMV
+#define MMV_WAVES_SPMV 8
+#endif
+#ifndef MMV_CPW_I8
+#define MMV_CPW_I8 4     // most chunks per wave, int8 inputs (6 spills registers)
+#endif
+#ifndef MMV_CPW_F16
+#define MMV_CPW_F16 2    // most chunks per wave, 16-bit inputs (4 spills registers)
+#endif
+#ifndef MMV_CPW_F32
+#define MMV_CPW_F32 1    // most chunks per wave, fp32 inputs (2 spills registers)
+#endif
+#ifndef MMV_CPW_SPMV
+#define MMV_CPW_SPMV 1
+#endif
+#ifndef MMV_UNROLL_CHUNKS
+#define MMV_UNROLL_CHUNKS 1   // 1: the chunk loops of the sum / SpMV kernels are unrolled (see kUnrollChunks)
+#endif
+#ifndef MMV_MIN_WAVES_PER_SIMD
+#define MMV_MIN_WAVES_PER_SIMD 4   // register budget: 512 / 4 = 128 VGPRs per lane
+#endif
+#ifndef MMV_SPMV_STAGGER_US
+#define MMV_SPMV_STAGGER_US 15   // SpMV: start times of the first round spread over this many microseconds
+#endif
+#ifndef MMV_KEEP_ROWS
+#define MMV_KEEP_ROWS 1   // 1: single-chunk waves of the matrix-core variant keep their row scans in LDS (see kKeepRows)
+#endif
+#ifndef MMV_DPP_SCAN
+#define MMV_DPP_SCAN 1   // 1: the sum-type kernels exchange lanes with DPP moves and v_permlane32_swap, 0: with lane shuffles through the LDS hardware
+#endif
+#ifndef MMV_ROLL_STEP
+#define MMV_ROLL_STEP 2
+#endif
+#ifndef MMV_LOAD_PRIO
+#define MMV_LOAD_PRIO 1   // wave priority while a workgroup takes its ticket and issues its loads (0: off)
+#endif
+#ifndef MMV_MIN_TILES
+#define MMV_MIN_TILES 512   // workgroups resident at once: 2 per compute unit (LDS)
+#endif
+
+constexpr int kS = 32;                          // row length = MFMA tile edge
+constexpr int kRowsPerChunk = 64;               // a chunk = 64 rows, one per lane = two 32x32 tiles
+constexpr int kChunkElems = kS * kRowsPerChunk; // 2048
+constexpr int kRowStride = 36;                  // dwords per LDS row: 4 meta + 32 values
+constexpr int kSlotF = 0;                       // flag word of the row
+constexpr int kSlotNegCarry = 2;                // minus the carry into the row
+constexpr int kSlotZero = 3;                    // x-bar(-1) = 0
+constexpr int kRowData = 4;
+
+constexpr uint32_t kHdrTicket = 0;              // workspace header words
+constexpr uint32_t kHdrError = 1;
+constexpr uint32_t kHdrHints = 32;              // first of the words the SpMV kernels read as hints (a cache line of
+                                                // their own: the line of the ticket is busy with atomics):
+constexpr uint32_t kHdrEmptyRows = 32;          // CSR SpMV: set when some row of the matrix has no entries
+constexpr uint32_t kHdrColumnRuns = 33;         // SpMV: set when neighbouring entries mostly have consecutive columns
+constexpr size_t kHdrBytes = 256;
+
+constexpr uint64_t kStatusInvalid = 0;          // descriptor not written yet
+constexpr uint64_t kStatusAggregate = 1;        // payload = aggregate of a tile without any flag
+constexpr uint64_t kStatusPrefix = 2;           // payload = carry out of the tile, look-back stops here
+constexpr uint32_t kMaxSpins = 1u << 20;        // bounded wait, then the status word is set
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+typedef short v8s __attribute__((ext_vector_type(8)));
+
+// What a kernel instantiation computes (values match mmv_op where there is one):
+//   kScan       segmented inclusive scan
+//   kSum        segmented sum (one output per segment, index = number of segment ends before it)
+//   kSpmv       row-sorted COO SpMV: products val * x[col], sums scattered to y[row]
+//   kPlainScan  unsegmented inclusive scan (no flag vector: every row aggregate is carried on)
+//   kSpmvCsr    CSR SpMV: as kSpmv, but the sum of the k-th segment goes to y[rowmap[k]]
+enum Op { kScan = 0, kSum = 1, kSpmv = 2, kPlainScan = 3, kSpmvCsr = 7 };
+
+struct Params {
+    const void *x;          // values (scan, sum) / val (spmv)
+    const uint32_t *fw;     // packed flag words (scan, sum)
+    uint64_t n;             // elements / nnz
+    void *z;                // scan output
+    void *out;              // sum output
+    uint64_t out_cap;
+    uint64_t *nseg;
+    const int32_t *row;     // spmv (coo)
+    const uint32_t *rowmap; // spmv (csr): row index of the k-th non-empty row
+    uint32_t first_one;     // plain scan of a flag vector: element 0 counts as 1 whatever it holds
+    const int32_t *col;
+    const float *xv;
+    float *y;
+    uint32_t *hdr;          // workspace header
+    uint64_t *desc_v;       // value descriptors, one per tile
+    const uint32_t *tile_count;  // sum: segment starts per tile (position 0 not counted), or ...
+    uint32_t count_is_prefix;    // ... their exclusive prefix sums already (long vectors)
+    uint32_t num_tiles;
+    uint32_t big_tiles;     // tiles [0, big_tiles) have the full number of chunks per wave ...
+    uint32_t tail_cpw;      // ... the rest have this many (shorter tiles at the end shorten the tail)
+    uint32_t ordered;       // the whole grid is resident at once: workgroup b takes tile b, no ticket
+    uint32_t stagger_wgs;   // workgroups [0, stagger_wgs) start after a delay of up to ...
+    uint32_t stagger_ticks; // ... this many ticks of the 100 MHz clock, spread evenly over them
+#ifdef MMV_TRACE
+    uint64_t *trace;        // 8 timestamps per tile (development builds only)
+#endif
+};
+
+#ifdef MMV_TRACE
+#define MMV_STAMP(k)                                                                     \
+    do {                                                                                 \
+        if (tid == 0 && P.trace) P.trace[(uint64_t)tile * 8 + (k)] = wall_clock64();     \
+    } while (0)
+#else
+#define MMV_STAMP(k) do { } while (0)
+#endif
+
+}  // namespace
