@@ -219,6 +219,9 @@ template <typename TT, int kOp, bool kMfma> hipError_t launch_variant(Params P, 
 #endif
     const uint32_t resident = resident_workgroups((const void *)seg_kernel<TT, kOp, kMfma>, TT::kWaves * 64);
     P.ordered = P.num_tiles <= resident ? 1u : 0u;
+#if defined(MMV_FORCE_ORDERED) && MMV_FORCE_ORDERED
+    P.ordered = 1u;
+#endif
     // SpMV: the workgroups of the first round start spread over about one tile time.  Started together
     // they stay in step (load, gather, compute all at the same time) and the memory pipe idles half the
     // time; measured 4 to 7 % on the long SpMV kernels, nothing on the scans.
