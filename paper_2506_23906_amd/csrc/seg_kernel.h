@@ -74,6 +74,12 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
     // faster), through the LDS hardware for the int8 and fp32 scans (0.9 % faster / no difference)
     constexpr bool kAluLanes = MMV_DPP_SCAN != 0 && (!kScanLike || TT::kEpl == 8);
     constexpr bool kCounts = kOp == kSum || kOp == kSpmvCsr;        // output index = segment ordinal
+    // A chunk in which every position starts a segment is its own result (Algorithm "Revert Speculative
+    // Prefix Sums", the case of all flags set, taken here for 64 rows at once): with 32-bit inputs and one
+    // chunk per wave the striped registers are stored as they are, straight after the load (all-flag
+    // vectors 8 % faster).  Matrix-core variant only: in the other one the test cost 1 % on vectors without
+    // such chunks and gained 2 % on those with.
+    constexpr bool kDenseShortcut = MMV_DENSE_SHORTCUT != 0 && kOp == kScan && sizeof(In) == 4 && kKeepRows;
     // the count of the segments before the tile comes from a table of per-tile counts made by a
     // small kernel before this one, so that no chunk has to wait for it
     constexpr bool kProduct = kOp == kSpmv || kOp == kSpmvCsr;      // values are val * x[col]
@@ -149,6 +155,7 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
     }
     A run_v = A(0);
     uint32_t run_f = 0, run_c = 0;
+    bool dense_chunk = false;   // (uniform) the wave's chunk was stored in phase A already
 
     // ================= phase A: aggregates =================
 #pragma unroll 1
@@ -210,12 +217,38 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
         A agg_v;
         if constexpr (kMfma && kKeepRows) {
             // one chunk per wave: the row scans made here stay in the wave's LDS rows until phase B
-            if constexpr (K > 1) to_operand_layout<K>(raw[S], rows, lane);
+            if constexpr (kDenseShortcut) {
+                // A chunk all of whose positions start segments: the striped registers are the result.  The row
+                // scans are still made, for the aggregates; the test sits behind the first use of the loaded
+                // values, and the 0 / 1 operands are made before that, as they are without the branch (a branch
+                // ahead of the loads' first use, or operands made behind it: 1.5 to 3 % on vectors without such
+                // chunks).
+                typename SpecMfma<TT>::Operand op = SpecMfma<TT>::operand(lane);
+                SpecMfma<TT>::pin(op);
+                operand_layout_write4(raw[S], rows, lane);
+                dense_chunk = cb + kChunkElems <= n && __ballot(F[S] != 0xFFFFFFFFu) == 0;
+                if (dense_chunk) {
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                A acc[16];
-                SpecMfma<TT>::run(raw[S] + t * K, lane, acc);
-                store_spec_rows(rows, t, lane, acc);
+                    for (int i = 0; i < 2 * K; ++i)
+                        __builtin_nontemporal_store(
+                            raw[S][i],
+                            reinterpret_cast<v4u *>((A *)P.z + cb + 1024u * (i / K) + raw_offset<TT, kMfma>(i % K, lane)));
+                }
+                operand_layout_read4(raw[S], rows, lane);
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    A acc[16];
+                    SpecMfma<TT>::run(raw[S] + t * K, lane, acc, op);
+                    store_spec_rows(rows, t, lane, acc);
+                }
+            } else {
+                if constexpr (K > 1) to_operand_layout<K>(raw[S], rows, lane);
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    A acc[16];
+                    SpecMfma<TT>::run(raw[S] + t * K, lane, acc);
+                    store_spec_rows(rows, t, lane, acc);
+                }
             }
             rows[lane * kRowStride + kSlotZero] = 0;
             wave_lds_sync();
@@ -319,6 +352,9 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
         }
     }
     MMV_STAMP(2);
+    // (wave 0) the tile's first element starts a segment: nothing of the tile takes a carry from the tiles before
+    // (after the loop the register slots are back in place: slot 0 is the wave's first chunk)
+    const bool head_flagged = (__builtin_amdgcn_readfirstlane(F[0]) & 1u) != 0;
     if (lane == 0) {
         sm.wave_v[wave] = to_bits(run_v);
         sm.wave_f[wave] = run_f;
@@ -368,7 +404,7 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
             // ---- step 5c, second half: carry of the predecessor tiles by decoupled look-back ----
             A tile_carry = A(0);
             if (wave == 0) {
-                if (tile > 0) tile_carry = lookback<A, kAluLanes>(P.desc_v, (int)tile, lane, P.hdr);
+                if (tile > 0 && !head_flagged) tile_carry = lookback<A, kAluLanes>(P.desc_v, (int)tile, lane, P.hdr);
                 MMV_STAMP(4);
                 if (lane == 0) {
                     if (!final_now) desc_store(P.desc_v + tile, kStatusPrefix, to_bits(tile_carry + tagg_v));
@@ -393,7 +429,7 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
             const int S = kUnrollChunks ? c : u;
             // a chunk is "open" when no flag of the tile precedes it
             const bool chunk_open = !(wex_f || __builtin_amdgcn_readfirstlane(pre_f[S]));
-            if (c < cpw_t && chunk_open == (pass == 1)) {
+            if (c < cpw_t && chunk_open == (pass == 1) && !(kDenseShortcut && dense_chunk)) {
                 const uint64_t cb = wave_base + (uint64_t)c * kChunkElems;
                 const bool chunk_full = cb + kChunkElems <= n;
                 const uint64_t row_start = cb + 32u * lane;

@@ -85,10 +85,14 @@ template <typename TT, bool kMfma> __device__ __forceinline__ int raw_offset(int
 // The padded row strides keep the 128-bit accesses (almost) free of bank conflicts.
 template <int K> __device__ __forceinline__ void to_operand_layout(v4u (&raw)[2 * K], uint32_t *rows, int lane);
 
-template <> __device__ __forceinline__ void to_operand_layout<4>(v4u (&raw)[8], uint32_t *rows, int lane) {
+// (the two halves of the fp32 form are also called one by one: between them the registers still hold the
+// striped layout)
+__device__ __forceinline__ void operand_layout_write4(const v4u (&raw)[8], uint32_t *rows, int lane) {
 #pragma unroll
     for (int i = 0; i < 8; ++i)
         *reinterpret_cast<v4u *>(rows + (8 * i + (lane >> 3)) * kRowStride + kRowData + 4 * (lane & 7)) = raw[i];
+}
+__device__ __forceinline__ void operand_layout_read4(v4u (&raw)[8], const uint32_t *rows, int lane) {
     wave_lds_sync();
     const int c = lane & 31, h = lane >> 5;
 #pragma unroll
@@ -97,6 +101,10 @@ template <> __device__ __forceinline__ void to_operand_layout<4>(v4u (&raw)[8], 
         for (int q = 0; q < 4; ++q)
             raw[4 * t + q] = *reinterpret_cast<const v4u *>(rows + (32 * t + c) * kRowStride + kRowData + 16 * h + 4 * q);
     wave_lds_sync();
+}
+template <> __device__ __forceinline__ void to_operand_layout<4>(v4u (&raw)[8], uint32_t *rows, int lane) {
+    operand_layout_write4(raw, rows, lane);
+    operand_layout_read4(raw, rows, lane);
 }
 
 template <> __device__ __forceinline__ void to_operand_layout<2>(v4u (&raw)[4], uint32_t *rows, int lane) {
@@ -210,6 +218,12 @@ template <> struct SpecMfma<TBF16> {
 template <> struct SpecMfma<TF32> {
     // fp32 on the fp32 matrix instruction: sixteen K-steps of two positions, half h supplies position
     // 16 h + j in step j (word j / 4, element j % 4 of the lane's registers, as they are).
+    struct Operand {};
+    static __device__ __forceinline__ Operand operand(int) { return Operand(); }
+    static __device__ __forceinline__ void pin(Operand &) {}
+    static __device__ __forceinline__ void run(const v4u *raw, int lane, float (&acc)[16], const Operand &) {
+        run(raw, lane, acc);
+    }
     static __device__ __forceinline__ void run(const v4u *raw, int lane, float (&acc)[16]) {
         const int c = lane & 31, h = lane >> 5;
         const int ones = c - 16 * h + 1;   // positions 16 h + j <= c  <=>  j < ones
@@ -228,8 +242,28 @@ template <> struct SpecMfma<TF32> {
     // multiplied by the 0/1 matrix (exact products) and accumulated in fp32.  Six
     // 32x32x16 instructions of 8 passes instead of sixteen 32x32x2 fp32 ones of 16 passes.
     // In K-step ks half h supplies positions 16 h + 8 ks .. + 7 (the lane's own words 2 ks, 2 ks + 1).
-    static __device__ __forceinline__ void run(const v4u *raw, int lane, float (&acc)[16]) {
+    // the 0 / 1 operand of the two K-steps (lower-triangular ones, as bf16); the same for every tile of a lane
+    struct Operand {
+        v4u a[2];
+    };
+    static __device__ __forceinline__ Operand operand(int lane) {
         const int c = lane & 31, h = lane >> 5;
+        Operand op;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            v8s a;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) a[j] = (16 * h + 8 * ks + j <= c) ? (short)0x3F80 : (short)0;  // bf16 1.0
+            op.a[ks] = __builtin_bit_cast(v4u, a);
+        }
+        return op;
+    }
+    // keeps the compiler from moving the making of the operand past this point
+    static __device__ __forceinline__ void pin(Operand &op) { asm volatile("" : "+v"(op.a[0]), "+v"(op.a[1])); }
+    static __device__ __forceinline__ void run(const v4u *raw, int lane, float (&acc)[16]) {
+        run(raw, lane, acc, operand(lane));
+    }
+    static __device__ __forceinline__ void run(const v4u *raw, int lane, float (&acc)[16], const Operand &op) {
         v16f r = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
@@ -252,10 +286,7 @@ template <> struct SpecMfma<TF32> {
                     mid[2 * q + pr] = __builtin_amdgcn_perm(pm[1], pm[0], 0x07060302u);
                     lo[2 * q + pr] = __builtin_amdgcn_perm(pl[1], pl[0], 0x07060302u);
                 }
-            v8s a;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) a[j] = (16 * h + 8 * ks + j <= c) ? (short)0x3F80 : (short)0;  // bf16 1.0
-            const v8bf ab = __builtin_bit_cast(v8bf, a);
+            const v8bf ab = __builtin_bit_cast(v8bf, op.a[ks]);
             const v4u wl = {lo[0], lo[1], lo[2], lo[3]};
             const v4u wm = {mid[0], mid[1], mid[2], mid[3]};
             const v4u wh = {hi[0], hi[1], hi[2], hi[3]};

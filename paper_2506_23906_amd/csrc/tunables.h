@@ -45,6 +45,9 @@ namespace {
 #ifndef MMV_DPP_SCAN
 #define MMV_DPP_SCAN 1   // 1: the sum-type kernels exchange lanes with DPP moves and v_permlane32_swap, 0: with lane shuffles through the LDS hardware
 #endif
+#ifndef MMV_DENSE_SHORTCUT
+#define MMV_DENSE_SHORTCUT 1   // 1: fp32 scans store a chunk whose positions all start segments straight from its registers
+#endif
 #ifndef MMV_ROLL_STEP
 #define MMV_ROLL_STEP 2
 #endif

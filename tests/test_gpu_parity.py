@@ -157,6 +157,33 @@ def test_in_place_fp32():
     check_scan(z.cpu().numpy(), x, f)
 
 
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_fp32_chunks_with_every_flag_set(variant):
+    """Blocks of 2048 positions that all start segments (stored straight from the loaded registers by the
+    matrix-core variant) between ordinary ones, at aligned and unaligned places, with a ragged end, and in place:
+    in a whole chunk of set flags the result is the input bit for bit."""
+    rng = np.random.default_rng(2390670)
+    n = 37 * 16384 + 2048 * 3 + 777
+    x = rng.standard_normal(n, dtype=np.float32)
+    f = (rng.random(n) < 0.02).astype(np.uint8)
+    dense = np.zeros(n, dtype=bool)
+    for a, b in [(0, 2048), (4096, 4096 + 3 * 2048), (16384 * 5 - 2048, 16384 * 5 + 2048), (100_000, 109_999),
+                 (16384 * 20, 16384 * 23), (n - 2048 - 777, n - 777), (n - 700, n)]:
+        dense[a:b] = True
+    f[dense] = 1
+    z = run_segscan(x, f, variant)
+    check_scan(z, x, f)
+    if variant == "mfma":
+        whole = np.flatnonzero(f[:n - n % 2048].reshape(-1, 2048).all(axis=1))      # chunks of 2048 with every flag set
+        assert len(whole) >= 12
+        for c in whole:
+            assert np.array_equal(z[2048 * c:2048 * c + 2048].view(np.uint32), x[2048 * c:2048 * c + 2048].view(np.uint32)), c
+    xt = dev(x)
+    B.mmv_segscan(xt, packed_dev(f), n=n, z=xt, variant=variant)      # in place
+    torch.cuda.synchronize()
+    check_scan(xt.cpu().numpy(), x, f)
+
+
 def test_out_capacity_smaller_than_segment_count():
     x, f = W.segscan_i8_uniform_len(50_000, max_len=16, seed=9)
     ref = oracle.segsum(x, f)
