@@ -338,12 +338,20 @@ def write_report(args, events: HipEvents) -> None:
     emit(workload="3 segscan i8 n=2^%d U{1..4096}, one flag byte per element (whole call)" % args.log2n, n=n, ms=ms,
          gelem_s=n / ms / 1e6, gb_s=n * 6 / ms / 1e6, frac_of_peak=n * 6 / ms / 1e6 / HBM_PEAK_GBS)
     del f8, ws8
-    for density in (0.0, 1e-4, 1e-3, 3e-3, 1e-2, 0.1, 1.0):
+    # (the densities of the paper's figure on segmented scan against flag density, Sec. 5.2.2: 0.01 % to 1 %, for int8
+    # and fp16 inputs; 0, 10 % and 100 % added)
+    densities = (0.0, 1e-4, 1e-3, 3e-3, 5e-3, 1e-2, 0.1, 1.0)
+    xh = xt.to(torch.float16)
+    zf = zt.view(torch.float32)
+    wsh = B.new_workspace(B.MMV_OP_SEGSCAN, B.MMV_F16_F32, B.MMV_FLAGS_PACKED32, n)
+    for density in densities:
         fd = torch.from_numpy(W.pack_flags(W.uniform_density_flags(n, density, 77)).view(np.int32)).cuda()
         for variant in ("mfma", "shuffle"):
             run("density sweep i8 n=2^%d density=%g %s" % (args.log2n, density, variant), n, n * 5 + n // 8,
                 lambda: B.mmv_segscan(xt, fd, n=n, z=zt, variant=variant, ws=ws), ws, steps=30)
-    del xt, ft, zt
+        run("density sweep f16 n=2^%d density=%g mfma" % (args.log2n, density), n, n * 6 + n // 8,
+            lambda: B.mmv_segscan(xh, fd, n=n, z=zf, ws=wsh), wsh, steps=30)
+    del xt, ft, zt, xh, zf
 
     # workload 4
     nr = 1 << 20
