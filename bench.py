@@ -321,6 +321,19 @@ def write_report(args, events: HipEvents) -> None:
         ws = B.new_workspace(B.MMV_OP_SEGSUM, B.MMV_F16_F32, B.MMV_FLAGS_PACKED32, n)
         run("2 segsum f16 n=2^24 geometric(32) " + variant, n, n * 2 + n // 8 + nsegs * 4,
             lambda: B.mmv_segsum(xt, ft, n=n, out=out, nseg=nseg, variant=variant, ws=ws), ws)
+    # the rows above read the same 34 MiB every call, which the 256 MiB memory-side cache may hold; the next one
+    # rotates over nine copies (306 MiB) so that no call finds its inputs cached
+    cold = [(xt, ft)] + [(xt.clone(), ft.clone()) for _ in range(8)]
+    turn = [0]
+
+    def cold_step():
+        xk, fk = cold[turn[0] % len(cold)]
+        turn[0] += 1
+        B.mmv_segsum(xk, fk, n=n, out=out, nseg=nseg, ws=ws)
+
+    run("2 segsum f16 n=2^24 geometric(32) mfma, inputs rotated over 9 copies (not cached)", n,
+        n * 2 + n // 8 + nsegs * 4, cold_step, ws)
+    del cold
 
     # workload 3, both variants, and a flag-density sweep on the same values
     x, f = W.segscan_i8_uniform_len(1 << args.log2n)
