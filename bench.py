@@ -63,6 +63,7 @@ class HipEvents:
 
 
 EVENTS_EVERY = 1
+LAST_KERNEL_SAMPLES: list = []   # kernel times of the last time_steps() call that used events
 
 
 def time_steps(step, steps: int, warmup: int, events: HipEvents | None):
@@ -86,7 +87,9 @@ def time_steps(step, steps: int, warmup: int, events: HipEvents | None):
     kernel_ms = None
     if events:
         B.mmv_set_kernel_events(None, None)
-        kernel_ms = float(np.mean([events.elapsed_ms(a, b) for a, b in pairs]))
+        samples = [events.elapsed_ms(a, b) for a, b in pairs]
+        kernel_ms = float(np.mean(samples))
+        LAST_KERNEL_SAMPLES[:] = samples
         events.destroy_all()
     return (t1 - t0) * 1e3 / steps, kernel_ms
 
@@ -202,6 +205,9 @@ def main() -> int:
             "kernel_events_every_nth_step": EVENTS_EVERY,
             "tile_elems": B.mmv_tile_elems(),
             "kernel_ms": kernel_ms,
+            "kernel_ms_median": float(np.median(LAST_KERNEL_SAMPLES)),
+            "kernel_ms_min": float(np.min(LAST_KERNEL_SAMPLES)),
+            "workspace_reset_kernel_in_ms_per_step": True,   # the events of kernel_ms bracket the scan kernel alone
             "hbm_frac_of_peak_whole_step": algo_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         },
         "roofline": {
