@@ -370,7 +370,14 @@ def write_report(args, events: HipEvents) -> None:
                 lambda: B.mmv_segscan(xt, fd, n=n, z=zt, variant=variant, ws=ws), ws, steps=30)
         run("density sweep f16 n=2^%d density=%g mfma" % (args.log2n, density), n, n * 6 + n // 8,
             lambda: B.mmv_segscan(xh, fd, n=n, z=zf, ws=wsh), wsh, steps=30)
-    del xt, ft, zt, xh, zf
+    # another group on the same kernel: bytes under bit-wise exclusive or (the matrix-core variant takes the running
+    # xor as the parity of integer sums, two bit planes per product)
+    xu = torch.from_numpy(np.random.default_rng(2390692).integers(0, 256, size=n, dtype=np.uint8)).cuda()
+    wsx = B.new_workspace(B.MMV_OP_SEGSCAN, B.MMV_U8_XOR, B.MMV_FLAGS_PACKED32, n)
+    for variant in ("mfma", "shuffle"):
+        run("xor segscan u8 n=2^%d U{1..4096} %s" % (args.log2n, variant), n, n * 5 + n // 8,
+            lambda: B.mmv_segscan(xu, ft, n=n, z=zt, variant=variant, ws=wsx), wsx, steps=30)
+    del xt, ft, zt, xh, zf, xu
 
     # workload 4
     nr = 1 << 20

@@ -52,7 +52,10 @@ typedef enum {
     MMV_F32_F32 = 0,
     MMV_F16_F32 = 1,
     MMV_BF16_F32 = 2,
-    MMV_I8_I32 = 3 /* 32-bit two's complement, wraps (Z/2^32 is a group, Sec. 2) */
+    MMV_I8_I32 = 3, /* 32-bit two's complement, wraps (Z/2^32 is a group, Sec. 2) */
+    MMV_U8_XOR = 4  /* another group (Sec. 2 asks only for a group): bytes under bit-wise exclusive or; the
+                       result byte comes in the low bits of a 32-bit word.  mmv_segscan, mmv_segsum and
+                       mmv_scan only; the un-fused compositions and SpMV answer MMV_ERR_UNSUPPORTED. */
 } mmv_dtype;
 
 /* Segment-start flags f of Problem 2.1. */

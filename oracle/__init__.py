@@ -66,6 +66,10 @@ def _load():
         lib.oracle_segscan_i8.restype = None
         lib.oracle_segsum_i8.argtypes = [vp, vp, u64, vp]
         lib.oracle_segsum_i8.restype = u64
+        lib.oracle_segscan_xor_u8.argtypes = [vp, vp, u64, vp]
+        lib.oracle_segscan_xor_u8.restype = None
+        lib.oracle_segsum_xor_u8.argtypes = [vp, vp, u64, vp]
+        lib.oracle_segsum_xor_u8.restype = u64
         lib.oracle_segscan_f64.argtypes = [vp, vp, u64, vp]
         lib.oracle_segscan_f64.restype = None
         lib.oracle_segscan_f32in.argtypes = [vp, vp, u64, vp]
@@ -112,7 +116,8 @@ def segscan(x, f) -> np.ndarray:
     """Segmented inclusive scan (Problem 2.1).
 
     int8 values -> int32 result with wrap-around; float16/float32/float64
-    values -> float64 result accumulated in float64.
+    values -> float64 result accumulated in float64; uint8 values are elements
+    of the group of bytes under bit-wise exclusive or -> int32 holding the byte.
     """
     x = np.ascontiguousarray(x)
     n = x.shape[0]
@@ -121,6 +126,10 @@ def segscan(x, f) -> np.ndarray:
     if x.dtype == np.int8:
         z = np.empty(n, dtype=np.int32)
         lib.oracle_segscan_i8(_ptr(x), _ptr(f), n, _ptr(z))
+        return z
+    if x.dtype == np.uint8:
+        z = np.empty(n, dtype=np.int32)
+        lib.oracle_segscan_xor_u8(_ptr(x), _ptr(f), n, _ptr(z))
         return z
     if x.dtype == np.float32:
         z = np.empty(n, dtype=np.float64)
@@ -141,12 +150,16 @@ def segsum(x, f) -> np.ndarray:
     f = _flags_u8(f, n)
     lib = _load()
     if n == 0:
-        return np.empty(0, dtype=np.int32 if x.dtype == np.int8 else np.float64)
+        return np.empty(0, dtype=np.int32 if x.dtype in (np.int8, np.uint8) else np.float64)
     # room for the worst case (every element its own segment); the C loop tests
     # i == n-1 before it looks at f[i+1], so nothing past the end is read.
     if x.dtype == np.int8:
         out = np.empty(n, dtype=np.int32)
         k = lib.oracle_segsum_i8(_ptr(x), _ptr(f), n, _ptr(out))
+        return out[:k].copy()
+    if x.dtype == np.uint8:
+        out = np.empty(n, dtype=np.int32)
+        k = lib.oracle_segsum_xor_u8(_ptr(x), _ptr(f), n, _ptr(out))
         return out[:k].copy()
     if x.dtype in (np.float16, np.float32, np.float64):
         xd = np.ascontiguousarray(x, dtype=np.float64)
@@ -185,6 +198,11 @@ def scan(x) -> np.ndarray:
     if x.dtype == np.int8:
         z = np.empty(n, dtype=np.int32)
         lib.oracle_scan_i8(_ptr(x), n, _ptr(z))
+        return z
+    if x.dtype == np.uint8:      # bytes under exclusive or: the segmented scan with no flag set
+        z = np.empty(n, dtype=np.int32)
+        none = np.zeros(n, dtype=np.uint8)
+        lib.oracle_segscan_xor_u8(_ptr(x), _ptr(none), n, _ptr(z))
         return z
     if x.dtype == np.float32:
         z = np.empty(n, dtype=np.float64)

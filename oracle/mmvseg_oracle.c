@@ -26,6 +26,9 @@
  *    (Sec. 4.1) subtracts from every element the speculative scan value at the
  *    last position of the previous segment.
  *
+ *  - the same segmented scan / sum over another group, bytes under bit-wise
+ *    exclusive or (Sec. 2 states the problem for any group).
+ *
  * Readings taken where the paper is silent:
  *  - position 0 always opens a segment, whatever f(0) holds;
  *  - int8 inputs accumulate in 32-bit two's complement with wrap-around
@@ -73,6 +76,37 @@ uint64_t oracle_segsum_i8(const int8_t *x, const uint8_t *f, uint64_t n, int32_t
             acc = acc + xi;
         if (i == n - 1 || f[i + 1])
             out[k++] = (int32_t)acc;
+    }
+    return k;
+}
+
+/* ---- another group: bytes under bit-wise exclusive or ---------------------- */
+
+/* Problem 2.1 asks only for a group (Sec. 2): here ((Z_2)^8, xor).  The same
+ * recurrence with xor for +; the result byte in the low bits of a 32-bit word. */
+void oracle_segscan_xor_u8(const uint8_t *x, const uint8_t *f, uint64_t n, uint32_t *z)
+{
+    uint32_t acc = 0;
+    for (uint64_t i = 0; i < n; ++i) {
+        if (i == 0 || f[i])
+            acc = x[i];
+        else
+            acc = acc ^ x[i];
+        z[i] = acc;
+    }
+}
+
+uint64_t oracle_segsum_xor_u8(const uint8_t *x, const uint8_t *f, uint64_t n, uint32_t *out)
+{
+    uint32_t acc = 0;
+    uint64_t k = 0;
+    for (uint64_t i = 0; i < n; ++i) {
+        if (i == 0 || f[i])
+            acc = x[i];
+        else
+            acc = acc ^ x[i];
+        if (i == n - 1 || f[i + 1])
+            out[k++] = acc;
     }
     return k;
 }

@@ -17,7 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmmvseg.so")
 
 MMV_OK = 0
-MMV_F32_F32, MMV_F16_F32, MMV_BF16_F32, MMV_I8_I32 = 0, 1, 2, 3
+MMV_F32_F32, MMV_F16_F32, MMV_BF16_F32, MMV_I8_I32, MMV_U8_XOR = 0, 1, 2, 3, 4
 MMV_FLAGS_U8, MMV_FLAGS_PACKED32 = 0, 1
 MMV_VARIANT_MFMA, MMV_VARIANT_SHUFFLE = 0, 1
 MMV_OP_SEGSCAN, MMV_OP_SEGSUM, MMV_OP_SPMV_COO = 0, 1, 2
@@ -32,9 +32,9 @@ EXPORTS = [
 ]
 
 _DTYPES = {torch.float32: MMV_F32_F32, torch.float16: MMV_F16_F32, torch.bfloat16: MMV_BF16_F32,
-           torch.int8: MMV_I8_I32}
+           torch.int8: MMV_I8_I32, torch.uint8: MMV_U8_XOR}   # uint8 values: bytes under bit-wise exclusive or
 _OUT_DTYPE = {MMV_F32_F32: torch.float32, MMV_F16_F32: torch.float32, MMV_BF16_F32: torch.float32,
-              MMV_I8_I32: torch.int32}
+              MMV_I8_I32: torch.int32, MMV_U8_XOR: torch.int32}
 _VARIANTS = {"mfma": MMV_VARIANT_MFMA, "shuffle": MMV_VARIANT_SHUFFLE}
 
 _lib = None

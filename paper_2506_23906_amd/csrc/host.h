@@ -32,6 +32,7 @@ inline int max_cpw(mmv_op op, mmv_dtype dt) {
         case MMV_F16_F32: return TF16::kMaxCpw;
         case MMV_BF16_F32: return TBF16::kMaxCpw;
         case MMV_I8_I32: return TI8::kMaxCpw;
+        case MMV_U8_XOR: return TX8::kMaxCpw;
     }
     return 1;
 }
@@ -42,6 +43,7 @@ inline int waves_of(mmv_op op, mmv_dtype dt) {
         case MMV_F16_F32: return TF16::kWaves;
         case MMV_BF16_F32: return TBF16::kWaves;
         case MMV_I8_I32: return TI8::kWaves;
+        case MMV_U8_XOR: return TX8::kWaves;
     }
     return 1;
 }
@@ -255,6 +257,7 @@ template <int kOp> hipError_t launch_dt(const Params &P, mmv_dtype dt, mmv_varia
         case MMV_F16_F32: return launch_seg<TF16, kOp>(P, v, s);
         case MMV_BF16_F32: return launch_seg<TBF16, kOp>(P, v, s);
         case MMV_I8_I32: return launch_seg<TI8, kOp>(P, v, s);
+        case MMV_U8_XOR: return launch_seg<TX8, kOp>(P, v, s);
     }
     return hipErrorInvalidValue;
 }
@@ -266,7 +269,7 @@ int grid_for(uint64_t items_per_thread_total) {
     return (int)blocks;
 }
 
-bool valid_dtype(int dt) { return dt >= 0 && dt <= 3; }
+bool valid_dtype(int dt) { return dt >= 0 && dt <= 4; }
 bool valid_ff(int ff) { return ff == 0 || ff == 1; }
 bool valid_variant(int v) { return v == 0 || v == 1; }
 bool valid_elem(int et) { return et == 0 || et == 1; }

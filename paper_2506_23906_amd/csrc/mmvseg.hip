@@ -205,6 +205,7 @@ mmv_status mmv_segsum_scd(const void *d_x, const void *d_flags, uint64_t n, void
                           uint64_t *d_nseg, mmv_dtype dt, mmv_flag_fmt ff, mmv_variant v, void *d_ws, size_t ws_bytes,
                           void *hip_stream) {
     if (!valid_dtype(dt) || !valid_ff(ff) || !valid_variant(v) || n > kMaxN) return MMV_ERR_INVALID_ARG;
+    if (dt == MMV_U8_XOR) return MMV_ERR_UNSUPPORTED;   // DIFF subtracts
     if (!d_nseg) return MMV_ERR_NULL;
     hipStream_t s = (hipStream_t)hip_stream;
     if (n == 0) {
@@ -244,6 +245,7 @@ mmv_status mmv_segsum_scd(const void *d_x, const void *d_flags, uint64_t n, void
 mmv_status mmv_segscan_sscr(const void *d_x, const void *d_flags, uint64_t n, void *d_z, mmv_dtype dt, mmv_flag_fmt ff,
                             mmv_variant v, void *d_ws, size_t ws_bytes, void *hip_stream) {
     if (!valid_dtype(dt) || !valid_ff(ff) || !valid_variant(v) || n > kMaxN) return MMV_ERR_INVALID_ARG;
+    if (dt == MMV_U8_XOR) return MMV_ERR_UNSUPPORTED;   // REVERT subtracts
     if (n == 0) return MMV_OK;
     if (!d_x || !d_flags || !d_z || !d_ws) return MMV_ERR_NULL;
     if (!aligned16(d_x) || !aligned16(d_flags) || !aligned16(d_z)) return MMV_ERR_INVALID_ARG;

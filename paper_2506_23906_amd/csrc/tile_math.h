@@ -16,6 +16,27 @@ struct TI8 {
     static constexpr mmv_dtype kDtype = MMV_I8_I32;
     static __device__ __forceinline__ acc_t widen(in_t v) { return (acc_t)(int32_t)v; }
 };
+// Another group on the same skeleton (Sec. 2 asks only for a group): bit-wise exclusive or on bytes,
+// (Z_2)^8.  "Addition" and "subtraction" are both XOR, the neutral element is 0, so the revert
+// z(j) = x-bar(j) - x-bar(start - 1) and the carries work unchanged through the operators below.
+struct XorWord {
+    uint32_t v;
+    XorWord() = default;
+    __device__ __host__ constexpr explicit XorWord(uint32_t x) : v(x) {}
+    __device__ __host__ constexpr explicit XorWord(int x) : v((uint32_t)x) {}
+    friend __device__ __forceinline__ XorWord operator+(XorWord a, XorWord b) { return XorWord(a.v ^ b.v); }
+    friend __device__ __forceinline__ XorWord operator-(XorWord a, XorWord b) { return XorWord(a.v ^ b.v); }
+    __device__ __forceinline__ XorWord &operator+=(XorWord b) { v ^= b.v; return *this; }
+    __device__ __forceinline__ XorWord &operator-=(XorWord b) { v ^= b.v; return *this; }
+};
+struct TX8 {
+    typedef uint8_t in_t;
+    typedef XorWord acc_t;   // the result byte in the low bits of a 32-bit word
+    static constexpr int kEpl = 16;
+    static constexpr int kMaxCpw = MMV_CPW_I8;
+    static constexpr int kWaves = MMV_WAVES;
+    static constexpr mmv_dtype kDtype = MMV_U8_XOR;
+};
 struct TF16 {
     typedef _Float16 in_t;
     typedef float acc_t;
@@ -173,6 +194,39 @@ template <> struct SpecMfma<TI8> {
         r = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, __builtin_bit_cast(v4i, raw[0]), r, 0, 0, 0);
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[v] = (uint32_t)r[v];
+    }
+};
+
+template <> struct SpecMfma<TX8> {
+    // Exclusive or through integer sums: the running XOR of a bit is the parity of its running count.
+    // Two bit planes share one product (bit b in bit 0 and bit b + 1 in bit 6 of the int8 operand: counts
+    // of up to 32 need six bits each), so a byte takes four matrix instructions; bits 0 and 6 of the
+    // sums are the two parities.
+    static __device__ __forceinline__ void run(const v4u *raw, int lane, XorWord (&acc)[16]) {
+        const int c = lane & 31, h = lane >> 5;
+        v4i a;  // as for int8 sums: one where position <= c
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            int cnt = c - (16 * h + 4 * d) + 1;
+            cnt = cnt < 0 ? 0 : (cnt > 4 ? 4 : cnt);
+            a[d] = cnt == 4 ? 0x01010101 : (int)(0x01010101u & ((1u << (8 * cnt)) - 1u));
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[v] = XorWord(0u);
+#pragma unroll 1
+        for (int pr = 0; pr < 4; ++pr) {   // (rolled: one set of sums at a time, or the registers do not suffice)
+            v4i b;
+#pragma unroll
+            for (int d = 0; d < 4; ++d)
+                b[d] = (int)(((raw[0][d] >> (2 * pr)) & 0x01010101u) | (((raw[0][d] >> (2 * pr + 1)) & 0x01010101u) << 6));
+            v16i r = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+            r = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, r, 0, 0, 0);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const uint32_t u = (uint32_t)r[v];
+                acc[v].v |= ((u & 1u) << (2 * pr)) | (((u >> 6) & 1u) << (2 * pr + 1));
+            }
+        }
     }
 };
 
@@ -341,6 +395,31 @@ template <> struct RowAgg<TI8> {
     }
 };
 
+template <> struct RowAgg<TX8> {
+    // as RowAgg<TI8>, with the masked bytes folded by XOR instead of summed
+    template <bool kAlu> static __device__ __forceinline__ XorWord run(const v4u *raw, uint32_t F, int lane) {
+        const int h = lane >> 5;
+        const Halves Fh = wave_halves<kAlu>(F, lane);
+        uint32_t tot[2];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int st = last_flag_pos(t ? Fh.hi : Fh.lo);
+            int k = st - 16 * h;
+            k = k < 0 ? 0 : (k > 16 ? 16 : k);
+            const uint64_t ones = ~0ull;
+            const uint64_t m_lo = k >= 8 ? 0ull : ones << (8 * k);
+            const uint64_t m_hi = k >= 16 ? 0ull : ones << (8 * (k > 8 ? k - 8 : 0));
+            uint32_t x = (raw[t][0] & (uint32_t)m_lo) ^ (raw[t][1] & (uint32_t)(m_lo >> 32)) ^
+                         (raw[t][2] & (uint32_t)m_hi) ^ (raw[t][3] & (uint32_t)(m_hi >> 32));
+            x ^= x >> 16;
+            x ^= x >> 8;
+            const Halves ph = wave_halves<kAlu>(x & 0xFFu, lane);
+            tot[t] = ph.lo ^ ph.hi;
+        }
+        return XorWord(lane < 32 ? tot[0] : tot[1]);
+    }
+};
+
 template <bool kBf16> struct RowAggHalf {
     template <bool kAlu> static __device__ __forceinline__ float run(const v4u *raw, uint32_t F, int lane) {
         typedef _Float16 v2h __attribute__((ext_vector_type(2)));
@@ -418,6 +497,9 @@ __device__ __forceinline__ void store_spec_rows(uint32_t *rows, int t, int lane,
 template <typename TT> __device__ __forceinline__ typename TT::acc_t raw_elem(const v4u &w, int i);
 template <> __device__ __forceinline__ uint32_t raw_elem<TI8>(const v4u &w, int i) {
     return (uint32_t)(int32_t)(int8_t)(w[i >> 2] >> (8 * (i & 3)));
+}
+template <> __device__ __forceinline__ XorWord raw_elem<TX8>(const v4u &w, int i) {
+    return XorWord((w[i >> 2] >> (8 * (i & 3))) & 0xFFu);
 }
 template <> __device__ __forceinline__ float raw_elem<TF16>(const v4u &w, int i) {
     return (float)__builtin_bit_cast(_Float16, (unsigned short)(w[i >> 1] >> (16 * (i & 1))));

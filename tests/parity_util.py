@@ -2,7 +2,7 @@
 through the binding, and compare with the CPU oracle.
 
 Comparison rules
-* integers (int8 -> int32): bit-exact on every element and on the segment count.
+* integers (int8 -> int32, and bytes under exclusive or): bit-exact on every element and on the segment count.
 * floating point: |got - ref| <= tol * max(A_i, 1) for every element, where ref
   is the fp64-accumulated oracle, A_i the segmented inclusive scan of |x| in
   fp64 (A_i >= |ref_i|; the classical summation bound is relative to it) and 1
@@ -71,7 +71,7 @@ def abs_scan(x: np.ndarray, f: np.ndarray) -> np.ndarray:
 
 def check_scan(got: np.ndarray, x: np.ndarray, f: np.ndarray, tol=None, chunk: int = 1 << 24):
     ref = oracle.segscan(x, f)
-    if x.dtype == np.int8:
+    if x.dtype in (np.int8, np.uint8):      # int8 sums and bytes under xor: exact
         assert got.dtype == np.int32
         assert np.array_equal(got, ref), _first_diff(got, ref)
         return 0.0
@@ -94,7 +94,7 @@ def check_sum(got: np.ndarray, nseg: int, x: np.ndarray, f: np.ndarray, tol=None
     ref = oracle.segsum(x, f)
     assert nseg == len(ref), (nseg, len(ref))
     got = got[:nseg]
-    if x.dtype == np.int8:
+    if x.dtype in (np.int8, np.uint8):
         assert np.array_equal(got, ref), _first_diff(got, ref)
         return 0.0
     tol = TOL[x.dtype] if tol is None else tol
@@ -118,6 +118,8 @@ def _first_diff(got, ref):
 def random_values(rng, n: int, dtype) -> np.ndarray:
     if dtype == np.int8:
         return rng.integers(-128, 128, size=n, dtype=np.int8)
+    if dtype == np.uint8:
+        return rng.integers(0, 256, size=n, dtype=np.uint8)
     if dtype == np.float16:
         return rng.standard_normal(n).astype(np.float16)
     return (rng.random(n, dtype=np.float32) * 2 - 1).astype(np.float32)

@@ -78,7 +78,7 @@ def test_argument_errors_are_caught_on_the_host(libmmvseg_path):
     assert lib.mmv_segsum(a16, a16, 10, a16, 10, None, B.MMV_I8_I32, B.MMV_FLAGS_U8, 0, a16 << 4, 4096, None) == NULL
     # misaligned pointers, bad enums
     assert lib.mmv_segscan(a16 + 4, a16, 10, a16 * 2, B.MMV_I8_I32, B.MMV_FLAGS_U8, 0, a16 << 4, 4096, None) == INVALID
-    assert lib.mmv_segscan(a16, a16, 10, a16 * 2, 4, B.MMV_FLAGS_U8, 0, a16 << 4, 4096, None) == INVALID
+    assert lib.mmv_segscan(a16, a16, 10, a16 * 2, 5, B.MMV_FLAGS_U8, 0, a16 << 4, 4096, None) == INVALID
     assert lib.mmv_segscan(a16, a16, 10, a16 * 2, B.MMV_I8_I32, 2, 0, a16 << 4, 4096, None) == INVALID
     assert lib.mmv_segscan(a16, a16, 10, a16 * 2, B.MMV_I8_I32, B.MMV_FLAGS_U8, 2, a16 << 4, 4096, None) == INVALID
     # output may alias the input only when both are fp32
@@ -106,6 +106,10 @@ def test_argument_errors_are_caught_on_the_host(libmmvseg_path):
     assert lib.mmv_segsum_scd(a16, a16, 10, a16, 10, a16, B.MMV_I8_I32, B.MMV_FLAGS_U8, 0, a16 << 4, 16, None) == WORKSPACE
     assert lib.mmv_segscan_sscr(a16, a16, 10, a16 * 2, B.MMV_I8_I32, B.MMV_FLAGS_U8, 0, a16 << 4, 16, None) == WORKSPACE
     assert lib.mmv_segscan_sscr(a16, a16, 10, a16, B.MMV_I8_I32, B.MMV_FLAGS_U8, 0, a16 << 4, 1 << 20, None) == INVALID
+    # the un-fused routes subtract (DIFF, REVERT): not for the group of bytes under exclusive or
+    assert lib.mmv_segsum_scd(a16, a16, 10, a16, 10, a16, B.MMV_U8_XOR, B.MMV_FLAGS_U8, 0, a16 << 4, 1 << 20, None) == 3
+    assert lib.mmv_segscan_sscr(a16, a16, 10, a16 * 2, B.MMV_U8_XOR, B.MMV_FLAGS_U8, 0, a16 << 4, 1 << 20, None) == 3
+    assert B.mmv_workspace_bytes(B.MMV_OP_SEGSCAN, B.MMV_U8_XOR, B.MMV_FLAGS_PACKED32, 1 << 20) > 0
     assert lib.mmv_spmv_csr(0, 0, 0, None, None, None, None, None, 0, None, 0, None) == OK
     assert lib.mmv_spmv_csr(4, 4, 4, None, a16, a16, a16, a16, 0, a16 << 4, 1 << 20, None) == NULL
     assert lib.mmv_spmv_csr(4, 4, 1 << 31, a16, a16, a16, a16, a16, 0, a16 << 4, 1 << 20, None) == INVALID
