@@ -200,8 +200,19 @@ template <> struct SpecMfma<TI8> {
 template <> struct SpecMfma<TX8> {
     // Exclusive or through integer sums: the running XOR of a bit is the parity of its running count.
     // Two bit planes share one product (bit b in bit 0 and bit b + 1 in bit 6 of the int8 operand: counts
-    // of up to 32 need six bits each), so a byte takes four matrix instructions; bits 0 and 6 of the
-    // sums are the two parities.
+    // of up to 32 need six bits each), so a byte takes four matrix instructions.  Two results are packed
+    // into one word (fields at bits 0, 6, 12, 18), whose four parity bits a 24-bit multiplication moves
+    // next to each other: bit 6 i times 2^(15 - 5 i) lands at bit 15 + i, and no two partial products meet.
+    static __device__ __forceinline__ v16i planes(const v4u &w, v4i a, int p) {   // sums of planes p and p + 1
+        v4i b;
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            const uint32_t t = w[d] >> p;
+            b[d] = (int)((t & 0x01010101u) | ((t << 5) & 0x40404040u));
+        }
+        v16i r = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+        return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, r, 0, 0, 0);
+    }
     static __device__ __forceinline__ void run(const v4u *raw, int lane, XorWord (&acc)[16]) {
         const int c = lane & 31, h = lane >> 5;
         v4i a;  // as for int8 sums: one where position <= c
@@ -214,17 +225,13 @@ template <> struct SpecMfma<TX8> {
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[v] = XorWord(0u);
 #pragma unroll 1
-        for (int pr = 0; pr < 4; ++pr) {   // (rolled: one set of sums at a time, or the registers do not suffice)
-            v4i b;
-#pragma unroll
-            for (int d = 0; d < 4; ++d)
-                b[d] = (int)(((raw[0][d] >> (2 * pr)) & 0x01010101u) | (((raw[0][d] >> (2 * pr + 1)) & 0x01010101u) << 6));
-            v16i r = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-            r = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, r, 0, 0, 0);
+        for (int nib = 0; nib < 2; ++nib) {   // (rolled: one nibble at a time, or the registers do not suffice)
+            const v16i r0 = planes(raw[0], a, 4 * nib);
+            const v16i r1 = planes(raw[0], a, 4 * nib + 2);
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const uint32_t u = (uint32_t)r[v];
-                acc[v].v |= ((u & 1u) << (2 * pr)) | (((u >> 6) & 1u) << (2 * pr + 1));
+                const uint32_t packed = (((uint32_t)r1[v] << 12) + (uint32_t)r0[v]) & 0x041041u;
+                acc[v].v |= (((packed * 0x8421u) >> 15) & 0xFu) << (4 * nib);
             }
         }
     }
