@@ -203,6 +203,73 @@ def test_compositions_survive_wrap_around():
     assert z[17_000_000] == 127 and z[-1] == 127 * 500_000 and z[16_999_999] == wrap32([127 * 17_000_000])[0]
 
 
+# ---- REVERT on floats ---------------------------------------------------------------------------
+#
+# The float form of REVERT widens to double and subtracts there.  Pins that are not its own formula: the
+# worked example of Sec. 2 carried in fp32, integer-valued fp32 inputs (every intermediate is exact, so
+# the composition REVERT(SCAN, SCAN, COMPRESS) must equal the sequential definition), a hand case with
+# non-integers whose differences are exact binary fractions, the numpy formulation, and the int32 form
+# of the same function on the same integers.
+
+def test_revert_fp32_on_the_worked_example(golden_sec2):
+    g = golden_sec2
+    xhat = np.array([2, 4, 7, 10, 11, 14, 15, 17], dtype=np.float32)   # SCAN(x) of the example
+    fhat = np.array([1, 1, 2, 2, 2, 3, 3, 3], dtype=np.int32)           # SCAN(f)
+    w = np.array([4, 11, 17], dtype=np.float32)                         # COMPRESS(SCAN(x), f^-)
+    z = oracle.revert(xhat, fhat, w)
+    assert z.dtype == np.float64
+    assert z.tolist() == [float(v) for v in g["segscan"]]
+
+
+def test_revert_fp32_by_hand_with_binary_fractions():
+    xhat = np.array([0.5, 0.75, 1.0, 3.5, 3.625], dtype=np.float32)
+    fhat = np.array([1, 1, 2, 3, 3], dtype=np.int32)
+    w = np.array([0.75, 1.0, 3.625], dtype=np.float32)
+    assert oracle.revert(xhat, fhat, w).tolist() == [0.5, 0.75, 0.25, 2.5, 2.625]
+    # the first segment is left alone, the third subtracts w(1), not w(0) or w(2)
+    assert oracle.revert(xhat, np.array([1, 1, 1, 1, 1], dtype=np.int32), w).tolist() == xhat.astype(np.float64).tolist()
+    with pytest.raises(ValueError):
+        oracle.revert(xhat, np.array([1, 1, 2, 3, 6], dtype=np.int32), w)
+
+
+@pytest.mark.parametrize("density", [0.0, 0.02, 0.3, 1.0])
+def test_revert_fp32_integer_valued_composition_equals_definition(density):
+    rng = np.random.default_rng(51)
+    n = 5_000
+    xi = rng.integers(-100, 101, size=n)                      # |prefix| < 2^24: exact in fp32
+    x = xi.astype(np.float32)
+    f = W.uniform_density_flags(n, density, 6)
+    xhat = oracle.scan(x).astype(np.float32)                  # exact
+    fhat = _count_scan(f)
+    w = oracle.compress(xhat, _end_markers(f))
+    z = oracle.revert(xhat, fhat, w)
+    assert z.tolist() == [float(v) for v in F.definitional_segscan(xi, f)]
+    assert z.tolist() == F.revert(xhat.astype(np.float64), fhat, w.astype(np.float64)).tolist()
+    # the int32 form of REVERT on the same integers
+    zi = oracle.revert(xhat.astype(np.int32), fhat, w.astype(np.int32))
+    assert z.tolist() == [float(v) for v in zi.tolist()]
+
+
+def test_revert_fp32_brute_force_all_flag_patterns():
+    xi = np.array([3, -1, 4, 1, -5, 9, 2, -6], dtype=np.int64)
+    x = (xi * 0.25).astype(np.float32)                        # quarter steps: exact sums
+    for n in range(1, 9):
+        for bits in itertools.product([0, 1], repeat=n):
+            f = np.array(bits, dtype=np.uint8)
+            xhat = oracle.scan(x[:n]).astype(np.float32)
+            w = oracle.compress(xhat, _end_markers(f))
+            z = oracle.revert(xhat, _count_scan(f), w)
+            assert (z * 4).tolist() == [float(v) for v in F.definitional_segscan(xi[:n], f)]
+
+
+def test_revert_fp32_subtracts_in_double():
+    # 2^24 + 1 is not an fp32 number, so the inputs are 2^24 + 2 and 1: the difference 2^24 + 1 must come
+    # out exactly (a subtraction carried out in fp32 would round it)
+    xhat = np.array([1.0, 16777218.0], dtype=np.float32)
+    z = oracle.revert(xhat, np.array([1, 2], dtype=np.int32), np.array([1.0, 16777218.0], dtype=np.float32))
+    assert z.tolist() == [1.0, 16777217.0]
+
+
 # ---- CSR SpMV ---------------------------------------------------------------------------------------
 
 def test_spmv_csr_is_scipy_csr():
