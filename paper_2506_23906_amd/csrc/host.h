@@ -183,47 +183,32 @@ CsrLayout csr_layout(uint64_t n_rows, uint64_t nnz) {
     return L;
 }
 
-#ifdef MMV_TRACE
-uint64_t *g_trace = nullptr;
-#endif
-
 // Optional instrumentation (mmv_set_kernel_events): events recorded right before and
 // right after the main kernel of a call made by this host thread.
 thread_local hipEvent_t tl_ev_start = nullptr, tl_ev_stop = nullptr;
 
-// Workgroups of `kernel` that the current device holds at once (0 when a query fails); asked once
-// per kernel and device.
-uint32_t resident_workgroups(const void *kernel, int threads) {
-    struct Entry {
-        const void *kernel;
-        int device;
-        uint32_t value;
-    };
-    static std::mutex mu;
-    static std::vector<Entry> known;
+// Workgroups of `kernel` that the current device holds at once (0 when a query fails).  `cache` is the
+// caller's table for this kernel, one word per device (0 = not asked yet, else the value + 1): a fixed
+// array per kernel instantiation, so nothing grows and nothing is allocated after the library is loaded.
+constexpr int kMaxDevices = 64;
+uint32_t resident_workgroups(const void *kernel, int threads, std::atomic<uint32_t> (&cache)[kMaxDevices]) {
     int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return 0;
-    std::lock_guard<std::mutex> lock(mu);
-    for (const Entry &e : known)
-        if (e.kernel == kernel && e.device == dev) return e.value;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 0;
+    const uint32_t known = cache[dev].load(std::memory_order_relaxed);
+    if (known) return known - 1u;
     int per_cu = 0, cus = 0;
     uint32_t value = 0;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, 0) == hipSuccess &&
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && per_cu > 0 && cus > 0)
         value = (uint32_t)per_cu * (uint32_t)cus;
-    known.push_back({kernel, dev, value});
+    cache[dev].store(value + 1u, std::memory_order_relaxed);   // (two threads asking at once store the same value)
     return value;
 }
 
 template <typename TT, int kOp, bool kMfma> hipError_t launch_variant(Params P, hipStream_t s) {
-#ifdef MMV_TRACE
-    P.trace = g_trace;
-#endif
-    const uint32_t resident = resident_workgroups((const void *)seg_kernel<TT, kOp, kMfma>, TT::kWaves * 64);
+    static std::atomic<uint32_t> occupancy[kMaxDevices];
+    const uint32_t resident = resident_workgroups((const void *)seg_kernel<TT, kOp, kMfma>, TT::kWaves * 64, occupancy);
     P.ordered = P.num_tiles <= resident ? 1u : 0u;
-#if defined(MMV_FORCE_ORDERED) && MMV_FORCE_ORDERED
-    P.ordered = 1u;
-#endif
     // SpMV: the workgroups of the first round start spread over about one tile time.  Started together
     // they stay in step (load, gather, compute all at the same time) and the memory pipe idles half the
     // time; measured 4 to 7 % on the long SpMV kernels, nothing on the scans.
@@ -392,10 +377,10 @@ mmv_status revert_impl(const void *d_xhat, const int32_t *d_fhat, const void *d_
     if (tl_ev_start && hipEventRecord(tl_ev_start, s) != hipSuccess) return MMV_ERR_HIP;
     if (et == MMV_ELEM_I32)
         revert_kernel<uint32_t><<<(unsigned)blocks, 256, 0, s>>>((const uint32_t *)d_xhat, d_fhat, (const uint32_t *)d_w,
-                                                                  n, nw, (uint32_t *)d_z, nullptr);
+                                                                  n, nw, (uint32_t *)d_z);
     else
         revert_kernel<float><<<(unsigned)blocks, 256, 0, s>>>((const uint32_t *)d_xhat, d_fhat, (const uint32_t *)d_w, n,
-                                                               nw, (uint32_t *)d_z, nullptr);
+                                                               nw, (uint32_t *)d_z);
     const hipError_t e = hipGetLastError();
     if (tl_ev_stop && hipEventRecord(tl_ev_stop, s) != hipSuccess) return MMV_ERR_HIP;
     return e == hipSuccess ? MMV_OK : MMV_ERR_HIP;

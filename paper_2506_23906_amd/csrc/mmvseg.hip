@@ -30,8 +30,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
 #include <mutex>
-#include <vector>
 
 #include "mmvseg.h"
 
@@ -402,11 +402,6 @@ mmv_status mmv_set_kernel_events(void *ev_start, void *ev_stop) {
     tl_ev_stop = (hipEvent_t)ev_stop;
     return MMV_OK;
 }
-
-#ifdef MMV_TRACE
-// Development builds only: device buffer of 8 uint64 per tile that receives phase timestamps.
-void mmv_trace_buffer(void *d_trace) { g_trace = (uint64_t *)d_trace; }
-#endif
 
 const char *mmv_status_string(mmv_status s) {
     switch (s) {

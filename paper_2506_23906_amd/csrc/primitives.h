@@ -169,11 +169,12 @@ __global__ __launch_bounds__(256) void diff_kernel(const uint32_t *__restrict__ 
 
 // REVERT (Sec. 4.1): z(i) = xhat(i) - w(fhat(i) - 2) where the inclusive count of segment
 // starts fhat(i) is at least 2 (the printed index is read shifted by one: the first segment is
-// left alone).  A count that points outside w subtracts nothing and raises the error word.
+// left alone).  A count that points outside w subtracts nothing (there is no workspace to report it through;
+// the compositions of this library only ever pass counts that COMPRESS has produced entries for).
 template <typename A>
 __global__ __launch_bounds__(256) void revert_kernel(const uint32_t *xhat, const int32_t *__restrict__ fhat,
                                                      const uint32_t *__restrict__ w, uint64_t n, uint64_t nw,
-                                                     uint32_t *z, uint32_t *err) {
+                                                     uint32_t *z) {
     const uint64_t e0 = ((uint64_t)blockIdx.x * 256 + threadIdx.x) * 4;
     if (e0 >= n) return;
     v4u xv = {0, 0, 0, 0};
@@ -191,18 +192,15 @@ __global__ __launch_bounds__(256) void revert_kernel(const uint32_t *xhat, const
             }
     }
     v4u o;
-    bool bad = false;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         A v = from_bits<A>(xv[i]);
         const int64_t k = kv[i];
         if (k >= 2) {
             if ((uint64_t)(k - 2) < nw) v -= from_bits<A>(w[k - 2]);
-            else if (e0 + i < n) bad = true;
         }
         o[i] = to_bits(v);
     }
-    if (bad && err) __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (full) {
         __builtin_nontemporal_store(o, reinterpret_cast<v4u *>(z + e0));
     } else {

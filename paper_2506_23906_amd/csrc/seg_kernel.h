@@ -90,7 +90,6 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const uint64_t n = P.n;
     uint32_t *rows = sm.rows[wave];
-    MMV_STAMP(1);
     // tiles at the end of the vector are shorter (fewer chunks per wave)
     const bool big_tile = tile < P.big_tiles;
     const int cpw_t = big_tile ? kCpw : (int)P.tail_cpw;
@@ -351,7 +350,6 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
             }
         }
     }
-    MMV_STAMP(2);
     // (wave 0) the tile's first element starts a segment: nothing of the tile takes a carry from the tiles before
     // (after the loop the register slots are back in place: slot 0 is the wave's first chunk)
     const bool head_flagged = (__builtin_amdgcn_readfirstlane(F[0]) & 1u) != 0;
@@ -361,7 +359,6 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
         sm.wave_c[wave] = run_c;
     }
     __syncthreads();
-    MMV_STAMP(3);
 
     // ---- step 5b: waves of the tile ----
     A wex_v = A(0);
@@ -405,7 +402,6 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
             A tile_carry = A(0);
             if (wave == 0) {
                 if (tile > 0 && !head_flagged) tile_carry = lookback<A, kAluLanes>(P.desc_v, (int)tile, lane, P.hdr);
-                MMV_STAMP(4);
                 if (lane == 0) {
                     if (!final_now) desc_store(P.desc_v + tile, kStatusPrefix, to_bits(tile_carry + tagg_v));
                     sm.carry_v = to_bits(tile_carry);
@@ -419,7 +415,6 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
                 tile_carry = from_bits<A>(sm.carry_v);
             }
             if (!wex_f) span_carry = tile_carry + wex_v;
-            MMV_STAMP(5);
         }
 #pragma unroll 1
         for (int c0 = 0; c0 < kCpw; c0 += kStep) {
@@ -558,11 +553,6 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
             }
         }
     }
-    MMV_STAMP(6);
-#ifdef MMV_TRACE
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    MMV_STAMP(7);
-#endif
 }
 
 template <typename TT, int kOp, bool kMfma>
@@ -570,9 +560,6 @@ __global__ __launch_bounds__(TT::kWaves * 64, MMV_MIN_WAVES_PER_SIMD) void seg_k
     __shared__ SegShared<TT::kWaves> sm;
     constexpr bool kProduct = kOp == kSpmv || kOp == kSpmvCsr;
     const int tid = threadIdx.x;
-#ifdef MMV_TRACE
-    const uint64_t t_begin = wall_clock64();
-#endif
     // A workgroup that starts competes with the ones in the middle of their arithmetic: its ticket
     // and its loads go first (measured: 2 to 3 % on the long scans)
 #if MMV_LOAD_PRIO
@@ -606,9 +593,6 @@ __global__ __launch_bounds__(TT::kWaves * 64, MMV_MIN_WAVES_PER_SIMD) void seg_k
     }
     if (!P.ordered) __syncthreads();
     const uint32_t tile = __builtin_amdgcn_readfirstlane(P.ordered ? blockIdx.x : sm.tile);   // a scalar, like the wave index
-#ifdef MMV_TRACE
-    if (tid == 0 && P.trace) P.trace[(uint64_t)tile * 8] = t_begin;
-#endif
     if (kProduct && late_val)
         seg_tile<TT, kOp, kMfma, kProduct>(P, hints, sm, tile);
     else

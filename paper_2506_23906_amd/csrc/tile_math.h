@@ -271,32 +271,6 @@ template <> struct SpecMfma<TBF16> {
     }
 };
 
-#ifndef MMV_F32_NATIVE_MFMA
-#define MMV_F32_NATIVE_MFMA 0
-#endif
-
-#if MMV_F32_NATIVE_MFMA
-template <> struct SpecMfma<TF32> {
-    // fp32 on the fp32 matrix instruction: sixteen K-steps of two positions, half h supplies position
-    // 16 h + j in step j (word j / 4, element j % 4 of the lane's registers, as they are).
-    struct Operand {};
-    static __device__ __forceinline__ Operand operand(int) { return Operand(); }
-    static __device__ __forceinline__ void pin(Operand &) {}
-    static __device__ __forceinline__ void run(const v4u *raw, int lane, float (&acc)[16], const Operand &) {
-        run(raw, lane, acc);
-    }
-    static __device__ __forceinline__ void run(const v4u *raw, int lane, float (&acc)[16]) {
-        const int c = lane & 31, h = lane >> 5;
-        const int ones = c - 16 * h + 1;   // positions 16 h + j <= c  <=>  j < ones
-        v16f r = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-        for (int j = 0; j < 16; ++j)
-            r = __builtin_amdgcn_mfma_f32_32x32x2f32(j < ones ? 1.0f : 0.0f, from_bits<float>(raw[j / 4][j % 4]), r, 0, 0, 0);
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[v] = r[v];
-    }
-};
-#else
 template <> struct SpecMfma<TF32> {
     // fp32 through the bf16 matrix pipe, exactly: every value is split into three bf16 pieces
     // (8 + 8 + 8 significand bits, x = hi + mid + lo with no rounding), the pieces are
@@ -359,8 +333,6 @@ template <> struct SpecMfma<TF32> {
         for (int v = 0; v < 16; ++v) acc[v] = r[v];
     }
 };
-
-#endif
 
 template <> struct SpecMfma<TSpmv> : SpecMfma<TF32> {};
 

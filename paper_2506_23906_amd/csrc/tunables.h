@@ -121,18 +121,6 @@ struct Params {
     uint32_t ordered;       // the whole grid is resident at once: workgroup b takes tile b, no ticket
     uint32_t stagger_wgs;   // workgroups [0, stagger_wgs) start after a delay of up to ...
     uint32_t stagger_ticks; // ... this many ticks of the 100 MHz clock, spread evenly over them
-#ifdef MMV_TRACE
-    uint64_t *trace;        // 8 timestamps per tile (development builds only)
-#endif
 };
-
-#ifdef MMV_TRACE
-#define MMV_STAMP(k)                                                                     \
-    do {                                                                                 \
-        if (tid == 0 && P.trace) P.trace[(uint64_t)tile * 8 + (k)] = wall_clock64();     \
-    } while (0)
-#else
-#define MMV_STAMP(k) do { } while (0)
-#endif
 
 }  // namespace
