@@ -43,7 +43,8 @@ typedef enum {
     MMV_ERR_NULL = 2,        /* a required pointer is NULL */
     MMV_ERR_UNSUPPORTED = 3, /* valid but not implemented combination */
     MMV_ERR_WORKSPACE = 4,   /* workspace too small or misaligned */
-    MMV_ERR_HIP = 5          /* a HIP launch failed */
+    MMV_ERR_HIP = 5,         /* a HIP launch failed */
+    MMV_ERR_TOO_LARGE = 6    /* mmv_segscan_static: the input needs more scratch than the built-in array holds */
 } mmv_status;
 
 /* Input element type / accumulator-and-output type (appendix "Implementation of
@@ -106,6 +107,24 @@ size_t mmv_spmv_csr_workspace_bytes(uint64_t n_rows, uint64_t nnz);
 mmv_status mmv_segscan(const void *d_x, const void *d_flags, uint64_t n, void *d_z,
                        mmv_dtype dt, mmv_flag_fmt ff, mmv_variant v,
                        void *d_ws, size_t ws_bytes, void *hip_stream);
+
+/* mmv_segscan for callers that cannot allocate device memory and have no workspace to pass: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and error
+ * behaviour as mmv_segscan, without d_ws / ws_bytes: the tile descriptors (and, for MMV_FLAGS_U8, the packed
+ * copy of the flags) live in an array of MMV_STATIC_SCRATCH_BYTES bytes that is part of the library's device
+ * code, so every GPU the library runs on holds that much memory from the first call on it until the process
+ * ends.  The call allocates and frees nothing, on the device or through any library.
+ *   limit   mmv_workspace_bytes(MMV_OP_SEGSCAN, dt, ff, n) <= MMV_STATIC_SCRATCH_BYTES, else
+ *           MMV_ERR_TOO_LARGE is returned and nothing is launched.  With packed flags that is about 2^31
+ *           fp32, 2^32 16-bit or 2^33 int8 elements; with one flag byte per element about 8 million.
+ *   sharing every call on one GPU uses that GPU's one array, which keeps the last call's contents: each
+ *           call clears what it needs inside its stream, and two calls that overlap in time on one GPU
+ *           (two streams, two host threads) race and give undefined results.  Calls on different GPUs
+ *           are independent.  A time-out of the look-back cannot be read back (there is no workspace to
+ *           hand to mmv_workspace_status). */
+#define MMV_STATIC_SCRATCH_BYTES (1u << 20)
+mmv_status mmv_segscan_static(const void *d_x, const void *d_flags, uint64_t n, void *d_z,
+                              mmv_dtype dt, mmv_flag_fmt ff, mmv_variant v, void *hip_stream);
 
 /* Segmented sum (Sec. 2): the last element of every segment of the segmented
  * scan, in segment order; equals Algorithm SCD (Sec. 4.1) with the compress

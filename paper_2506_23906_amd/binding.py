@@ -28,8 +28,9 @@ EXPORTS = [
     "mmv_workspace_bytes", "mmv_segscan", "mmv_segsum", "mmv_spmv_coo", "mmv_workspace_status",
     "mmv_stream_copy", "mmv_gather_reference", "mmv_status_string", "mmv_tile_elems", "mmv_set_kernel_events",
     "mmv_spmv_csr_workspace_bytes", "mmv_spmv_csr", "mmv_scan", "mmv_compress", "mmv_diff", "mmv_revert",
-    "mmv_segsum_scd", "mmv_segscan_sscr",
+    "mmv_segsum_scd", "mmv_segscan_sscr", "mmv_segscan_static",
 ]
+STATIC_SCRATCH_BYTES = 1 << 20   # MMV_STATIC_SCRATCH_BYTES
 
 _DTYPES = {torch.float32: MMV_F32_F32, torch.float16: MMV_F16_F32, torch.bfloat16: MMV_BF16_F32,
            torch.int8: MMV_I8_I32, torch.uint8: MMV_U8_XOR}   # uint8 values: bytes under bit-wise exclusive or
@@ -58,6 +59,8 @@ def load() -> ctypes.CDLL:
     lib.mmv_workspace_bytes.restype = sz
     lib.mmv_segscan.argtypes = [vp, vp, u64, vp, i32, i32, i32, vp, sz, vp]
     lib.mmv_segscan.restype = i32
+    lib.mmv_segscan_static.argtypes = [vp, vp, u64, vp, i32, i32, i32, vp]
+    lib.mmv_segscan_static.restype = i32
     lib.mmv_segsum.argtypes = [vp, vp, u64, vp, u64, vp, i32, i32, i32, vp, sz, vp]
     lib.mmv_segsum.restype = i32
     lib.mmv_spmv_coo.argtypes = [u64, u64, u64, vp, vp, vp, vp, vp, i32, vp, sz, vp]
@@ -149,6 +152,17 @@ def mmv_segscan(x: torch.Tensor, flags: torch.Tensor, n: int | None = None, z: t
     st = lib.mmv_segscan(_dev(x, "x"), _dev(flags, "flags"), n, _dev(z, "z"), dt, ff, _VARIANTS[variant],
                          _dev(ws, "ws"), ws.numel(), _stream_ptr(stream))
     _check(st, "mmv_segscan")
+    return z
+
+
+def mmv_segscan_static(x: torch.Tensor, flags: torch.Tensor, z: torch.Tensor, n: int | None = None,
+                       variant: str = "mfma", stream=None) -> torch.Tensor:
+    """mmv_segscan on the library's built-in scratch array: the caller passes inputs and the output, nothing
+    is allocated (neither here nor in the library)."""
+    n = x.numel() if n is None else n
+    st = load().mmv_segscan_static(_dev(x, "x"), _dev(flags, "flags"), n, _dev(z, "z"), _DTYPES[x.dtype],
+                                   _flag_fmt(flags), _VARIANTS[variant], _stream_ptr(stream))
+    _check(st, "mmv_segscan_static")
     return z
 
 

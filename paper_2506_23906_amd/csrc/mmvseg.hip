@@ -44,6 +44,41 @@
 #include "host.h"
 
 
+// ---- scratch for callers that cannot allocate (mmv_segscan_static) -------------------------------------------
+//
+// Device memory that exists from the moment the library is loaded: every GPU that runs this code object
+// holds its own copy of the array at its own address until the process ends.  In host code the array's
+// name is only a handle for hipGetSymbolAddress, never an address: the device address is asked once per
+// device, with that device current, and kept.
+static __device__ __align__(256) unsigned char scratch[MMV_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+std::atomic<void *> g_scratch_ptr[kMaxDevices];   // device address of `scratch`, per device; null = not asked yet
+
+// Address of the current device's copy of `scratch` (nullptr on failure).
+void *static_scratch() {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (p) return p;
+    void *q = nullptr;
+    if (hipGetSymbolAddress(&q, HIP_SYMBOL(scratch)) != hipSuccess || !q) return nullptr;
+    g_scratch_ptr[dev].store(q, std::memory_order_release);   // (two threads asking at once store the same address)
+    return q;
+}
+
+mmv_status segscan_call(const void *d_x, const void *d_flags, uint64_t n, void *d_z, mmv_dtype dt, mmv_flag_fmt ff,
+                        mmv_variant v, void *d_ws, size_t ws_bytes, hipStream_t s) {
+    Params P = {};
+    const mmv_status st = prepare(MMV_OP_SEGSCAN, d_x, d_flags, n, dt, ff, v, d_ws, ws_bytes, s, P);
+    if (st != MMV_OK) return st;
+    P.z = d_z;
+    return launch_dt<kScan>(P, dt, v, s) == hipSuccess ? MMV_OK : MMV_ERR_HIP;
+}
+
+}  // namespace
+
 // ---- C ABI ------------------------------------------------------------------------------------------------------
 
 extern "C" {
@@ -74,12 +109,21 @@ mmv_status mmv_segscan(const void *d_x, const void *d_flags, uint64_t n, void *d
     if (!d_z) return MMV_ERR_NULL;
     if (!aligned16(d_z)) return MMV_ERR_INVALID_ARG;
     if (d_z == d_x && valid_dtype(dt) && dt != MMV_F32_F32) return MMV_ERR_INVALID_ARG;
-    hipStream_t s = (hipStream_t)hip_stream;
-    Params P = {};
-    const mmv_status st = prepare(MMV_OP_SEGSCAN, d_x, d_flags, n, dt, ff, v, d_ws, ws_bytes, s, P);
-    if (st != MMV_OK) return st;
-    P.z = d_z;
-    return launch_dt<kScan>(P, dt, v, s) == hipSuccess ? MMV_OK : MMV_ERR_HIP;
+    return segscan_call(d_x, d_flags, n, d_z, dt, ff, v, d_ws, ws_bytes, (hipStream_t)hip_stream);
+}
+
+mmv_status mmv_segscan_static(const void *d_x, const void *d_flags, uint64_t n, void *d_z, mmv_dtype dt,
+                              mmv_flag_fmt ff, mmv_variant v, void *hip_stream) {
+    if (!valid_dtype(dt) || !valid_ff(ff) || !valid_variant(v) || n > kMaxN) return MMV_ERR_INVALID_ARG;
+    if (n == 0) return MMV_OK;
+    if (!d_z) return MMV_ERR_NULL;
+    if (!aligned16(d_z)) return MMV_ERR_INVALID_ARG;
+    if (d_z == d_x && dt != MMV_F32_F32) return MMV_ERR_INVALID_ARG;
+    // the tile descriptors (and the packed copy of one-byte flags) must fit the built-in array
+    if (ws_layout(MMV_OP_SEGSCAN, dt, ff, n).total > (size_t)MMV_STATIC_SCRATCH_BYTES) return MMV_ERR_TOO_LARGE;
+    void *ws = static_scratch();
+    if (!ws) return MMV_ERR_HIP;
+    return segscan_call(d_x, d_flags, n, d_z, dt, ff, v, ws, (size_t)MMV_STATIC_SCRATCH_BYTES, (hipStream_t)hip_stream);
 }
 
 mmv_status mmv_segsum(const void *d_x, const void *d_flags, uint64_t n, void *d_out, uint64_t out_capacity,
@@ -411,6 +455,7 @@ const char *mmv_status_string(mmv_status s) {
         case MMV_ERR_UNSUPPORTED: return "unsupported";
         case MMV_ERR_WORKSPACE: return "workspace too small or misaligned";
         case MMV_ERR_HIP: return "HIP error";
+        case MMV_ERR_TOO_LARGE: return "input too large for the built-in scratch of mmv_segscan_static";
     }
     return "unknown status";
 }
