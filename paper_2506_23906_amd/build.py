@@ -19,8 +19,10 @@ FLAGS = [
 ]
 
 
-def build(verbose: bool = False, extra: list[str] | None = None) -> str:
-    tmp = LIB + ".tmp.%d" % os.getpid()
+def build(verbose: bool = False, extra: list[str] | None = None, out: str | None = None) -> str:
+    """Compiles the library; `extra` adds compiler flags (-D tunables), `out` names another output file."""
+    lib = out or LIB
+    tmp = lib + ".tmp.%d" % os.getpid()
     cmd = [HIPCC] + FLAGS + (extra or []) + ["-o", tmp, SRC]
     res = subprocess.run(cmd, capture_output=True, text=True)
     # the host pass does not know the packed-fp32 feature name; that note is harmless
@@ -30,8 +32,8 @@ def build(verbose: bool = False, extra: list[str] | None = None) -> str:
         raise RuntimeError("hipcc failed building libmmvseg.so")
     if verbose and err.strip():
         sys.stderr.write(err + "\n")
-    os.replace(tmp, LIB)
-    return LIB
+    os.replace(tmp, lib)
+    return lib
 
 
 if __name__ == "__main__":

@@ -19,14 +19,13 @@ __global__ __launch_bounds__(256) void fill_zero_kernel(uint32_t *a, uint64_t na
 // counted: it opens segment 0 whatever its flag says; bits at or beyond n are not counted).  The
 // same launch zeroes the header and the descriptors of the main kernel.
 __global__ __launch_bounds__(256) void count_tiles_kernel(uint32_t *zero, uint64_t zero_words, const uint32_t *fw,
-                                                          uint64_t n, uint32_t big_tiles, uint32_t big_elems,
-                                                          uint32_t tail_elems, uint32_t *cnt) {
+                                                          uint64_t n, TileRegions reg, uint32_t unit, uint32_t *cnt) {
     __shared__ uint32_t s_part[4];
     const uint32_t b = blockIdx.x, tid = threadIdx.x;
     for (uint64_t i = (uint64_t)b * 256 + tid; i < zero_words; i += (uint64_t)gridDim.x * 256) zero[i] = 0;
-    const uint64_t base = b < big_tiles ? (uint64_t)b * big_elems
-                                        : (uint64_t)big_tiles * big_elems + (uint64_t)(b - big_tiles) * tail_elems;
-    const uint64_t elems = b < big_tiles ? big_elems : tail_elems;
+    const TileSpan span = tile_span(reg, b, unit);
+    const uint64_t base = span.base;
+    const uint64_t elems = (uint64_t)span.cpw * unit;
     const uint64_t end = base + elems < n ? base + elems : n;
     uint32_t sum = 0;
     for (uint64_t w = (base >> 5) + tid; w < ((end + 31) >> 5); w += 256) {   // tiles begin on word borders
@@ -153,9 +152,8 @@ __global__ __launch_bounds__(256) void row_flags_kernel(const int32_t *row, uint
 // as in count_tiles_kernel; the rows of a wave that start in the same tile share one atomic add
 // on a zeroed table) and (d) the mark that some row is empty.
 __global__ __launch_bounds__(256) void csr_flags_kernel(const int32_t *rowptr, uint64_t n_rows, uint32_t *fw,
-                                                        uint32_t *rowmask, uint32_t *hdr, uint32_t big_tiles,
-                                                        uint32_t big_elems, uint32_t tail_elems, uint32_t *tile_count,
-                                                        const int32_t *col, uint64_t nnz) {
+                                                        uint32_t *rowmask, uint32_t *hdr, TileRegions reg, uint32_t unit,
+                                                        uint32_t *tile_count, const int32_t *col, uint64_t nnz) {
     const int lane = threadIdx.x & 63;
     if (blockIdx.x == 0 && threadIdx.x < 64) sample_column_runs(col, nnz, hdr, lane);
     const uint64_t r = (uint64_t)blockIdx.x * 256 + threadIdx.x;
@@ -166,9 +164,7 @@ __global__ __launch_bounds__(256) void csr_flags_kernel(const int32_t *rowptr, u
         nonempty = b > a;
         if (nonempty) {
             atomicOr(fw + ((uint32_t)a >> 5), 1u << ((uint32_t)a & 31u));
-            const uint64_t big_total = (uint64_t)big_tiles * big_elems;
-            if (a > 0) tile = (uint32_t)a < big_total ? (uint32_t)a / big_elems
-                                                      : big_tiles + (uint32_t)(((uint32_t)a - big_total) / tail_elems);
+            if (a > 0) tile = tile_of_element(reg, (uint64_t)a, unit);
         }
     }
     const uint64_t m = __ballot(nonempty);

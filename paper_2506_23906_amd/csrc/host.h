@@ -7,22 +7,24 @@ namespace {
 // ---- host side -------------------------------------------------------------------------------------------------
 
 inline size_t round256(size_t b) { return (b + 255) & ~(size_t)255; }
-// Tile plan.  A tile costs one ticket (about 11 ns, serialised), so tiles are as large as the
-// registers allow: kMaxCpw chunks of 2048 elements per wave.  The workgroups of the last round
-// would leave most of the chip idle while they finish, so the end of the vector is cut into
-// shorter tiles (one chunk per wave); inputs that fit into one round of resident workgroups
-// get equal tiles of just the size that gives every workgroup one.
+// Tile plan.  A tile costs one ticket (about 11 ns, serialised), so tiles are as large as the registers
+// allow: kMaxCpw chunks of 2048 elements per wave.  Inputs that fit into one round of resident workgroups
+// get equal tiles of just the size that gives every workgroup one.  A longer vector starts with groups of
+// tiles of 1, 2, ... chunks per wave and ends with groups of ..., 2, 1: started together on full tiles, the
+// workgroups of the first round all load, then all compute, then all store (nothing overlaps for a whole
+// tile time), and those of the last round would leave most of the chip idle while the last ones finish.
+// (Measured on the int8 scan: the time of a launch is a fixed 22 us plus 0.216 ms per 2^28 elements with
+// full tiles throughout and one group of short tiles at the end.)
 constexpr uint64_t kResident = MMV_MIN_TILES;   // workgroups resident at once (2 per compute unit)
-#ifndef MMV_TAIL_ROUNDS
-#define MMV_TAIL_ROUNDS 1
+#ifndef MMV_HEAD_GROUP
+#define MMV_HEAD_GROUP 128   // tiles per length at the start of a long vector (0: full tiles from the start)
+#endif
+#ifndef MMV_TAIL_GROUP
+#define MMV_TAIL_GROUP 128   // tiles per length (2 chunks per wave and more) at the end of a long vector
 #endif
 #ifndef MMV_TAIL_TILES
-#define MMV_TAIL_TILES (MMV_TAIL_ROUNDS * kResident / 2)   // half a round measured best (256, 512, 768 within 1.5 %)
+#define MMV_TAIL_TILES 256   // tiles of one chunk per wave at the very end (the last of them is ragged)
 #endif
-#ifndef MMV_TAIL_CPW
-#define MMV_TAIL_CPW 1
-#endif
-constexpr uint64_t kTailTiles = MMV_TAIL_TILES;  // short tiles at the end of a long vector
 constexpr uint64_t kCountSumTiles = 2048;        // up to this many tiles the segmented sum needs no prefix kernel
 inline bool is_spmv(mmv_op op) { return op == MMV_OP_SPMV_COO || op == MMV_OP_SPMV_CSR; }
 inline int max_cpw(mmv_op op, mmv_dtype dt) {
@@ -48,33 +50,57 @@ inline int waves_of(mmv_op op, mmv_dtype dt) {
     return 1;
 }
 struct TilePlan {
-    uint64_t big_tiles, tail_tiles;
-    uint32_t big_elems, tail_cpw, tail_elems;
-    uint64_t tiles() const { return big_tiles + tail_tiles; }
+    TileRegions reg;
+    uint64_t tiles;        // all tiles (reg.num_tiles holds it when it fits 31 bits)
+    uint32_t unit;         // elements of one chunk per wave
+    uint32_t body_elems;   // elements of a tile in the middle of the vector
 };
 inline TilePlan tile_plan(mmv_op op, mmv_dtype dt, uint64_t n) {
-    TilePlan p;
+    TilePlan p = {};
     const uint64_t unit = (uint64_t)waves_of(op, dt) * kChunkElems;  // one chunk per wave
     const int cpw = max_cpw(op, dt);
-    p.big_elems = (uint32_t)(unit * cpw);
-    if (n <= kResident * p.big_elems) {
+    p.unit = (uint32_t)unit;
+    TileRegions &R = p.reg;
+    uint64_t tiles = 0, at = 0;
+    auto add = [&](uint32_t c, uint64_t count) {   // `count` tiles of c chunks per wave from element `at` on
+        if (count == 0) return;
+        R.base[R.count] = at;
+        R.first[R.count] = (uint32_t)tiles;
+        R.cpw[R.count] = c;
+        ++R.count;
+        tiles += count;
+        at += count * c * unit;
+    };
+    if (n <= kResident * unit * cpw) {
         // one round: equal tiles, as small as gives every resident workgroup at most one
         uint64_t c = (n + kResident * unit - 1) / (kResident * unit);
         if (c < 1) c = 1;
         if (c > (uint64_t)cpw) c = cpw;
-        p.tail_cpw = (uint32_t)c;
-        p.big_tiles = 0;
+        p.body_elems = (uint32_t)(unit * c);
+        add((uint32_t)c, (n + unit * c - 1) / (unit * c));
     } else {
-        p.tail_cpw = MMV_TAIL_CPW < cpw ? MMV_TAIL_CPW : cpw;
-        const uint64_t tail = kTailTiles * unit * p.tail_cpw < n ? kTailTiles * unit * p.tail_cpw : n;
-        p.big_tiles = (n - tail) / p.big_elems;
+        p.body_elems = (uint32_t)(unit * cpw);
+        uint64_t head = 0, tail = (uint64_t)MMV_TAIL_TILES * unit;   // elements in the short tiles of both ends
+        for (int c = 1; c < cpw; ++c) head += (uint64_t)MMV_HEAD_GROUP * c * unit;
+        for (int c = 2; c < cpw; ++c) tail += (uint64_t)MMV_TAIL_GROUP * c * unit;
+        const bool graded = cpw > 1 && head + tail <= n;
+        if (!graded) head = 0, tail = (uint64_t)MMV_TAIL_TILES * unit < n ? (uint64_t)MMV_TAIL_TILES * unit : n;
+        if (graded)
+            for (int c = 1; c < cpw; ++c) add((uint32_t)c, MMV_HEAD_GROUP);
+        add((uint32_t)cpw, (n - head - tail) / (unit * cpw));
+        if (graded)
+            for (int c = cpw - 1; c >= 2; --c) add((uint32_t)c, MMV_TAIL_GROUP);
+        if (cpw > 1 || R.count == 0) {
+            add(1u, (n - at + unit - 1) / unit);          // what is left, the last tile ragged
+        } else {
+            tiles += (n - at + unit - 1) / unit;          // (tiles of one chunk per wave throughout: one region)
+        }
     }
-    p.tail_elems = (uint32_t)(unit * p.tail_cpw);
-    const uint64_t rest = n - p.big_tiles * p.big_elems;
-    p.tail_tiles = (rest + p.tail_elems - 1) / p.tail_elems;
+    p.tiles = tiles;
+    R.num_tiles = (uint32_t)(tiles < 0x7fffffffull ? tiles : 0x7fffffffull);
     return p;
 }
-inline uint64_t tiles_for(uint64_t n, mmv_op op, mmv_dtype dt) { return tile_plan(op, dt, n).tiles(); }
+inline uint64_t tiles_for(uint64_t n, mmv_op op, mmv_dtype dt) { return tile_plan(op, dt, n).tiles; }
 inline bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
 inline bool aligned4(const void *p) { return ((uintptr_t)p & 3u) == 0; }
 
@@ -208,12 +234,12 @@ uint32_t resident_workgroups(const void *kernel, int threads, std::atomic<uint32
 template <typename TT, int kOp, bool kMfma> hipError_t launch_variant(Params P, hipStream_t s) {
     static std::atomic<uint32_t> occupancy[kMaxDevices];
     const uint32_t resident = resident_workgroups((const void *)seg_kernel<TT, kOp, kMfma>, TT::kWaves * 64, occupancy);
-    P.ordered = P.num_tiles <= resident ? 1u : 0u;
+    P.first_round = P.num_tiles < resident ? P.num_tiles : resident;
     // SpMV: the workgroups of the first round start spread over about one tile time.  Started together
     // they stay in step (load, gather, compute all at the same time) and the memory pipe idles half the
     // time; measured 4 to 7 % on the long SpMV kernels, nothing on the scans.
     P.stagger_wgs = resident;
-    P.stagger_ticks = (kOp == kSpmv || kOp == kSpmvCsr) ? MMV_SPMV_STAGGER_US * 100u : 0u;
+    P.stagger_ticks = ((kOp == kSpmv || kOp == kSpmvCsr) && P.num_tiles > resident) ? MMV_SPMV_STAGGER_US * 100u : 0u;
     seg_kernel<TT, kOp, kMfma><<<P.num_tiles, TT::kWaves * 64, 0, s>>>(P, P.hdr + kHdrHints);
     return hipGetLastError();
 }
@@ -221,10 +247,9 @@ template <typename TT, int kOp, bool kMfma> hipError_t launch_variant(Params P, 
 template <typename TT, int kOp>
 hipError_t launch_seg(Params P, mmv_variant v, hipStream_t s) {
     const TilePlan plan = tile_plan((mmv_op)kOp, TT::kDtype, P.n);
-    if (plan.tiles() > 0x7fffffffull) return hipErrorInvalidValue;
-    P.num_tiles = (uint32_t)plan.tiles();
-    P.big_tiles = (uint32_t)plan.big_tiles;
-    P.tail_cpw = plan.tail_cpw;
+    if (plan.tiles > 0x7fffffffull) return hipErrorInvalidValue;
+    P.num_tiles = (uint32_t)plan.tiles;
+    P.reg = plan.reg;
     if (tl_ev_start && hipEventRecord(tl_ev_start, s) != hipSuccess) return hipErrorUnknown;
     if (v == MMV_VARIANT_MFMA) {
         if (launch_variant<TT, kOp, true>(P, s) != hipSuccess) return hipErrorUnknown;

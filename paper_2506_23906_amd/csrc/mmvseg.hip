@@ -148,16 +148,15 @@ mmv_status mmv_segsum(const void *d_x, const void *d_flags, uint64_t n, void *d_
     const TilePlan plan = tile_plan(MMV_OP_SEGSUM, dt, n);
     const WsLayout L = ws_layout(MMV_OP_SEGSUM, dt, ff, n);
     uint32_t *tile_count = (uint32_t *)((char *)d_ws + L.desc_c);
-    if (plan.tiles() > 0x7fffffffull) return MMV_ERR_INVALID_ARG;
-    count_tiles_kernel<<<(unsigned)plan.tiles(), 256, 0, s>>>((uint32_t *)d_ws, L.desc_c / 4, P.fw, n,
-                                                               (uint32_t)plan.big_tiles, plan.big_elems,
-                                                               plan.tail_elems, tile_count);
+    if (plan.tiles > 0x7fffffffull) return MMV_ERR_INVALID_ARG;
+    count_tiles_kernel<<<(unsigned)plan.tiles, 256, 0, s>>>((uint32_t *)d_ws, L.desc_c / 4, P.fw, n, plan.reg,
+                                                             plan.unit, tile_count);
     if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
     // few tiles: every tile of the main kernel adds up the counts before it; many: one more small kernel
     // turns the counts into prefix sums first
-    P.count_is_prefix = plan.tiles() > kCountSumTiles ? 1u : 0u;
+    P.count_is_prefix = plan.tiles > kCountSumTiles ? 1u : 0u;
     if (P.count_is_prefix) {
-        scan_counts_kernel<<<1, 1024, 0, s>>>(tile_count, (uint32_t)plan.tiles(), d_nseg);
+        scan_counts_kernel<<<1, 1024, 0, s>>>(tile_count, (uint32_t)plan.tiles, d_nseg);
         if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
     }
     P.tile_count = tile_count;
@@ -360,8 +359,8 @@ mmv_status mmv_spmv_csr(uint64_t n_rows, uint64_t n_cols, uint64_t nnz, const in
     uint32_t *tile_count = (uint32_t *)(ws + C.main_ws + L.desc_c);
     const uint64_t row_blocks = (n_rows + 255) / 256;
     csr_flags_kernel<<<(unsigned)row_blocks, 256, 0, s>>>(d_rowptr, n_rows, fw, (uint32_t *)(ws + C.rowmask),
-                                                          (uint32_t *)(ws + C.main_ws), (uint32_t)plan.big_tiles,
-                                                          plan.big_elems, plan.tail_elems, tile_count, d_col, nnz);
+                                                          (uint32_t *)(ws + C.main_ws), plan.reg, plan.unit,
+                                                          tile_count, d_col, nnz);
     if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
     // rowmap = COMPRESS(0 .. n_rows - 1, rowmask): the k-th segment belongs to row rowmap[k]
     {
@@ -383,9 +382,9 @@ mmv_status mmv_spmv_csr(uint64_t n_rows, uint64_t n_cols, uint64_t nnz, const in
     P.hdr = (uint32_t *)(ws + C.main_ws);
     P.desc_v = (uint64_t *)(ws + C.main_ws + L.desc_v);
     P.fw = fw;
-    P.count_is_prefix = plan.tiles() > kCountSumTiles ? 1u : 0u;
+    P.count_is_prefix = plan.tiles > kCountSumTiles ? 1u : 0u;
     if (P.count_is_prefix) {
-        scan_counts_kernel<<<1, 1024, 0, s>>>(tile_count, (uint32_t)plan.tiles(), (uint64_t *)(ws + C.rowcount));
+        scan_counts_kernel<<<1, 1024, 0, s>>>(tile_count, (uint32_t)plan.tiles, (uint64_t *)(ws + C.rowcount));
         if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
     }
     P.tile_count = tile_count;
@@ -464,8 +463,7 @@ uint32_t mmv_tile_elems(mmv_op op, mmv_dtype dt, uint64_t n) {
     if (!valid_dtype(dt)) return 0;
     if (op == MMV_OP_COMPRESS) return (uint32_t)compress_tile(n);
     if (op != MMV_OP_SEGSCAN && op != MMV_OP_SEGSUM && op != MMV_OP_SCAN && !is_spmv(op)) return 0;
-    const TilePlan p = tile_plan(op, is_spmv(op) ? MMV_F32_F32 : dt, n);
-    return p.big_tiles ? p.big_elems : p.tail_elems;
+    return tile_plan(op, is_spmv(op) ? MMV_F32_F32 : dt, n).body_elems;
 }
 
 }  // extern "C"

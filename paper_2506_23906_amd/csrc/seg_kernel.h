@@ -90,13 +90,10 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const uint64_t n = P.n;
     uint32_t *rows = sm.rows[wave];
-    // tiles at the end of the vector are shorter (fewer chunks per wave)
-    const bool big_tile = tile < P.big_tiles;
-    const int cpw_t = big_tile ? kCpw : (int)P.tail_cpw;
-    const uint64_t tile_base =
-        big_tile ? (uint64_t)tile * (kWaves * kCpw * kChunkElems)
-                 : (uint64_t)P.big_tiles * (kWaves * kCpw * kChunkElems) +
-                       (uint64_t)(tile - P.big_tiles) * ((uint64_t)kWaves * P.tail_cpw * kChunkElems);
+    // tiles at both ends of a long vector are shorter (fewer chunks per wave)
+    const TileSpan span = tile_span(P.reg, tile, kWaves * kChunkElems);
+    const int cpw_t = (int)span.cpw;
+    const uint64_t tile_base = span.base;
     const uint64_t wave_base = tile_base + (uint64_t)wave * cpw_t * kChunkElems;
 
     // ---- all inputs of my span: flag word of my row and raw values (and columns) per chunk ----
@@ -575,24 +572,27 @@ __global__ __launch_bounds__(TT::kWaves * 64, MMV_MIN_WAVES_PER_SIMD) void seg_k
     if constexpr (kProduct) late_val = hints[kHdrColumnRuns - kHdrHints] != 0;
 
     // Tiles are handed out by an atomic ticket, so that a tile never waits for a predecessor that
-    // has not started (workgroups need not start in index order).  The tickets of the workgroups
-    // that start together are served one after the other (about 11 ns each): a grid that is resident
-    // as a whole cannot block itself that way and skips them.
+    // has not started.  The tickets of workgroups that start together are served one after the other
+    // (about 11 ns each: the 512 workgroups of the first round would get theirs spread over 6 us), so the
+    // workgroups that are resident at once from the start (all of them, if the grid fits the device) take
+    // the tile of their own index instead: they are started in index order, so the predecessors of such a
+    // tile are never behind it.  Tickets begin where those tiles end.
+    const bool own_index = blockIdx.x < P.first_round;
     if (tid == 0) {
         sm.ready = 0;
-        if (!P.ordered) {
-            if (blockIdx.x < P.stagger_wgs) {
-                // low-discrepancy spread of the start times: fraction of blockIdx * golden ratio
-                const uint32_t frac = blockIdx.x * 2654435769u;
-                const uint64_t wait = ((uint64_t)frac * P.stagger_ticks) >> 32;
-                const uint64_t t0 = wall_clock64();
-                while (wall_clock64() - t0 < wait) __builtin_amdgcn_s_sleep(8);
-            }
-            sm.tile = __hip_atomic_fetch_add(P.hdr + kHdrTicket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (blockIdx.x < P.stagger_wgs && P.stagger_ticks) {
+            // low-discrepancy spread of the start times: fraction of blockIdx * golden ratio
+            const uint32_t frac = blockIdx.x * 2654435769u;
+            const uint64_t wait = ((uint64_t)frac * P.stagger_ticks) >> 32;
+            const uint64_t t0 = wall_clock64();
+            while (wall_clock64() - t0 < wait) __builtin_amdgcn_s_sleep(8);
         }
+        if (!own_index)
+            sm.tile = P.first_round +
+                      __hip_atomic_fetch_add(P.hdr + kHdrTicket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    if (!P.ordered) __syncthreads();
-    const uint32_t tile = __builtin_amdgcn_readfirstlane(P.ordered ? blockIdx.x : sm.tile);   // a scalar, like the wave index
+    if (!own_index) __syncthreads();
+    const uint32_t tile = __builtin_amdgcn_readfirstlane(own_index ? blockIdx.x : sm.tile);   // a scalar, like the wave index
     if (kProduct && late_val)
         seg_tile<TT, kOp, kMfma, kProduct>(P, hints, sm, tile);
     else

@@ -97,6 +97,51 @@ typedef short v8s __attribute__((ext_vector_type(8)));
 //   kSpmvCsr    CSR SpMV: as kSpmv, but the sum of the k-th segment goes to y[rowmap[k]]
 enum Op { kScan = 0, kSum = 1, kSpmv = 2, kPlainScan = 3, kSpmvCsr = 7 };
 
+// The tiles of one launch, as up to kMaxRegions runs of equally long tiles: a long vector starts with tiles
+// of growing length (the workgroups of the first round then finish at different times and the stores of
+// the short ones begin while the long ones still load), continues with tiles of the full length and ends
+// with tiles of shrinking length (the workgroups of the last round finish together).  The length of a tile
+// is its number of chunks per wave.
+constexpr int kMaxRegions = 8;
+struct TileRegions {
+    uint64_t base[kMaxRegions];    // first element of the region
+    uint32_t first[kMaxRegions];   // first tile of the region (first[0] = 0)
+    uint32_t cpw[kMaxRegions];     // chunks per wave of its tiles
+    uint32_t count;                // regions in use
+    uint32_t num_tiles;
+};
+struct TileSpan {
+    uint64_t base;   // first element of the tile
+    uint32_t cpw;    // its chunks per wave
+};
+// Where tile `tile` lies (`unit` = elements of one chunk per wave: waves x 2048).  With a uniform tile number
+// everything here stays in scalar registers.
+__host__ __device__ __forceinline__ TileSpan tile_span(const TileRegions &R, uint32_t tile, uint32_t unit) {
+    uint64_t base = R.base[0];
+    uint32_t first = 0, cpw = R.cpw[0];
+#pragma unroll
+    for (int i = 1; i < kMaxRegions; ++i)
+        if (i < (int)R.count && tile >= R.first[i]) {
+            base = R.base[i];
+            first = R.first[i];
+            cpw = R.cpw[i];
+        }
+    return {base + (uint64_t)(tile - first) * cpw * unit, cpw};
+}
+// The tile that holds element e.
+__host__ __device__ __forceinline__ uint32_t tile_of_element(const TileRegions &R, uint64_t e, uint32_t unit) {
+    uint64_t base = R.base[0];
+    uint32_t first = 0, cpw = R.cpw[0];
+#pragma unroll
+    for (int i = 1; i < kMaxRegions; ++i)
+        if (i < (int)R.count && e >= R.base[i]) {
+            base = R.base[i];
+            first = R.first[i];
+            cpw = R.cpw[i];
+        }
+    return first + (uint32_t)((e - base) / ((uint64_t)cpw * unit));
+}
+
 struct Params {
     const void *x;          // values (scan, sum) / val (spmv)
     const uint32_t *fw;     // packed flag words (scan, sum)
@@ -116,9 +161,9 @@ struct Params {
     const uint32_t *tile_count;  // sum: segment starts per tile (position 0 not counted), or ...
     uint32_t count_is_prefix;    // ... their exclusive prefix sums already (long vectors)
     uint32_t num_tiles;
-    uint32_t big_tiles;     // tiles [0, big_tiles) have the full number of chunks per wave ...
-    uint32_t tail_cpw;      // ... the rest have this many (shorter tiles at the end shorten the tail)
-    uint32_t ordered;       // the whole grid is resident at once: workgroup b takes tile b, no ticket
+    TileRegions reg;        // which elements a tile covers
+    uint32_t first_round;   // workgroups [0, first_round) are resident together from the start and take the tile
+                            // of their own index; the others take tickets
     uint32_t stagger_wgs;   // workgroups [0, stagger_wgs) start after a delay of up to ...
     uint32_t stagger_ticks; // ... this many ticks of the 100 MHz clock, spread evenly over them
 };

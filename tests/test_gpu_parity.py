@@ -127,6 +127,23 @@ def test_long_segments_across_many_tiles():
         check_sum(out, nseg, x, f)
 
 
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_vectors_longer_than_one_round_of_workgroups(dtype, variant):
+    """Just beyond what the resident workgroups cover with full tiles: the vector starts with tiles of growing length,
+    continues with full ones and ends with short ones; the first round of workgroups takes tiles by index, the rest by
+    ticket.  Sparse flags, so that carries cross every kind of tile border."""
+    rng = np.random.default_rng(77)
+    full = B.mmv_tile_elems(B.MMV_OP_SEGSCAN, B._DTYPES[torch.from_numpy(np.zeros(1, dtype=dtype)).dtype], 1 << 40)
+    for n in (512 * full + 1, 515 * full + 4321):
+        x = random_values(rng, n, dtype)
+        f = W.uniform_density_flags(n, 2e-5, seed=n % 1000)
+        print("long vector", dtype.__name__, variant, n, flush=True)
+        check_scan(run_segscan(x, f, variant), x, f)
+        out, nseg = run_segsum(x, f, variant)
+        check_sum(out, nseg, x, f)
+
+
 def test_repeated_runs_are_bit_identical_on_integers():
     x, f = W.segscan_i8_uniform_len(1 << 22, seed=4)
     xt, ft = dev(x), packed_dev(f)
