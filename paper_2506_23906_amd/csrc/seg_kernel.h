@@ -43,7 +43,8 @@ template <int N, int M> __device__ __forceinline__ void rotate_rows(v4u (&a)[N][
 template <int kWaves> struct SegShared {
     __attribute__((aligned(16))) uint32_t rows[kWaves][kRowsPerChunk * kRowStride];
     uint32_t wave_v[kWaves], wave_f[kWaves], wave_c[kWaves];
-    uint32_t tile, carry_v, carry_c, ready;
+    uint32_t early_v[kWaves], early_f[kWaves];   // plain sum and any-flag of every wave's span, written as the loads land
+    uint32_t tile, carry_v, carry_c, ready, arrived;
 };
 
 // One tile, from the loads on.  kLateVal (SpMV only): the values are loaded behind the gathers of
@@ -83,6 +84,14 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
     // the count of the segments before the tile comes from a table of per-tile counts made by a
     // small kernel before this one, so that no chunk has to wait for it
     constexpr bool kProduct = kOp == kSpmv || kOp == kSpmvCsr;      // values are val * x[col]
+    // A tile that holds no flag hands on a plain sum, and its successors cannot finish before they have it.  In the
+    // scan kernels such a tile publishes that sum as soon as its loads have landed, ahead of the row scans of
+    // phase A (which take several microseconds when all waves of a compute unit are at it): the wave whose loads
+    // land last adds up the sums of all waves.  Without this a vector without flags ran 13 % slower than one
+    // with a flag in every tile, each tile waiting 6 us for the slowest of the tiles before it.
+    constexpr int kEarlyMode = !kScanLike ? 0 : (sizeof(In) == 1 ? MMV_EARLY_I8 : (sizeof(In) == 2 ? MMV_EARLY_F16 : MMV_EARLY_F32));
+    constexpr bool kEarly = kEarlyMode != 0;
+    constexpr bool kEarlyLookback = kEarlyMode == 2;
 
     // the wave index as a scalar: everything derived from it (the wave's span, chunk bases, the
     // "whole chunk inside the vector" tests, base addresses of loads and stores) then lives in scalar
@@ -100,15 +109,19 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
     uint32_t F[kCpw];
     v4u raw[kCpw][2 * K];
     v4u rawc[kProduct ? kCpw : 1][2 * K];  // column indices (spmv)
+    // (the flag words go first: a wave knows whether its span holds a flag before the values have landed)
+#pragma unroll
+    for (int c = 0; c < kCpw; ++c) {
+        F[c] = 0;
+        if constexpr (kOp != kPlainScan) {
+            const uint64_t rs = wave_base + (uint64_t)c * kChunkElems + 32u * lane;
+            if (c < cpw_t && rs < n) F[c] = __builtin_nontemporal_load(P.fw + (rs >> 5));
+        }
+    }
 #pragma unroll
     for (int c = 0; c < kCpw; ++c) {
         const uint64_t cb = wave_base + (uint64_t)c * kChunkElems;
-        F[c] = 0;
         if (c < cpw_t) {
-            const uint64_t rs = cb + 32u * lane;
-            if constexpr (kOp != kPlainScan) {
-                if (rs < n) F[c] = __builtin_nontemporal_load(P.fw + (rs >> 5));
-            }
             if constexpr (kProduct) load_raw<TInt, kMfma>(P.col, cb, n, lane, rawc[c]);
             if constexpr (!kProduct || !kLateVal) load_raw<TT, kMfma>((const In *)P.x, cb, n, lane, raw[c]);
         }
@@ -120,6 +133,56 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
     if constexpr (kOp == kPlainScan && sizeof(In) == 1) {
         // counting segment starts: position 0 always opens a segment (byte 0 of the first word, both layouts)
         if (P.first_one && tile == 0 && tid == 0) raw[0][0][0] = (raw[0][0][0] & ~0xFFu) | 1u;
+    }
+    // bits beyond n do not count
+    if constexpr (kOp != kPlainScan) {
+#pragma unroll
+        for (int c = 0; c < kCpw; ++c) {
+            const uint64_t rs = wave_base + (uint64_t)c * kChunkElems + 32u * lane;
+            if (rs + 32 > n) F[c] = rs < n ? (F[c] & ((1u << (uint32_t)(n - rs)) - 1u)) : 0u;
+        }
+    }
+    if constexpr (kEarly) {
+        uint32_t any = 0;
+#pragma unroll
+        for (int c = 0; c < kCpw; ++c) any |= F[c];
+        if (tile == 0) any |= 1u;                       // nobody waits for the first tile's sum ahead of time
+        const bool span_flagged = __ballot(any != 0) != 0;
+        A s = A(0);
+        if (!span_flagged) {
+#pragma unroll
+            for (int c = 0; c < kCpw; ++c)
+                if (c < cpw_t) s += RawSum<TT>::run(raw[c]);
+            s = wave_sum<A, kAluLanes>(s);
+        }
+        uint32_t before = 0;
+        if (lane == 0) {
+            sm.early_v[wave] = to_bits(s);
+            sm.early_f[wave] = span_flagged ? 1u : 0u;
+            before = __hip_atomic_fetch_add(&sm.arrived, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
+        if (__builtin_amdgcn_readfirstlane(before) == kWaves - 1) {   // my wave's loads landed last
+            A total = A(0);
+            uint32_t flagged = 0;
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) {
+                total += from_bits<A>(sm.early_v[w]);
+                flagged |= sm.early_f[w];
+            }
+            if (!flagged) {
+                if (lane == 0) desc_store(P.desc_v + tile, kStatusAggregate, to_bits(total));
+                if constexpr (kEarlyLookback) {
+                    // ... and it looks back for the carry of the tiles before right away, so that the tile's own
+                    // prefix is out for its successors a whole phase A earlier (the other waves go on meanwhile)
+                    const A carry_in = lookback<A, kAluLanes>(P.desc_v, (int)tile, lane, P.hdr);
+                    if (lane == 0) {
+                        desc_store(P.desc_v + tile, kStatusPrefix, to_bits(carry_in + total));
+                        sm.carry_v = to_bits(carry_in);
+                        __hip_atomic_store(&sm.ready, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    }
+                }
+            }
+        }
     }
 
     // CSR SpMV: without empty rows the k-th segment is row k and the row map was not made
@@ -163,8 +226,6 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
       if (c < cpw_t) {
         const uint64_t cb = wave_base + (uint64_t)c * kChunkElems;
         const uint64_t row_start = cb + 32u * lane;  // first element of the row this lane owns
-        // ---- flags of my row (one 32-bit word = one row); bits beyond n do not count ----
-        if (row_start + 32 > n) F[S] = row_start < n ? (F[S] & ((1u << (uint32_t)(n - row_start)) - 1u)) : 0u;
         if constexpr (kProduct && kLateVal) {
             // product vector p(i) = val(i) * x(col(i)), in the layout the columns were loaded in: the
             // gathers go out as soon as the columns are there, the loads of the values right behind them
@@ -383,7 +444,9 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
 
     // ---- step 5c, first half: publish this tile ----
     const bool final_now = tile == 0 || tagg_f;  // carry out does not depend on predecessors
-    if (tid == 0) desc_store(P.desc_v + tile, final_now ? kStatusPrefix : kStatusAggregate, to_bits(tagg_v));
+    // (a tile without any flag, other than tile 0, has published its aggregate already where kEarly is set)
+    if (tid == 0 && (!kEarly || final_now))
+        desc_store(P.desc_v + tile, final_now ? kStatusPrefix : kStatusAggregate, to_bits(tagg_v));
 
     // carry into my span (used only by rows with no flag before them in the tile); the carry of
     // the predecessor tiles is added once it is known
@@ -397,7 +460,9 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
         if (pass == 1) {
             // ---- step 5c, second half: carry of the predecessor tiles by decoupled look-back ----
             A tile_carry = A(0);
-            if (wave == 0) {
+            // (a tile without flags, other than tile 0, has looked back already where kEarly is set)
+            const bool looked_back = kEarlyLookback && !final_now;
+            if (wave == 0 && !looked_back) {
                 if (tile > 0 && !head_flagged) tile_carry = lookback<A, kAluLanes>(P.desc_v, (int)tile, lane, P.hdr);
                 if (lane == 0) {
                     if (!final_now) desc_store(P.desc_v + tile, kStatusPrefix, to_bits(tile_carry + tagg_v));
@@ -405,7 +470,7 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
                     __hip_atomic_store(&sm.ready, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
                 }
             }
-            if (wave != 0 && !wex_f) {
+            if ((wave != 0 || looked_back) && !wex_f) {
                 // my span starts inside a segment that began in an earlier tile: wait for wave 0
                 while (__hip_atomic_load(&sm.ready, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) == 0)
                     __builtin_amdgcn_s_sleep(1);
@@ -580,6 +645,7 @@ __global__ __launch_bounds__(TT::kWaves * 64, MMV_MIN_WAVES_PER_SIMD) void seg_k
     const bool own_index = blockIdx.x < P.first_round;
     if (tid == 0) {
         sm.ready = 0;
+        sm.arrived = 0;
         if (blockIdx.x < P.stagger_wgs && P.stagger_ticks) {
             // low-discrepancy spread of the start times: fraction of blockIdx * golden ratio
             const uint32_t frac = blockIdx.x * 2654435769u;
@@ -591,7 +657,7 @@ __global__ __launch_bounds__(TT::kWaves * 64, MMV_MIN_WAVES_PER_SIMD) void seg_k
             sm.tile = P.first_round +
                       __hip_atomic_fetch_add(P.hdr + kHdrTicket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    if (!own_index) __syncthreads();
+    __syncthreads();
     const uint32_t tile = __builtin_amdgcn_readfirstlane(own_index ? blockIdx.x : sm.tile);   // a scalar, like the wave index
     if (kProduct && late_val)
         seg_tile<TT, kOp, kMfma, kProduct>(P, hints, sm, tile);

@@ -336,6 +336,65 @@ template <> struct SpecMfma<TF32> {
 
 template <> struct SpecMfma<TSpmv> : SpecMfma<TF32> {};
 
+// ---- plain sum of the raw registers of one chunk (for the aggregate of a tile that holds no flag) ----------
+//
+// A lane's partial sum over its 2 * K words; the layout does not matter.  Elements beyond n were loaded as zeros.
+template <typename TT> struct RawSum;
+template <> struct RawSum<TI8> {
+    static __device__ __forceinline__ uint32_t run(const v4u *raw) {
+        int s = 0;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int d = 0; d < 4; ++d) s = __builtin_amdgcn_sdot4((int)raw[i][d], 0x01010101, s, false);
+        return (uint32_t)s;
+    }
+};
+template <> struct RawSum<TX8> {
+    static __device__ __forceinline__ XorWord run(const v4u *raw) {
+        uint32_t x = 0;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int d = 0; d < 4; ++d) x ^= raw[i][d];
+        x ^= x >> 16;
+        x ^= x >> 8;
+        return XorWord(x & 0xFFu);
+    }
+};
+template <bool kBf16> struct RawSumHalf {
+    static __device__ __forceinline__ float run(const v4u *raw) {
+        typedef _Float16 v2h __attribute__((ext_vector_type(2)));
+        typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+        constexpr uint32_t kOnes = kBf16 ? 0x3F803F80u : 0x3C003C00u;
+        float s = 0.0f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                const uint32_t pair = raw[i][d];
+                if (kBf16)
+                    s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(v2bf, pair), __builtin_bit_cast(v2bf, kOnes), s, false);
+                else
+                    s = __builtin_amdgcn_fdot2(__builtin_bit_cast(v2h, pair), __builtin_bit_cast(v2h, kOnes), s, false);
+            }
+        return s;
+    }
+};
+template <> struct RawSum<TF16> : RawSumHalf<false> {};
+template <> struct RawSum<TBF16> : RawSumHalf<true> {};
+template <> struct RawSum<TF32> {
+    static __device__ __forceinline__ float run(const v4u *raw) {
+        float s[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int d = 0; d < 4; ++d) s[d] += from_bits<float>(raw[i][d]);
+        return (s[0] + s[1]) + (s[2] + s[3]);
+    }
+};
+template <> struct RawSum<TSpmv> : RawSum<TF32> {};
+
 // ---- steps 2-4 without the detour through LDS: row aggregates from the raw registers -----------------
 //
 // The aggregate of a row after the revert is x-bar(31) - x-bar(start - 1) = the sum of

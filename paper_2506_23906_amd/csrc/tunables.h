@@ -54,6 +54,18 @@ namespace {
 #ifndef MMV_LOAD_PRIO
 #define MMV_LOAD_PRIO 1   // wave priority while a workgroup takes its ticket and issues its loads (0: off)
 #endif
+// Scan kernels, tiles without any flag: 0 = the aggregate is published after phase A, as for every other tile;
+// 1 = the plain sum is published as soon as the tile's loads have landed; 2 = and the wave that publishes it looks
+// back for the carry at once.  Per input width (measured best on MI355X).
+#ifndef MMV_EARLY_I8
+#define MMV_EARLY_I8 2
+#endif
+#ifndef MMV_EARLY_F16
+#define MMV_EARLY_F16 1
+#endif
+#ifndef MMV_EARLY_F32
+#define MMV_EARLY_F32 0
+#endif
 #ifndef MMV_MIN_TILES
 #define MMV_MIN_TILES 512   // workgroups resident at once: 2 per compute unit (LDS)
 #endif
