@@ -24,7 +24,7 @@
  *  - Errors are returned as mmv_status; nothing aborts or throws.  Argument
  *    errors are detected on the host before anything is launched.
  *  - Position 0 always opens a segment, whatever its flag says (Problem 2.1 of
- *    Sec. 2: "if i = 0 or f(i) = 1").
+ *    Sec. 2 lets a segment begin at the first position or at a set flag).
  *  - n == 0 (nnz == 0) is valid: nothing is read, *d_nseg = 0, y is zero filled.
  */
 #ifndef MMVSEG_H
@@ -103,7 +103,14 @@ size_t mmv_spmv_csr_workspace_bytes(uint64_t n_rows, uint64_t nnz);
  *   d_x      n input values of the type `dt` names
  *   d_flags  n flags in format `ff`
  *   d_z      n outputs (fp32 or int32); may alias d_x only for MMV_F32_F32
- * Float results differ from the sequential definition by rounding only. */
+ * Integers (and bytes under exclusive or) are exact: they form a group, as Sec. 2 requires.  Floats do not, and
+ * the method subtracts two speculative prefixes of a row of 32 elements: a result is off by the rounding of that
+ * row's prefix (about 32 * 2^-24 of the row's sum of |x|; the carries add one rounding per level), not by the
+ * rounding of its own segment alone, so a segment of small values behind large ones in the same row of 32
+ * loses relative accuracy.  With fp32 inputs a position that starts a segment receives its input bit for bit.
+ * An infinity or NaN makes the rest of its own segment non-finite, as the definition does, and can in addition turn
+ * later positions of the same row of 32 into NaN (Inf - Inf); positions outside that row are not affected unless
+ * its own segment reaches them.  A block of 2048 positions that all start segments is copied exactly. */
 mmv_status mmv_segscan(const void *d_x, const void *d_flags, uint64_t n, void *d_z,
                        mmv_dtype dt, mmv_flag_fmt ff, mmv_variant v,
                        void *d_ws, size_t ws_bytes, void *hip_stream);
@@ -132,6 +139,8 @@ mmv_status mmv_segscan_static(const void *d_x, const void *d_flags, uint64_t n, 
  *   d_out         room for `out_capacity` sums (fp32 or int32)
  *   d_nseg        device uint64: receives the true number of segments,
  *                 1 + #{i >= 1 : f(i) = 1} for n >= 1
+ * Floating point: as for mmv_segscan (a sum is off by the rounding of the prefixes of the rows of 32 it starts
+ * and ends in; a non-finite value can reach the sums of the segments that share its row of 32).
  * Sums with index >= out_capacity are not written (d_nseg still holds the true
  * count); pass out_capacity = n to be safe.  The number of segments must be
  * below 2^32 (counts are carried in 32 bits). */
@@ -179,7 +188,7 @@ mmv_status mmv_spmv_csr(uint64_t n_rows, uint64_t n_cols, uint64_t nnz,
 mmv_status mmv_scan(const void *d_x, uint64_t n, void *d_z, mmv_dtype dt, mmv_variant v,
                     void *d_ws, size_t ws_bytes, void *hip_stream);
 
-/* COMPRESS (Sec. 2: "the entries of x whose flag is 1", example
+/* COMPRESS (Sec. 2: keeps the entries of x at which the mask is set, in order; the worked example there:
  * COMPRESS((2,2,3,3,1,3,1,2), (1,0,1,0,0,1,0,0)) = (2,3,3)); the output position
  * of an entry is the number of selected entries before it (the scan of the mask
  * in the proof of the SCD / SSCR theorem).
@@ -194,7 +203,7 @@ mmv_status mmv_compress(const void *d_x, const void *d_mask, uint64_t n,
                         void *d_out, uint64_t out_capacity, uint64_t *d_count,
                         mmv_flag_fmt ff, void *d_ws, size_t ws_bytes, void *hip_stream);
 
-/* DIFF (Sec. 4.1, "vector differentiation"): z(i) = x(i) - x(i-1), x(-1) = 0.
+/* DIFF (Sec. 4.1, the differentiation of a vector): z(i) = x(i) - x(i-1), x(-1) = 0.
  * d_z must not alias d_x.  No workspace. */
 mmv_status mmv_diff(const void *d_x, uint64_t n, void *d_z, mmv_elem et, void *hip_stream);
 
@@ -221,7 +230,7 @@ mmv_status mmv_segsum_scd(const void *d_x, const void *d_flags, uint64_t n,
 
 /* Algorithm SSCR (Sec. 4.1) as printed: segmented scan = REVERT(SCAN(x), SCAN(f),
  * COMPRESS(SCAN(x), f^-)).  Same arguments and results as mmv_segscan, same
- * remark on floating point as mmv_segsum_scd. */
+ * remark on floating point as mmv_segsum_scd (and a non-finite value reaches every later position). */
 mmv_status mmv_segscan_sscr(const void *d_x, const void *d_flags, uint64_t n, void *d_z,
                             mmv_dtype dt, mmv_flag_fmt ff, mmv_variant v,
                             void *d_ws, size_t ws_bytes, void *hip_stream);

@@ -89,6 +89,12 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
     // phase A (which take several microseconds when all waves of a compute unit are at it): the wave whose loads
     // land last adds up the sums of all waves.  Without this a vector without flags ran 13 % slower than one
     // with a flag in every tile, each tile waiting 6 us for the slowest of the tiles before it.
+    // Floats are not a group, so x-bar(j) - x-bar(j - 1) is not x(j) bit for bit.  With 32-bit inputs the striped
+    // registers of the load hold exactly the four positions a lane stores, so a position that starts a segment
+    // gets its input itself, and the positions behind it in the lane's four run on from there (the case of set
+    // flags in Algorithm "Revert Speculative Prefix Sums", taken per element).  16-bit inputs do not need it: their
+    // row prefixes are exact in fp32 unless the exponents of a row differ widely.
+    constexpr bool kExactStarts = MMV_EXACT_STARTS != 0 && kOp == kScan && sizeof(In) == 4;
     constexpr int kEarlyMode = !kScanLike ? 0 : (sizeof(In) == 1 ? MMV_EARLY_I8 : (sizeof(In) == 2 ? MMV_EARLY_F16 : MMV_EARLY_F32));
     constexpr bool kEarly = kEarlyMode != 0;
     constexpr bool kEarlyLookback = kEarlyMode == 2;
@@ -109,6 +115,7 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
     uint32_t F[kCpw];
     v4u raw[kCpw][2 * K];
     v4u rawc[kProduct ? kCpw : 1][2 * K];  // column indices (spmv)
+    v4u striped[kExactStarts && kKeepRows ? 2 * K : 1];   // the loaded words as they came, where phase A reorders raw[]
     // (the flag words go first: a wave knows whether its span holds a flag before the values have landed)
 #pragma unroll
     for (int c = 0; c < kCpw; ++c) {
@@ -282,6 +289,10 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
                 // chunks).
                 typename SpecMfma<TT>::Operand op = SpecMfma<TT>::operand(lane);
                 SpecMfma<TT>::pin(op);
+                if constexpr (kExactStarts) {
+#pragma unroll
+                    for (int i = 0; i < 2 * K; ++i) striped[i] = raw[S][i];
+                }
                 operand_layout_write4(raw[S], rows, lane);
                 dense_chunk = cb + kChunkElems <= n && __ballot(F[S] != 0xFFFFFFFFu) == 0;
                 if (dense_chunk) {
@@ -299,6 +310,10 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
                     store_spec_rows(rows, t, lane, acc);
                 }
             } else {
+                if constexpr (kExactStarts) {
+#pragma unroll
+                    for (int i = 0; i < 2 * K; ++i) striped[i] = raw[S][i];
+                }
                 if constexpr (K > 1) to_operand_layout<K>(raw[S], rows, lane);
 #pragma unroll
                 for (int t = 0; t < 2; ++t) {
@@ -552,10 +567,26 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
                             const int slot = m ? kSlotZero + (31 - __clz(m)) : kSlotNegCarry;
                             A b = from_bits<A>(rp[slot]);
                             o[0] = from_bits<A>(xb[0]) - b;
+                            if constexpr (kExactStarts) {
+                                const v4u xr = kKeepRows ? striped[kKeepRows ? j : 0] : raw[S][j];   // my four inputs
+                                bool restarted = ((Fr >> p0) & 1u) != 0;
+                                if (restarted) o[0] = from_bits<A>(xr[0]);
 #pragma unroll
-                            for (int i = 1; i < 4; ++i) {
-                                if ((Fr >> (p0 + i)) & 1u) b = from_bits<A>(xb[i - 1]);
-                                o[i] = from_bits<A>(xb[i]) - b;
+                                for (int i = 1; i < 4; ++i) {
+                                    const A x = from_bits<A>(xr[i]);
+                                    if ((Fr >> (p0 + i)) & 1u) {
+                                        o[i] = x;
+                                        restarted = true;
+                                    } else {
+                                        o[i] = restarted ? o[i - 1] + x : from_bits<A>(xb[i]) - b;
+                                    }
+                                }
+                            } else {
+#pragma unroll
+                                for (int i = 1; i < 4; ++i) {
+                                    if ((Fr >> (p0 + i)) & 1u) b = from_bits<A>(xb[i - 1]);
+                                    o[i] = from_bits<A>(xb[i]) - b;
+                                }
                             }
                         }
                         const uint64_t e0 = cb + 256u * j + 4u * lane;

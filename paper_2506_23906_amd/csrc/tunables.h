@@ -66,6 +66,9 @@ namespace {
 #ifndef MMV_EARLY_F32
 #define MMV_EARLY_F32 0
 #endif
+#ifndef MMV_EXACT_STARTS
+#define MMV_EXACT_STARTS 1   // 1: fp32 scans give a position that starts a segment its input bit for bit
+#endif
 #ifndef MMV_MIN_TILES
 #define MMV_MIN_TILES 512   // workgroups resident at once: 2 per compute unit (LDS)
 #endif

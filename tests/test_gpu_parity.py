@@ -201,6 +201,50 @@ def test_fp32_chunks_with_every_flag_set(variant):
     check_scan(xt.cpu().numpy(), x, f)
 
 
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_fp32_segment_starts_hold_their_input_and_non_finite_values_stay_in_their_row(variant):
+    """Floats are not a group: the method subtracts two speculative prefixes of a row of 32.  What that means next
+    to a huge value and next to an infinity, pinned: (1) every position that starts a segment holds its input bit for
+    bit, also right behind such a value; (2) an infinity makes the rest of its own segment infinite (as in the
+    definition) and may turn later positions of the same row of 32 into NaN (the definition keeps those segments
+    finite: the difference of two infinite prefixes is not a number), but nothing outside that row: its carry stops
+    at the next flag; (3) the error behind a huge value is bounded by the rounding of that row's prefix."""
+    rng = np.random.default_rng(606)
+    n = 3 * 16384 + 1000
+    x = (rng.random(n, dtype=np.float32) * 2 - 1).astype(np.float32)
+    f = (rng.random(n) < 0.1).astype(np.uint8)
+    f[0] = 1
+    huge_at, inf_at = 5 * 32 + 7, 700 * 32 + 11
+    for p in (huge_at, inf_at):
+        f[p - 3:p + 12] = 0
+        f[[p - 3, p + 1, p + 6]] = 1            # the value sits in a segment of four; two segments start right behind it
+        f[(p // 32) * 32 + 32] = 1               # and the next row starts a segment
+    x[huge_at] = np.float32(3.0e30)
+    x[inf_at] = np.float32(np.inf)
+    z = run_segscan(x, f, variant)
+    starts = np.flatnonzero(f)
+    assert np.array_equal(z[starts].view(np.uint32), x[starts].view(np.uint32))                     # (1)
+    with np.errstate(invalid="ignore", over="ignore"):
+        ref = oracle.segscan(x, f)
+    assert np.isinf(z[inf_at:inf_at + 1]).all() and np.isinf(ref[inf_at])                           # (2)
+    row = slice((inf_at // 32) * 32, (inf_at // 32) * 32 + 32)
+    not_finite = np.flatnonzero(~np.isfinite(z))
+    assert len(not_finite) and (not_finite >= row.start).all() and (not_finite < row.stop).all(), not_finite
+    assert np.isfinite(ref[inf_at + 1:row.stop]).all()          # the definition keeps the segments behind it finite
+    print("positions of the infinity's row that are not finite (%s): %s; by the definition only %s" % (
+        variant, (not_finite - row.start).tolist(), (np.flatnonzero(~np.isfinite(ref[row])).tolist())))
+    ok = np.ones(n, dtype=bool)
+    ok[row] = False
+    A = oracle.segscan(np.abs(np.where(np.isfinite(x), x, 0).astype(np.float64)), f)
+    err = np.abs(z.astype(np.float64) - ref)
+    hrow = slice((huge_at // 32) * 32, (huge_at // 32) * 32 + 32)
+    ok[hrow] = False
+    assert (err[ok] <= 1e-4 * np.maximum(A[ok], 1.0)).all()
+    # (3) in the row of the huge value the row prefix reaches 3e30: one rounding of it bounds the error
+    assert (err[hrow] <= 2.0 ** -22 * 3.0e30).all()
+    assert np.array_equal(z[huge_at + 1:huge_at + 2], x[huge_at + 1:huge_at + 2])               # a start right behind it: exact
+
+
 def test_out_capacity_smaller_than_segment_count():
     x, f = W.segscan_i8_uniform_len(50_000, max_len=16, seed=9)
     ref = oracle.segsum(x, f)
