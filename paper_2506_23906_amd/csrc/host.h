@@ -27,8 +27,14 @@ constexpr uint64_t kResident = MMV_MIN_TILES;   // workgroups resident at once (
 #endif
 constexpr uint64_t kCountSumTiles = 2048;        // up to this many tiles the segmented sum needs no prefix kernel
 inline bool is_spmv(mmv_op op) { return op == MMV_OP_SPMV_COO || op == MMV_OP_SPMV_CSR; }
-inline int max_cpw(mmv_op op, mmv_dtype dt) {
+inline int max_cpw(mmv_op op, mmv_dtype dt, bool mfma) {
     if (is_spmv(op)) return TSpmv::kMaxCpw;
+    if (op == MMV_OP_SEGSUM && mfma) {   // the segmented sum that speculates over whole chunks takes longer tiles
+        if (dt == MMV_I8_I32 && chunk_sum_kernel<TI8, kSum, true>()) return sum_cpw<TI8>();
+        if (dt == MMV_U8_XOR && chunk_sum_kernel<TX8, kSum, true>()) return sum_cpw<TX8>();
+        if (dt == MMV_F16_F32 && chunk_sum_kernel<TF16, kSum, true>()) return sum_cpw<TF16>();
+        if (dt == MMV_BF16_F32 && chunk_sum_kernel<TBF16, kSum, true>()) return sum_cpw<TBF16>();
+    }
     switch (dt) {
         case MMV_F32_F32: return TF32::kMaxCpw;
         case MMV_F16_F32: return TF16::kMaxCpw;
@@ -55,10 +61,10 @@ struct TilePlan {
     uint32_t unit;         // elements of one chunk per wave
     uint32_t body_elems;   // elements of a tile in the middle of the vector
 };
-inline TilePlan tile_plan(mmv_op op, mmv_dtype dt, uint64_t n) {
+inline TilePlan tile_plan(mmv_op op, mmv_dtype dt, uint64_t n, bool mfma = true) {
     TilePlan p = {};
     const uint64_t unit = (uint64_t)waves_of(op, dt) * kChunkElems;  // one chunk per wave
-    const int cpw = max_cpw(op, dt);
+    const int cpw = max_cpw(op, dt, mfma);
     p.unit = (uint32_t)unit;
     TileRegions &R = p.reg;
     uint64_t tiles = 0, at = 0;
@@ -80,16 +86,25 @@ inline TilePlan tile_plan(mmv_op op, mmv_dtype dt, uint64_t n) {
         add((uint32_t)c, (n + unit * c - 1) / (unit * c));
     } else {
         p.body_elems = (uint32_t)(unit * cpw);
+        // lengths of the short tiles: a quarter, a half and three quarters of the full length
+        int steps[3], nsteps = 0;
+        for (int q = 1; q <= 3; ++q) {
+            const int c = cpw * q / 4;
+            if (c >= 1 && c < cpw && (nsteps == 0 || steps[nsteps - 1] != c)) steps[nsteps++] = c;
+        }
         uint64_t head = 0, tail = (uint64_t)MMV_TAIL_TILES * unit;   // elements in the short tiles of both ends
-        for (int c = 1; c < cpw; ++c) head += (uint64_t)MMV_HEAD_GROUP * c * unit;
-        for (int c = 2; c < cpw; ++c) tail += (uint64_t)MMV_TAIL_GROUP * c * unit;
-        const bool graded = cpw > 1 && head + tail <= n;
+        for (int i = 0; i < nsteps; ++i) {
+            head += (uint64_t)MMV_HEAD_GROUP * steps[i] * unit;
+            if (steps[i] >= 2) tail += (uint64_t)MMV_TAIL_GROUP * steps[i] * unit;
+        }
+        const bool graded = nsteps > 0 && head + tail <= n;
         if (!graded) head = 0, tail = (uint64_t)MMV_TAIL_TILES * unit < n ? (uint64_t)MMV_TAIL_TILES * unit : n;
         if (graded)
-            for (int c = 1; c < cpw; ++c) add((uint32_t)c, MMV_HEAD_GROUP);
+            for (int i = 0; i < nsteps; ++i) add((uint32_t)steps[i], MMV_HEAD_GROUP);
         add((uint32_t)cpw, (n - head - tail) / (unit * cpw));
         if (graded)
-            for (int c = cpw - 1; c >= 2; --c) add((uint32_t)c, MMV_TAIL_GROUP);
+            for (int i = nsteps - 1; i >= 0; --i)
+                if (steps[i] >= 2) add((uint32_t)steps[i], MMV_TAIL_GROUP);
         if (cpw > 1 || R.count == 0) {
             add(1u, (n - at + unit - 1) / unit);          // what is left, the last tile ragged
         } else {
@@ -100,7 +115,11 @@ inline TilePlan tile_plan(mmv_op op, mmv_dtype dt, uint64_t n) {
     R.num_tiles = (uint32_t)(tiles < 0x7fffffffull ? tiles : 0x7fffffffull);
     return p;
 }
-inline uint64_t tiles_for(uint64_t n, mmv_op op, mmv_dtype dt) { return tile_plan(op, dt, n).tiles; }
+// (for sizing: the variant with the shorter tiles needs more descriptors)
+inline uint64_t tiles_for(uint64_t n, mmv_op op, mmv_dtype dt) {
+    const uint64_t a = tile_plan(op, dt, n, true).tiles, b = tile_plan(op, dt, n, false).tiles;
+    return a > b ? a : b;
+}
 inline bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
 inline bool aligned4(const void *p) { return ((uintptr_t)p & 3u) == 0; }
 
@@ -246,7 +265,7 @@ template <typename TT, int kOp, bool kMfma> hipError_t launch_variant(Params P, 
 
 template <typename TT, int kOp>
 hipError_t launch_seg(Params P, mmv_variant v, hipStream_t s) {
-    const TilePlan plan = tile_plan((mmv_op)kOp, TT::kDtype, P.n);
+    const TilePlan plan = tile_plan((mmv_op)kOp, TT::kDtype, P.n, v == MMV_VARIANT_MFMA);
     if (plan.tiles > 0x7fffffffull) return hipErrorInvalidValue;
     P.num_tiles = (uint32_t)plan.tiles;
     P.reg = plan.reg;

@@ -39,6 +39,8 @@
 #include "lanes.h"
 #include "tile_math.h"
 #include "seg_kernel.h"
+#include "sum_kernel.h"
+#include "seg_entry.h"
 #include "aux_kernels.h"
 #include "primitives.h"
 #include "host.h"
@@ -145,7 +147,7 @@ mmv_status mmv_segsum(const void *d_x, const void *d_flags, uint64_t n, void *d_
     P.out_cap = out_capacity;
     P.nseg = d_nseg;
     // number of segment starts before every tile: per-tile counts, then their exclusive scan
-    const TilePlan plan = tile_plan(MMV_OP_SEGSUM, dt, n);
+    const TilePlan plan = tile_plan(MMV_OP_SEGSUM, dt, n, v == MMV_VARIANT_MFMA);
     const WsLayout L = ws_layout(MMV_OP_SEGSUM, dt, ff, n);
     uint32_t *tile_count = (uint32_t *)((char *)d_ws + L.desc_c);
     if (plan.tiles > 0x7fffffffull) return MMV_ERR_INVALID_ARG;

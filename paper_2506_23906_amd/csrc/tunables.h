@@ -69,6 +69,15 @@ namespace {
 #ifndef MMV_EXACT_STARTS
 #define MMV_EXACT_STARTS 1   // 1: fp32 scans give a position that starts a segment its input bit for bit
 #endif
+#ifndef MMV_CHUNK_SUM
+#define MMV_CHUNK_SUM 1   // 1: the segmented sum of 8- and 16-bit inputs (matrix-core variant) speculates over whole chunks
+#endif
+#ifndef MMV_SUM_CPW_I8
+#define MMV_SUM_CPW_I8 4    // chunks per wave of the chunk-speculating segmented sum, 8-bit inputs
+#endif
+#ifndef MMV_SUM_CPW_F16
+#define MMV_SUM_CPW_F16 2   // ... 16-bit inputs
+#endif
 #ifndef MMV_MIN_TILES
 #define MMV_MIN_TILES 512   // workgroups resident at once: 2 per compute unit (LDS)
 #endif
@@ -78,6 +87,7 @@ constexpr int kRowsPerChunk = 64;               // a chunk = 64 rows, one per la
 constexpr int kChunkElems = kS * kRowsPerChunk; // 2048
 constexpr int kRowStride = 36;                  // dwords per LDS row: 4 meta + 32 values
 constexpr int kSlotF = 0;                       // flag word of the row
+constexpr int kSlotPrefix = 1;                  // (segmented sum) sum of the rows of the chunk before this one
 constexpr int kSlotNegCarry = 2;                // minus the carry into the row
 constexpr int kSlotZero = 3;                    // x-bar(-1) = 0
 constexpr int kRowData = 4;
