@@ -56,7 +56,12 @@ typedef enum {
     MMV_I8_I32 = 3, /* 32-bit two's complement, wraps (Z/2^32 is a group, Sec. 2) */
     MMV_U8_XOR = 4  /* another group (Sec. 2 asks only for a group): bytes under bit-wise exclusive or; the
                        result byte comes in the low bits of a 32-bit word.  mmv_segscan, mmv_segsum and
-                       mmv_scan only; the un-fused compositions and SpMV answer MMV_ERR_UNSUPPORTED. */
+                       mmv_scan only; the un-fused compositions and SpMV answer MMV_ERR_UNSUPPORTED.
+                       The matrix cores only add, so MMV_VARIANT_MFMA takes the running exclusive or as the
+                       parity of bit-plane sums (four products per 32x32 tile and the vector work of making
+                       the planes and gathering the parities): correct, but on this chip slower than
+                       MMV_VARIANT_SHUFFLE (62 % against 73 % of the HBM peak at 2^28 elements); callers that
+                       only want the result should pass MMV_VARIANT_SHUFFLE for this type. */
 } mmv_dtype;
 
 /* Segment-start flags f of Problem 2.1. */

@@ -40,7 +40,7 @@ inline int max_cpw(mmv_op op, mmv_dtype dt, bool mfma) {
         case MMV_F16_F32: return TF16::kMaxCpw;
         case MMV_BF16_F32: return TBF16::kMaxCpw;
         case MMV_I8_I32: return TI8::kMaxCpw;
-        case MMV_U8_XOR: return TX8::kMaxCpw;
+        case MMV_U8_XOR: return mfma ? chunks_per_wave<TX8, true>() : chunks_per_wave<TX8, false>();
     }
     return 1;
 }

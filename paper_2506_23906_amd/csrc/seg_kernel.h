@@ -55,7 +55,7 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
     typedef typename TT::acc_t A;
     typedef typename TT::in_t In;
     constexpr int kWaves = TT::kWaves;
-    constexpr int kCpw = TT::kMaxCpw;            // most chunks a wave takes (register arrays)
+    constexpr int kCpw = chunks_per_wave<TT, kMfma>();   // most chunks a wave takes (register arrays)
     constexpr int K = 16 / TT::kEpl;             // 128-bit words per lane and 32x32 tile
     constexpr bool kScanLike = kOp == kScan || kOp == kPlainScan;   // every element is an output
     // The chunk loops are either rolled, with the per-chunk registers rotated so that the body always

@@ -137,6 +137,7 @@ template <typename A> __device__ __forceinline__ A wave_inclusive_scan(A v) {
 // Chunks per wave of this tile body: a sum keeps little per chunk besides the loaded values, so its tiles can be
 // longer than those of the scan (fewer tickets, and the fixed costs of a tile spread over more elements).
 template <typename TT> constexpr int sum_cpw() { return sizeof(typename TT::in_t) == 1 ? MMV_SUM_CPW_I8 : MMV_SUM_CPW_F16; }
+template <> constexpr int sum_cpw<TX8>() { return MMV_CPW_X8_MFMA; }   // (the bit-plane products of exclusive or need the registers)
 template <typename TT, int kOp, bool kMfma> constexpr bool chunk_sum_kernel() {
     return MMV_CHUNK_SUM != 0 && kOp == kSum && kMfma && sizeof(typename TT::in_t) <= 2;
 }

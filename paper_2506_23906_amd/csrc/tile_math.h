@@ -37,6 +37,11 @@ struct TX8 {
     static constexpr int kWaves = MMV_WAVES;
     static constexpr mmv_dtype kDtype = MMV_U8_XOR;
 };
+// Most chunks a wave of seg_tile takes.  Bytes under exclusive or in the matrix-core variant hold four accumulators
+// of bit-plane sums per tile next to the raw words: two chunks fit the registers, four spill.
+template <typename TT, bool kMfma> constexpr int chunks_per_wave() { return TT::kMaxCpw; }
+template <> constexpr int chunks_per_wave<TX8, true>() { return MMV_CPW_X8_MFMA; }
+
 struct TF16 {
     typedef _Float16 in_t;
     typedef float acc_t;

@@ -21,6 +21,9 @@ namespace {
 #ifndef MMV_CPW_I8
 #define MMV_CPW_I8 4     // most chunks per wave, int8 inputs (6 spills registers)
 #endif
+#ifndef MMV_CPW_X8_MFMA
+#define MMV_CPW_X8_MFMA 2   // ... bytes under exclusive or on the matrix cores (4 spills registers)
+#endif
 #ifndef MMV_CPW_F16
 #define MMV_CPW_F16 2    // most chunks per wave, 16-bit inputs (4 spills registers)
 #endif
