@@ -95,26 +95,29 @@ def time_steps(step, steps: int, warmup: int, events: HipEvents | None):
 
 
 def load_traffic(name: str):
-    """HBM bytes per launch from the committed rocprofv3 --pmc summary of this workload, if any."""
-    path = os.path.join(ROOT, "profiles", name + "_hbm_traffic.txt")
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary of this workload (counters cannot be read
+    from inside this process), and a label that says so; (None, reason) if there is no such summary."""
+    rel = os.path.join("profiles", name + "_hbm_traffic.txt")
+    path = os.path.join(ROOT, rel)
     if os.path.exists(path):
         with open(path) as fh:
             for line in fh:
                 if line.startswith("traffic_bytes_per_launch"):
-                    return int(line.split("=")[1])
-    return None
+                    return int(line.split("=")[1]), ("replayed from %s (two rocprofv3 --pmc runs of this command, FETCH_SIZE "
+                                                     "and WRITE_SIZE scaled by a copy of known size); not measured in this run" % rel)
+    return None, "no counter summary for this workload under profiles/"
 
 
 def oracle_baseline(x, f, repeats: int = 3):
-    """The sequential CPU oracle, as it stands, on the same workload (one thread)."""
+    """The sequential CPU oracle, as it stands, on the same workload (one thread); returns (best seconds, result)."""
     import oracle
-    best = None
+    best, ref = None, None
     for _ in range(repeats):
         t0 = time.perf_counter()
-        oracle.segscan(x, f)
+        ref = oracle.segscan(x, f)
         dt = time.perf_counter() - t0
         best = dt if best is None else min(best, dt)
-    return best
+    return best, ref
 
 
 def main() -> int:
@@ -216,12 +219,23 @@ def main() -> int:
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
-            "traffic": load_traffic("segscan_i8_2p%d_%s" % (args.log2n, args.variant)),
+            "traffic": None,
         },
     }
+    traffic, source = load_traffic("segscan_i8_2p%d_%s" % (args.log2n, args.variant))
+    if args.density is None:
+        line["roofline"]["traffic"] = traffic
+        line["roofline"]["traffic_source"] = source
+    else:
+        line["roofline"]["traffic_source"] = "not measured for this flag density"
     if not args.no_cpu_baseline:
         import oracle
-        secs = oracle_baseline(x, f)
+        secs, ref = oracle_baseline(x, f)
+        # the output of the last timed step against the oracle's (bit-exact: integers)
+        got = zt.cpu().numpy()
+        assert np.array_equal(got, ref), "the timed run's output differs from the oracle's"
+        line["config"]["output_checked_against_oracle"] = True
+        del got, ref
         line["cpu_baseline"] = {
             "value": n / secs / 1e9,
             "unit": "Gelem/s",

@@ -37,6 +37,9 @@
 extern "C" {
 #endif
 
+/* Enum arguments: every enum below ends in an enumerator of value 0x7fffffff that no call accepts.  It gives the
+ * type the full non-negative range of an int, so that a caller who passes a number that is not one of the listed
+ * values gets MMV_ERR_INVALID_ARG (or 0 from the sizing functions) instead of undefined behaviour inside the library. */
 typedef enum {
     MMV_OK = 0,
     MMV_ERR_INVALID_ARG = 1, /* bad enum value, misaligned pointer, size out of range */
@@ -44,7 +47,8 @@ typedef enum {
     MMV_ERR_UNSUPPORTED = 3, /* valid but not implemented combination */
     MMV_ERR_WORKSPACE = 4,   /* workspace too small or misaligned */
     MMV_ERR_HIP = 5,         /* a HIP launch failed */
-    MMV_ERR_TOO_LARGE = 6    /* mmv_segscan_static: the input needs more scratch than the built-in array holds */
+    MMV_ERR_TOO_LARGE = 6,   /* mmv_segscan_static: the input needs more scratch than the built-in array holds */
+    MMV_STATUS_INT_MAX = 0x7fffffff /* (not a status; see "enum arguments" below) */
 } mmv_status;
 
 /* Input element type / accumulator-and-output type (appendix "Implementation of
@@ -62,6 +66,8 @@ typedef enum {
                        the planes and gathering the parities): correct, but on this chip slower than
                        MMV_VARIANT_SHUFFLE (62 % against 73 % of the HBM peak at 2^28 elements); callers that
                        only want the result should pass MMV_VARIANT_SHUFFLE for this type. */
+    ,
+    MMV_DTYPE_INT_MAX = 0x7fffffff
 } mmv_dtype;
 
 /* Segment-start flags f of Problem 2.1. */
@@ -69,13 +75,16 @@ typedef enum {
     MMV_FLAGS_U8 = 0,      /* one byte per element, non-zero = segment start */
     MMV_FLAGS_PACKED32 = 1 /* bit (i mod 32) of 32-bit word floor(i/32), LSB first;
                               ceil(n/32) words, bits beyond n ignored */
+    ,
+    MMV_FLAGS_INT_MAX = 0x7fffffff
 } mmv_flag_fmt;
 
 /* How the speculative s-block scans x-bar = MATMUL(x, U_s) (Sec. 1.1, first line
  * of BlockSegScan in the block-recursive algorithm) are computed. */
 typedef enum {
     MMV_VARIANT_MFMA = 0,   /* matrix cores: tile times triangular ones matrix, s = 32 */
-    MMV_VARIANT_SHUFFLE = 1 /* ablation: same rows scanned with vector adds and lane shuffles */
+    MMV_VARIANT_SHUFFLE = 1, /* ablation: same rows scanned with vector adds and lane shuffles */
+    MMV_VARIANT_INT_MAX = 0x7fffffff
 } mmv_variant;
 
 typedef enum {
@@ -86,11 +95,12 @@ typedef enum {
     MMV_OP_COMPRESS = 4,     /* mmv_compress (dt ignored) */
     MMV_OP_SEGSUM_SCD = 5,   /* mmv_segsum_scd, sized for out_capacity = n */
     MMV_OP_SEGSCAN_SSCR = 6, /* mmv_segscan_sscr */
-    MMV_OP_SPMV_CSR = 7      /* sized by mmv_spmv_csr_workspace_bytes */
+    MMV_OP_SPMV_CSR = 7,     /* sized by mmv_spmv_csr_workspace_bytes */
+    MMV_OP_INT_MAX = 0x7fffffff
 } mmv_op;
 
 /* Element type of the 32-bit vectors that DIFF and REVERT work on. */
-typedef enum { MMV_ELEM_I32 = 0 /* wraps */, MMV_ELEM_F32 = 1 } mmv_elem;
+typedef enum { MMV_ELEM_I32 = 0 /* wraps */, MMV_ELEM_F32 = 1, MMV_ELEM_INT_MAX = 0x7fffffff } mmv_elem;
 
 /* Bytes of scratch needed for one call.  `n` is the vector length (nnz for
  * SpMV).  Pure host function; returns 0 for invalid arguments and for

@@ -32,13 +32,17 @@ import subprocess
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
+# MMVSEG_ORACLE_SANITIZE=1 (tests/test_sanitizers.py): both C files are built with the address and undefined-
+# behaviour sanitizers into libraries of their own; the process must then have gcc's libasan preloaded.
+_SANITIZE = os.environ.get("MMVSEG_ORACLE_SANITIZE") == "1"
+_SAN_FLAGS = ("-fsanitize=address,undefined", "-fno-sanitize-recover=undefined", "-fno-omit-frame-pointer", "-g") if _SANITIZE else ()
 _SRC = os.path.join(_HERE, "mmvseg_oracle.c")
-_LIB = os.path.join(_HERE, "libmmvseg_oracle.so")
+_LIB = os.path.join(_HERE, "libmmvseg_oracle%s.so" % ("_san" if _SANITIZE else ""))
 _lib = None
 
 
 _HOST_SRC = os.path.join(_HERE, "host_threads.c")
-_HOST_LIB = os.path.join(_HERE, "libmmvseg_host_threads.so")
+_HOST_LIB = os.path.join(_HERE, "libmmvseg_host_threads%s.so" % ("_san" if _SANITIZE else ""))
 _host_lib = None
 
 
@@ -46,7 +50,7 @@ def _compile(src: str, lib: str, force: bool, extra=()) -> str:
     if force or not os.path.exists(lib) or os.path.getmtime(lib) < os.path.getmtime(src):
         tmp = lib + ".tmp.%d" % os.getpid()
         subprocess.check_call(["gcc", "-O2", "-std=c11", "-Wall", "-Wextra", "-fPIC", "-shared",
-                               "-fno-fast-math", *extra, "-o", tmp, src])
+                               "-fno-fast-math", *_SAN_FLAGS, *extra, "-o", tmp, src])
         os.replace(tmp, lib)
     return lib
 

@@ -41,6 +41,7 @@ inline int max_cpw(mmv_op op, mmv_dtype dt, bool mfma) {
         case MMV_BF16_F32: return TBF16::kMaxCpw;
         case MMV_I8_I32: return TI8::kMaxCpw;
         case MMV_U8_XOR: return mfma ? chunks_per_wave<TX8, true>() : chunks_per_wave<TX8, false>();
+        default: break;
     }
     return 1;
 }
@@ -52,6 +53,7 @@ inline int waves_of(mmv_op op, mmv_dtype dt) {
         case MMV_BF16_F32: return TBF16::kWaves;
         case MMV_I8_I32: return TI8::kWaves;
         case MMV_U8_XOR: return TX8::kWaves;
+        default: break;
     }
     return 1;
 }
@@ -287,6 +289,7 @@ template <int kOp> hipError_t launch_dt(const Params &P, mmv_dtype dt, mmv_varia
         case MMV_BF16_F32: return launch_seg<TBF16, kOp>(P, v, s);
         case MMV_I8_I32: return launch_seg<TI8, kOp>(P, v, s);
         case MMV_U8_XOR: return launch_seg<TX8, kOp>(P, v, s);
+        default: break;
     }
     return hipErrorInvalidValue;
 }

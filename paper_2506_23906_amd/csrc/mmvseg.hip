@@ -96,6 +96,7 @@ size_t mmv_workspace_bytes(mmv_op op, mmv_dtype dt, mmv_flag_fmt ff, uint64_t n)
         case MMV_OP_SEGSUM_SCD: return scd_layout(dt, ff, n, n).total;
         case MMV_OP_SEGSCAN_SSCR: return sscr_layout(dt, ff, n).total;
         case MMV_OP_SPMV_CSR: return 0;  // two sizes: see mmv_spmv_csr_workspace_bytes
+        default: break;
     }
     return 0;
 }
@@ -457,6 +458,7 @@ const char *mmv_status_string(mmv_status s) {
         case MMV_ERR_WORKSPACE: return "workspace too small or misaligned";
         case MMV_ERR_HIP: return "HIP error";
         case MMV_ERR_TOO_LARGE: return "input too large for the built-in scratch of mmv_segscan_static";
+        default: break;
     }
     return "unknown status";
 }
