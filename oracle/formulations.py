@@ -10,15 +10,19 @@ formulations that share no code with them:
   integers (what Problem 2.1 of Sec. 2 unrolls to).
 * ``matmul_op`` - MATMUL(x, A) of Sec. 1.1 (Notation): x viewed as a
   ceil(n/s) x s row-major matrix, zero padded, times A, flattened.
-* ``scan_alg`` - Algorithm "Scan in MMV-RAM" (Sec. 4).
+* ``scan_alg`` - the recursion behind Algorithm "Scan in MMV-RAM" (Sec. 4): scans of s-blocks as products
+  with U_s, the same scan applied to the block totals, every block shifted by the total before it.
 * ``compress``, ``diff``, ``scd`` - Algorithm SCD (Sec. 4.1): DIFF o COMPRESS o SCAN.
 * ``revert``, ``sscr`` - Algorithm SSCR (Sec. 4.1).
 * ``revspec_lemma`` - the filter-matrix construction of the REVSPEC lemma
   (appendix, block-recursive algorithm).
-* ``revert_spec_simple`` - Algorithm "Revert Speculative Prefix Sums"
-  (appendix), with its per-block shortcuts.
-* ``block_recursive_segscan`` - Algorithm "Block-recursive segmented scan"
-  (appendix): SegScan / Recurse / BlockSegScan / UpdateFirstSegment.
+* ``revert_spec_simple`` - what Algorithm "Revert Speculative Prefix Sums" (appendix) reaches, from its
+  definition: inside a block every position loses the speculative value just before the start of its segment.
+* ``block_recursive_segscan`` - the recursion of Algorithm "Block-recursive segmented scan" (appendix): blocks
+  scanned speculatively and reverted, the (last value, any flag) pairs of the blocks scanned by the same
+  function, the result of the block before added to the positions ahead of a block's first flag.
+These three are written from what the algorithms compute (the lemma, Problem 2.1, the recursion on block
+aggregates), on 2-D block views; they do not follow the printed instruction sequences.
 
 Readings taken where the printed pseudo-code cannot be right as it stands:
 
@@ -31,9 +35,9 @@ Readings taken where the printed pseudo-code cannot be right as it stands:
   while reading z_s(offset); offsets are read from the un-reverted speculative
   scan.
 * UpdateFirstSegment builds its mask from "flag count equals the count at the
-  block start", which also holds for the block's first position itself; adding
-  the filled value there would double it.  The first position of every shifted
-  block is excluded, as matrix B_s of Algorithm Scan does.
+  block start", which read literally also selects the first position of the shifted
+  block, whose value is the carry itself.  Here the carry of the block before goes to
+  the positions of a block ahead of its first flag, nothing else.
 * COMPRESS inside the SCD/SSCR proof masks with the end markers f^- and writes
   to the 1-based position g(i), i.e. output index g(i) - 1.
 """
@@ -73,13 +77,6 @@ def U(s):
     return np.triu(np.ones((s, s), dtype=np.int64))
 
 
-def B(s):
-    """Identity with an all-ones first row (Algorithm Scan)."""
-    m = np.eye(s, dtype=np.int64)
-    m[0, :] = 1
-    return m
-
-
 def D(s):
     """Bidiagonal difference matrix, 1 on the diagonal, -1 above it (Eq. for D_s)."""
     return np.eye(s, dtype=np.int64) - np.eye(s, k=1, dtype=np.int64)
@@ -98,38 +95,17 @@ def matmul_op(x, A):
     return (xp.reshape(-1, s) @ A).reshape(-1)
 
 
-def gathers(x, s):
-    """GATHERS: last element of every s-block."""
-    return _pad(x, s)[s - 1::s].copy()
-
-
-def scatters(z, zs, s):
-    """SCATTERS: write element i of zs to the last position of the i-th s-block of z."""
-    z = z.copy()
-    z[s - 1::s] = zs[:len(z[s - 1::s])]
-    return z
-
-
-def fills(x, s):
-    """FILLS: copy the first element of every s-block over the whole block."""
-    xp = _pad(x, s)
-    return np.repeat(xp[0::s], s)
-
-
 # ---- unsegmented scan --------------------------------------------------------
 
 def scan_alg(x, s):
-    """Algorithm Scan: local block scans, recursive scan of block lasts, B_s carry add."""
+    """Blocked scan: every s-block scanned by the product with U_s, the block totals scanned by the same function,
+    every block shifted by the scanned total of the block before it."""
     n = len(x)
-    z = matmul_op(x, U(s))
-    if n <= s:
-        return z[:n]
-    xs = gathers(z, s)
-    zs = scan_alg(xs, s)
-    z = scatters(z, zs, s)
-    tail = matmul_op(z[s - 1:], B(s))
-    z[s - 1:] = tail[:len(z) - (s - 1)]
-    return z[:n]
+    local = matmul_op(x, U(s)).reshape(-1, s)          # row b = inclusive scan of block b alone
+    if local.shape[0] > 1:
+        upto = scan_alg(local[:, -1], s)               # inclusive scan of the block totals
+        local[1:] += upto[:-1, None]
+    return local.reshape(-1)[:n]
 
 
 # ---- SCD / SSCR ----------------------------------------------------------------
@@ -230,65 +206,35 @@ def revspec(xbar, fbar, s):
 
 
 def revert_spec_simple(x, f, s):
-    """Speculative block scans reverted block by block with the shortcut cases."""
+    """Speculative block scans with the mis-speculation taken back, from the definition of the result: a position
+    whose segment starts inside its block at position p >= 1 loses the speculative value at p - 1; positions
+    ahead of the block's first flag, and segments that start at the block's first position, keep theirs.
+    (Blocks without a flag, or with their only flag in front, therefore stay as they are, and a block whose
+    every position is flagged turns back into its input: the shortcut cases of the appendix algorithm.)"""
     n = len(x)
-    z = matmul_op(x, U(s))
-    fbar = matmul_op((np.asarray(f) != 0).astype(np.int64), U(s))
-    xp = _pad(x, s)
-    for b in range(0, len(z), s):
-        zs, fb = z[b:b + s], fbar[b:b + s]
-        mu = fb[s - 1]
-        if mu == 0 or (mu == 1 and fb[0] == 1):
-            continue                          # speculation already correct
-        if mu == s:
-            zs[:] = xp[b:b + s]               # s segments of one element
-            continue
-        spec = zs.copy()                      # offsets come from the speculative values
-        for idx in range(int(fb[0]) + 1, int(mu) + 1):
-            offset = int((fb < idx).sum()) - 1
-            zs -= (fb == idx).astype(np.int64) * int(spec[offset])
-    return z[:n]
+    spec = matmul_op(x, U(s)).reshape(-1, s)
+    flags = _pad((np.asarray(f) != 0).astype(np.int64), s).reshape(-1, s)
+    pos = np.arange(s)
+    start = np.maximum.accumulate(np.where(flags != 0, pos, -1), axis=1)     # last flagged position at or before each position
+    before = np.where(start >= 1, np.take_along_axis(spec, np.maximum(start - 1, 0), axis=1), 0)
+    return (spec - before).reshape(-1)[:n]
 
 
 # ---- block-recursive segmented scan ------------------------------------------------
 
-def _block_seg_scan(x, f, s):
-    xbar = matmul_op(x, U(s))
-    fbar = matmul_op(f, U(s))
-    return revspec(xbar, fbar, s)
-
-
-def _update_first_segment(z, f, s):
-    n = len(z)
-    fbar = matmul_op(f, U(s))
-    fstart = fills(fbar, s)
-    m = ((fbar - fstart) == 0).astype(np.int64)
-    m &= 1 - _pad(f, s)
-    m[0::s] = 0                                # see module header
-    w = fills(_pad(z, s), s) * m
-    return (_pad(z, s) + w)[:n]
-
-
-def _recurse(z, f, s):
-    if len(z) <= s:
-        return z
-    z, f = _pad(z, s).copy(), _pad(f, s)
-    fbar = matmul_op(f, U(s))
-    fs = (gathers(fbar, s) != 0).astype(np.int64)
-    zs = gathers(z, s)
-    zs = _block_seg_scan(zs, fs, s)
-    zs = _recurse(zs, fs, s)
-    z = scatters(z, zs, s)
-    z[s - 1:] = _update_first_segment(z[s - 1:], f[s - 1:], s)
-    return z
-
-
 def block_recursive_segscan(x, f, s):
-    """SegScan(x, f; s): speculative block scans, REVSPEC, recursion on block lasts."""
+    """Segmented scan by recursion on blocks of s: each block scanned on its own (speculation through U_s, taken back
+    by REVSPEC as the lemma defines it), the blocks' (last value, any flag) pairs scanned by this same function,
+    and the scanned value of the block before added wherever a block continues it (ahead of its first flag)."""
     n = len(x)
     if n == 0:
         return np.zeros(0, dtype=np.int64)
     xp = _pad(x, s)
     fp = _pad((np.asarray(f) != 0).astype(np.int64), s)
-    z = _block_seg_scan(xp, fp, s)
-    return _recurse(z, fp, s)[:n]
+    z = revspec(matmul_op(xp, U(s)), matmul_op(fp, U(s)), s).reshape(-1, s)
+    fb = fp.reshape(-1, s)
+    if z.shape[0] > 1:
+        carried = block_recursive_segscan(z[:, -1], fb.any(axis=1), s)      # segmented scan over the blocks
+        open_ahead = np.cumsum(fb, axis=1) == 0                              # positions with no flag at or before them
+        z[1:] += np.where(open_ahead[1:], carried[:-1, None], 0)
+    return z.reshape(-1)[:n]

@@ -29,7 +29,6 @@ def test_scan_algorithm_is_cumsum(s, n):
 
 def test_scan_alg_matrix_shapes():
     assert F.U(3).tolist() == [[1, 1, 1], [0, 1, 1], [0, 0, 1]]
-    assert F.B(3).tolist() == [[1, 1, 1], [0, 1, 0], [0, 0, 1]]
     assert F.D(3).tolist() == [[1, -1, 0], [0, 1, -1], [0, 0, 1]]
     # MATMUL(x, U_s) prefix-sums every s-block on its own and zero-pads the tail
     assert F.matmul_op([1, 2, 3, 4, 5], F.U(3)).tolist() == [1, 3, 6, 4, 9, 9]
