@@ -20,10 +20,10 @@ constexpr uint64_t kResident = MMV_MIN_TILES;   // workgroups resident at once (
 #define MMV_HEAD_GROUP 128   // tiles per length at the start of a long vector (0: full tiles from the start)
 #endif
 #ifndef MMV_TAIL_GROUP
-#define MMV_TAIL_GROUP 128   // tiles per length (2 chunks per wave and more) at the end of a long vector
+#define MMV_TAIL_GROUP 64    // tiles per length (2 chunks per wave and more) at the end of a long vector
 #endif
 #ifndef MMV_TAIL_TILES
-#define MMV_TAIL_TILES 256   // tiles of one chunk per wave at the very end (the last of them is ragged)
+#define MMV_TAIL_TILES 128   // tiles of one chunk per wave at the very end (the last of them is ragged)
 #endif
 constexpr uint64_t kCountSumTiles = 2048;        // up to this many tiles the segmented sum needs no prefix kernel
 inline bool is_spmv(mmv_op op) { return op == MMV_OP_SPMV_COO || op == MMV_OP_SPMV_CSR; }
