@@ -140,6 +140,12 @@ def main() -> int:
     ap.add_argument("--report", default=None, help="also time every workload and write JSON lines here")
     ap.add_argument("--copy-only", action="store_true",
                     help="run only the streaming copy reference (1 GiB in, 1 GiB out), for counter calibration")
+    ap.add_argument("--segsum-only", type=float, default=None, metavar="DENSITY",
+                    help="run only mmv_segsum on the int8 values with uniformly random flags of this density "
+                         "(--steps calls, --variant), for counter runs; prints the kernel time")
+    ap.add_argument("--lib", default=None,
+                    help="load this build of libmmvseg.so instead of the one in the package (e.g. one made by "
+                         "paper_2506_23906_amd.build.build(extra=['-DMMV_CHUNK_SUM=0'], out=...), to compare tunables)")
     args = ap.parse_args()
     global EVENTS_EVERY
     EVENTS_EVERY = max(1, args.events_every)
@@ -154,7 +160,27 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
+    if args.lib:
+        B.LIB_PATH = os.path.abspath(args.lib)
     B.load()
+    if args.segsum_only is not None:
+        n = 1 << args.log2n
+        x, _ = W.segscan_i8_uniform_len(n)
+        f = W.uniform_density_flags(n, args.segsum_only, 78)
+        xt = torch.from_numpy(x).cuda()
+        ft = torch.from_numpy(W.pack_flags(f).view(np.int32)).cuda()
+        out = torch.empty(int(f.sum()) + 16, dtype=torch.int32, device="cuda")
+        nseg = torch.empty(1, dtype=torch.int64, device="cuda")
+        ws = B.new_workspace(B.MMV_OP_SEGSUM, B.MMV_I8_I32, B.MMV_FLAGS_PACKED32, n)
+        EVENTS_EVERY = 1
+        ms, kernel_ms = time_steps(lambda: B.mmv_segsum(xt, ft, n=n, out=out, nseg=nseg, variant=args.variant, ws=ws),
+                                   args.steps, args.warmup, HipEvents())
+        assert B.mmv_workspace_status(ws) == 0
+        nbytes = n + n // 8 + int(f.sum()) * 4
+        print(json.dumps({"segsum_only": True, "n": n, "density": args.segsum_only, "variant": args.variant,
+                          "segments": int(f.sum()), "kernel_ms": kernel_ms, "ms_per_call": ms, "algo_bytes": nbytes,
+                          "gb_s_kernel": nbytes / kernel_ms / 1e6, "frac_of_peak_kernel": nbytes / kernel_ms / 1e6 / HBM_PEAK_GBS}))
+        return 0
     if args.copy_only:
         src = torch.zeros(1 << 30, dtype=torch.uint8, device="cuda")
         dst = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
