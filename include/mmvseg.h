@@ -7,8 +7,11 @@
  * Conventions shared by every call
  * --------------------------------
  *  - Every pointer whose name starts with d_ is DEVICE memory owned by the
- *    caller.  The library allocates nothing and keeps no state between calls
- *    (apart from the optional timing events of mmv_set_kernel_events).
+ *    caller.  The library allocates nothing, on the device or on the host, and
+ *    what it keeps between calls is fixed in size and holds no result: per kernel
+ *    one word per device (how many of its workgroups the device holds at once,
+ *    asked from the runtime on first use), the device address of the array behind
+ *    mmv_segscan_static, and the per-thread timing events of mmv_set_kernel_events.
  *  - Work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL =
  *    the default stream).  Calls return as soon as the kernels are enqueued;
  *    results are valid once the caller has synchronised that stream.
