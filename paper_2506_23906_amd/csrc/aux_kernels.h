@@ -111,37 +111,53 @@ __device__ __forceinline__ void sample_column_runs(const int32_t *col, uint64_t 
     if (lane == 0 && 2 * runs > pairs) hdr[kHdrColumnRuns] = 1u;
 }
 
-// Segment-start flags of a row-sorted COO matrix, f(e) = [e == 0 or row(e) != row(e-1)],
-// bit-packed.  A lane takes four consecutive entries (one 128-bit load) and the entry before
-// them from the lane below; eight lanes OR their nibbles into one flag word.
+// Segment-start flags of a row-sorted COO matrix, f(e) = [e == 0 or row(e) != row(e-1)], bit-packed; the same
+// launch zero fills the workspace words (header, descriptors) and y.  A wave takes 2048 entries: every lane reads
+// eight times four consecutive indices (all loads in flight at once), compares them with their left neighbours
+// (the lane before it holds the one before its first: a DPP move), and eight lanes OR their nibbles into one
+// flag word (DPP again; no LDS traffic).
 __global__ __launch_bounds__(256) void row_flags_kernel(const int32_t *row, uint64_t nnz, uint32_t *words,
-                                                        const int32_t *col, uint32_t *hdr) {
+                                                        const int32_t *col, uint32_t *ws, uint64_t ws_words, uint32_t *y,
+                                                        uint64_t n_rows) {
     const int lane = threadIdx.x & 63;
-    if (blockIdx.x == 0 && threadIdx.x < 64) sample_column_runs(col, nnz, hdr, lane);
-    const uint64_t wave0 = ((uint64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * 1024;  // four rounds of 256 entries
+    const uint64_t stride = (uint64_t)gridDim.x * 256;
+    for (uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x; i < ws_words; i += stride) ws[i] = 0;
+    for (uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x; i < n_rows; i += stride) y[i] = 0;
+    if (blockIdx.x == 0) {   // (workgroup 0 has zeroed the header words itself)
+        __syncthreads();
+        if (threadIdx.x < 64) sample_column_runs(col, nnz, ws, lane);
+    }
+    const uint64_t wave0 = ((uint64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * 2048;   // eight rounds of 256 entries
+    if (wave0 >= nnz) return;
+    v4i r[8];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < 8; ++j) {
         const uint64_t e0 = wave0 + 256u * j + 4u * lane;
-        v4i r = {0, 0, 0, 0};
+        r[j] = v4i{0, 0, 0, 0};
         if (e0 + 4 <= nnz) {
-            r = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(row + e0));
+            r[j] = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(row + e0));
         } else {
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-                if (e0 + i < nnz) r[i] = row[e0 + i];
+                if (e0 + i < nnz) r[j][i] = row[e0 + i];
         }
-        int prev = __shfl_up(r[3], 1);
-        if (lane == 0) prev = (e0 > 0 && e0 - 1 < nnz) ? row[e0 - 1] : r[0];
-        uint32_t nib = (e0 == 0 || r[0] != prev) ? 1u : 0u;
+    }
+    int before_first = wave0 > 0 ? row[wave0 - 1] : -1;   // (no row index is negative: entry 0 starts a segment)
 #pragma unroll
-        for (int i = 1; i < 4; ++i) nib |= (r[i] != r[i - 1] ? 1u : 0u) << i;
+    for (int j = 0; j < 8; ++j) {
+        const uint64_t e0 = wave0 + 256u * j + 4u * lane;
+        int left = (int)dpp_or_zero<0x138, 0xF>((uint32_t)r[j][3]);   // wave_shr 1: the last index of the lane before
+        if (lane == 0) left = before_first;
+        const uint32_t nib = (r[j][0] != left ? 1u : 0u) | (r[j][1] != r[j][0] ? 2u : 0u) | (r[j][2] != r[j][1] ? 4u : 0u) |
+                             (r[j][3] != r[j][2] ? 8u : 0u);
         const uint32_t valid = e0 >= nnz ? 0u : (nnz - e0 >= 4 ? 0xFu : (1u << (uint32_t)(nnz - e0)) - 1u);
         uint32_t v = (nib & valid) << (4 * (lane & 7));
-        v |= __shfl_xor(v, 1);
-        v |= __shfl_xor(v, 2);
-        v |= __shfl_xor(v, 4);
+        v |= dpp_or_zero<0x111, 0xF>(v);   // row_shr 1, 2, 4: lane 8 k + 7 collects the eight nibbles of its row of 32
+        v |= dpp_or_zero<0x112, 0xF>(v);
+        v |= dpp_or_zero<0x114, 0xF>(v);
         const uint64_t w = ((wave0 + 256u * j) >> 5) + (lane >> 3);
-        if ((lane & 7) == 0 && w * 32 < nnz) words[w] = v;
+        if ((lane & 7) == 7 && w * 32 < nnz) words[w] = v;
+        before_first = __builtin_amdgcn_readlane(r[j][3], 63);
     }
 }
 

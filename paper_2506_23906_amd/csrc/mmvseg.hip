@@ -194,13 +194,14 @@ mmv_status mmv_spmv_coo(uint64_t n_rows, uint64_t n_cols, uint64_t nnz, const in
     P.desc_v = (uint64_t *)(ws + L.desc_v);
     P.num_tiles = (uint32_t)tiles_for(nnz, MMV_OP_SPMV_COO, MMV_F32_F32);
     P.fw = (const uint32_t *)(ws + L.packed);
-    const uint64_t zero_words = L.packed / 4;  // header + descriptors; the flag words are all written below
-    fill_zero_kernel<<<grid_for(zero_words > n_rows ? zero_words : n_rows), 256, 0, s>>>((uint32_t *)ws, zero_words,
-                                                                                      (uint32_t *)d_y, n_rows);
-    if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
-    const uint64_t flag_blocks = (nnz + 4095) / 4096;
+    // one launch ahead of the main kernel: header and descriptors and y zeroed, the flag words made from the row indices
+    const uint64_t zero_words = L.packed / 4;
+    uint64_t flag_blocks = (nnz + 8191) / 8192;
     if (flag_blocks > 0x7fffffffull) return MMV_ERR_INVALID_ARG;
-    row_flags_kernel<<<(unsigned)flag_blocks, 256, 0, s>>>(d_row, nnz, (uint32_t *)(ws + L.packed), d_col, (uint32_t *)ws);
+    const uint64_t fill_blocks = (uint64_t)grid_for(zero_words > n_rows ? zero_words : n_rows);   // (few entries, many rows)
+    if (flag_blocks < fill_blocks) flag_blocks = fill_blocks;
+    row_flags_kernel<<<(unsigned)flag_blocks, 256, 0, s>>>(d_row, nnz, (uint32_t *)(ws + L.packed), d_col, (uint32_t *)ws,
+                                                           zero_words, (uint32_t *)d_y, n_rows);
     if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
     return launch_seg<TSpmv, kSpmv>(P, v, s) == hipSuccess ? MMV_OK : MMV_ERR_HIP;
 }
