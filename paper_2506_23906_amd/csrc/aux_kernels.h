@@ -16,26 +16,34 @@ __global__ __launch_bounds__(256) void fill_zero_kernel(uint32_t *a, uint64_t na
 
 // Segmented sum, step "scan of the end markers" of COMPRESS (proof of the SCD / SSCR theorem)
 // at tile granularity: workgroup b counts the segment starts inside tile b (position 0 is not
-// counted: it opens segment 0 whatever its flag says; bits at or beyond n are not counted).  The
-// same launch zeroes the header and the descriptors of the main kernel.
+// counted: it opens segment 0 whatever its flag says; bits at or beyond n are not counted), and, if asked
+// (span_cnt), inside each of the `unit / 2048` equal spans of the tile that the waves of the main kernel take.
+// The same launch zeroes the header and the descriptors of the main kernel.
 __global__ __launch_bounds__(256) void count_tiles_kernel(uint32_t *zero, uint64_t zero_words, const uint32_t *fw,
-                                                          uint64_t n, TileRegions reg, uint32_t unit, uint32_t *cnt) {
+                                                          uint64_t n, TileRegions reg, uint32_t unit, uint32_t *cnt,
+                                                          uint32_t *span_cnt) {
     __shared__ uint32_t s_part[4];
-    const uint32_t b = blockIdx.x, tid = threadIdx.x;
+    const uint32_t b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     for (uint64_t i = (uint64_t)b * 256 + tid; i < zero_words; i += (uint64_t)gridDim.x * 256) zero[i] = 0;
     const TileSpan span = tile_span(reg, b, unit);
-    const uint64_t base = span.base;
-    const uint64_t elems = (uint64_t)span.cpw * unit;
-    const uint64_t end = base + elems < n ? base + elems : n;
-    uint32_t sum = 0;
-    for (uint64_t w = (base >> 5) + tid; w < ((end + 31) >> 5); w += 256) {   // tiles begin on word borders
-        uint32_t v = fw[w];
-        if (w == 0) v &= ~1u;
-        if ((w + 1) * 32 > n) v &= (1u << (uint32_t)(n - w * 32)) - 1u;
-        sum += __popc(v);
+    const uint32_t spans = unit / kChunkElems;
+    const uint64_t span_words = (uint64_t)span.cpw * (kChunkElems / 32);
+    const uint64_t last_word = (n + 31) >> 5;
+    uint32_t mine = 0;   // the spans are dealt to the four waves in turn
+    for (uint32_t sp = wave; sp < spans; sp += 4) {
+        const uint64_t w0 = (span.base >> 5) + sp * span_words;   // tiles and spans begin on word borders
+        uint32_t sum = 0;
+        for (uint64_t w = w0 + lane; w < w0 + span_words && w < last_word; w += 64) {
+            uint32_t v = fw[w];
+            if (w == 0) v &= ~1u;
+            if ((w + 1) * 32 > n) v &= (1u << (uint32_t)(n - w * 32)) - 1u;
+            sum += __popc(v);
+        }
+        sum = wave_sum(sum);
+        if (span_cnt && lane == 0) span_cnt[(uint64_t)b * spans + sp] = sum;
+        mine += sum;
     }
-    sum = wave_sum(sum);
-    if ((tid & 63) == 0) s_part[tid >> 6] = sum;
+    if (lane == 0) s_part[wave] = mine;
     __syncthreads();
     if (tid == 0) cnt[b] = s_part[0] + s_part[1] + s_part[2] + s_part[3];
 }

@@ -126,7 +126,7 @@ inline bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
 inline bool aligned4(const void *p) { return ((uintptr_t)p & 3u) == 0; }
 
 struct WsLayout {
-    size_t desc_v, desc_c, packed, total;
+    size_t desc_v, desc_c, span_c, packed, total;
 };
 
 WsLayout ws_layout(mmv_op op, mmv_dtype dt, mmv_flag_fmt ff, uint64_t n) {
@@ -135,8 +135,10 @@ WsLayout ws_layout(mmv_op op, mmv_dtype dt, mmv_flag_fmt ff, uint64_t n) {
     size_t off = kHdrBytes;
     L.desc_v = off;
     off += round256(t * 8);
-    L.desc_c = off;
+    L.desc_c = off;   // counts of segment starts: per tile, and (segmented sum) per wave span
     if (op == MMV_OP_SEGSUM || op == MMV_OP_SPMV_CSR) off += round256(t * 8);
+    L.span_c = off;
+    if (op == MMV_OP_SEGSUM) off += round256(t * 4 * (uint64_t)waves_of(op, dt));
     L.packed = off;
     if (is_spmv(op) || (ff == MMV_FLAGS_U8 && op != MMV_OP_SCAN)) off += round256(((n + 63) / 64) * 8);
     L.total = off;
@@ -254,14 +256,19 @@ uint32_t resident_workgroups(const void *kernel, int threads, std::atomic<uint32
 
 template <typename TT, int kOp, bool kMfma> hipError_t launch_variant(Params P, hipStream_t s) {
     static std::atomic<uint32_t> occupancy[kMaxDevices];
-    const uint32_t resident = resident_workgroups((const void *)seg_kernel<TT, kOp, kMfma>, TT::kWaves * 64, occupancy);
+    void (*kernel)(Params, const uint32_t *);
+    if constexpr (chunk_sum_kernel<TT, kOp, kMfma>())
+        kernel = sum_kernel<TT>;
+    else
+        kernel = seg_kernel<TT, kOp, kMfma>;
+    const uint32_t resident = resident_workgroups((const void *)kernel, TT::kWaves * 64, occupancy);
     P.first_round = P.num_tiles < resident ? P.num_tiles : resident;
     // SpMV: the workgroups of the first round start spread over about one tile time.  Started together
     // they stay in step (load, gather, compute all at the same time) and the memory pipe idles half the
     // time; measured 4 to 7 % on the long SpMV kernels, nothing on the scans.
     P.stagger_wgs = resident;
     P.stagger_ticks = ((kOp == kSpmv || kOp == kSpmvCsr) && P.num_tiles > resident) ? MMV_SPMV_STAGGER_US * 100u : 0u;
-    seg_kernel<TT, kOp, kMfma><<<P.num_tiles, TT::kWaves * 64, 0, s>>>(P, P.hdr + kHdrHints);
+    kernel<<<P.num_tiles, TT::kWaves * 64, 0, s>>>(P, P.hdr + kHdrHints);
     return hipGetLastError();
 }
 

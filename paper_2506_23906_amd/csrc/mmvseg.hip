@@ -152,8 +152,9 @@ mmv_status mmv_segsum(const void *d_x, const void *d_flags, uint64_t n, void *d_
     const WsLayout L = ws_layout(MMV_OP_SEGSUM, dt, ff, n);
     uint32_t *tile_count = (uint32_t *)((char *)d_ws + L.desc_c);
     if (plan.tiles > 0x7fffffffull) return MMV_ERR_INVALID_ARG;
+    uint32_t *span_count = (uint32_t *)((char *)d_ws + L.span_c);
     count_tiles_kernel<<<(unsigned)plan.tiles, 256, 0, s>>>((uint32_t *)d_ws, L.desc_c / 4, P.fw, n, plan.reg,
-                                                             plan.unit, tile_count);
+                                                             plan.unit, tile_count, span_count);
     if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
     // few tiles: every tile of the main kernel adds up the counts before it; many: one more small kernel
     // turns the counts into prefix sums first
@@ -163,6 +164,7 @@ mmv_status mmv_segsum(const void *d_x, const void *d_flags, uint64_t n, void *d_
         if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
     }
     P.tile_count = tile_count;
+    P.span_count = span_count;
     return launch_dt<kSum>(P, dt, v, s) == hipSuccess ? MMV_OK : MMV_ERR_HIP;
 }
 

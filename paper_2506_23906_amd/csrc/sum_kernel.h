@@ -134,20 +134,107 @@ template <typename A> __device__ __forceinline__ A wave_inclusive_scan(A v) {
     return v;
 }
 
-// Chunks per wave of this tile body: a sum keeps little per chunk besides the loaded values, so its tiles can be
-// longer than those of the scan (fewer tickets, and the fixed costs of a tile spread over more elements).
+// Inclusive scans over the 64 lanes of a row total and a count of at most 32 per lane, together.  Totals of rows of
+// 32 bytes and their sums over a chunk fit 20 bits, the counts 12, so the 8-bit sums scan both in one word.
+template <typename TT> struct ScanPair {
+    typedef typename TT::acc_t A;
+    static __device__ __forceinline__ void run(A tot, uint32_t cnt, A &inc_t, uint32_t &inc_c) {
+        inc_t = wave_inclusive_scan(tot);
+        inc_c = wave_inclusive_scan(cnt);
+    }
+};
+template <> struct ScanPair<TI8> {
+    static __device__ __forceinline__ void run(uint32_t tot, uint32_t cnt, uint32_t &inc_t, uint32_t &inc_c) {
+        const uint32_t both = wave_inclusive_scan((tot << 12) + cnt);
+        inc_c = both & 0xFFFu;
+        inc_t = (uint32_t)((int32_t)both >> 12);
+    }
+};
+
+// Most chunks per wave of this tile body: a wave holds only the chunks whose loads are in flight, whatever the
+// length of its span, so the tiles can be longer than those of the scan (fewer tickets, and the fixed costs of a
+// tile spread over more elements).
 template <typename TT> constexpr int sum_cpw() { return sizeof(typename TT::in_t) == 1 ? MMV_SUM_CPW_I8 : MMV_SUM_CPW_F16; }
-template <> constexpr int sum_cpw<TX8>() { return MMV_CPW_X8_MFMA; }   // (the bit-plane products of exclusive or need the registers)
 template <typename TT, int kOp, bool kMfma> constexpr bool chunk_sum_kernel() {
     return MMV_CHUNK_SUM != 0 && kOp == kSum && kMfma && sizeof(typename TT::in_t) <= 2;
 }
 
-template <typename TT>
-__device__ __forceinline__ void sum_tile(const Params &P, SegShared<TT::kWaves> &sm, const uint32_t tile) {
+// The LDS rows of one wave: the row scans x-bar of the chunk at hand.  Row scans of 32 bytes fit 16 bits
+// (|x-bar| <= 32 * 128), which halves the rows of the 8-bit inputs; 16-bit inputs keep 32-bit rows in the layout of
+// the scan kernels (they also pass through them on their way into the operand layout).
+template <typename TT, bool kNarrow = sizeof(typename TT::in_t) == 1> struct SumRows;
+template <typename TT> struct SumRows<TT, false> {
     typedef typename TT::acc_t A;
-    typedef typename TT::in_t In;
+    static constexpr int kWords = kRowsPerChunk * kRowStride;
+    static __device__ __forceinline__ void store(uint32_t *rows, int t, int lane, const A (&acc)[16]) { store_spec_rows(rows, t, lane, acc); }
+    static __device__ __forceinline__ A x_bar(const uint32_t *rows, int r, int p) { return from_bits<A>(rows[r * kRowStride + kRowData + p]); }
+};
+template <typename TT> struct SumRows<TT, true> {
+    typedef typename TT::acc_t A;
+    static constexpr int kStride = 18;   // words per row: 16 of values, 2 of padding (64-bit stores of a half-wave hit every bank once)
+    static constexpr int kWords = kRowsPerChunk * kStride;
+    // lane (c, h) holds positions 8 q + 4 h .. + 3 of row 32 t + c in acc[4 q .. 4 q + 3]
+    static __device__ __forceinline__ void store(uint32_t *rows, int t, int lane, const A (&acc)[16]) {
+        const int c = lane & 31, h = lane >> 5;
+        uint32_t *rp = rows + (32 * t + c) * kStride + 2 * h;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            v2u w = {__builtin_amdgcn_perm(to_bits(acc[4 * q + 1]), to_bits(acc[4 * q]), 0x05040100u),
+                     __builtin_amdgcn_perm(to_bits(acc[4 * q + 3]), to_bits(acc[4 * q + 2]), 0x05040100u)};
+            *reinterpret_cast<v2u *>(rp + 4 * q) = w;
+        }
+    }
+    static __device__ __forceinline__ A x_bar(const uint32_t *rows, int r, int p) {
+        return from_bits<A>((uint32_t)(int32_t) reinterpret_cast<const int16_t *>(rows)[r * (2 * kStride) + p]);
+    }
+};
+
+// LDS of one workgroup of the sum kernel.
+template <typename TT> struct SumShared {
+    __attribute__((aligned(16))) uint32_t rows[TT::kWaves][SumRows<TT>::kWords];
+    uint32_t wave_v[TT::kWaves], wave_f[TT::kWaves];
+    // per wave: the one output that needs the sum carried into the wave's span (its value so far, its index in the
+    // output, whether there is one)
+    uint32_t late_v[TT::kWaves], late_k[TT::kWaves], late_on[TT::kWaves];
+    uint32_t tile, carry_v, ready, arrived;
+};
+// Waves per SIMD the compiler is to leave room for: four workgroups of eight waves per compute unit for 8-bit sums
+// (narrow rows: 37 KB of LDS each; measured against three with one more chunk in flight: 4 to 6 % faster), two
+// where the rows are wide (74 KB).
+template <typename TT> constexpr int sum_waves_per_simd() { return MMV_MIN_WAVES_PER_SIMD; }
+template <> constexpr int sum_waves_per_simd<TI8>() { return MMV_SUM_WAVES_PER_SIMD_I8; }
+// Chunks of a wave whose loads are in flight at once (their values wait in registers).
+template <typename TT> constexpr int sum_load_depth() { return sizeof(typename TT::in_t) == 1 ? MMV_SUM_LOAD_DEPTH_I8 : MMV_SUM_LOAD_DEPTH_F16; }
+template <> constexpr int sum_load_depth<TX8>() { return 2; }
+
+// What a wave holds of one chunk while its loads are in flight: the flag word of its row, the flag word of the row
+// after it (whose lowest bit says whether the row's last position ends a segment), and the values.
+template <typename TT> struct SumSlot {
+    uint32_t F, Fnext;
+    v4u raw[2 * (16 / TT::kEpl)];
+};
+template <typename TT>
+__device__ __forceinline__ void sum_load_slot(const Params &P, uint64_t chunk_base, int lane, SumSlot<TT> &slot) {
+    const uint64_t rs = chunk_base + 32u * lane;
+    slot.F = slot.Fnext = 0;
+    if (rs < P.n) slot.F = __builtin_nontemporal_load(P.fw + (rs >> 5));
+    if (rs + 32 < P.n) slot.Fnext = __builtin_nontemporal_load(P.fw + (rs >> 5) + 1);
+    load_raw<TT, true>((const typename TT::in_t *)P.x, chunk_base, P.n, lane, slot.raw);
+}
+
+// One tile.  A wave takes the chunks of its span one after the other, a few of them in flight ahead of the one at
+// hand, and is done with a chunk's values when it moves on: everything a segment end needs lies inside its chunk,
+// except for the first end of a chunk when the segment began before the chunk, and of those only the one with no
+// flag of the wave's span before it needs anything from other waves or tiles (at most one per wave: after that
+// end comes a flag; kept in LDS and written at the end, when the carry is known).  The index of an output is the
+// number of segment starts before its segment; the starts before a wave's span come from the counting kernel.
+// So a tile can be long (few tickets, barriers and look-backs per element) without holding more in registers.
+template <typename TT>
+__device__ __forceinline__ void sum_tile(const Params &P, SumShared<TT> &sm, const uint32_t tile) {
+    typedef SumRows<TT> Rows;
+    typedef typename TT::acc_t A;
     constexpr int kWaves = TT::kWaves;
-    constexpr int kCpw = sum_cpw<TT>();
+    constexpr int kDepth = sum_load_depth<TT>();
     constexpr int K = 16 / TT::kEpl;
     static_assert(K <= 2, "8- and 16-bit inputs");
 
@@ -159,214 +246,195 @@ __device__ __forceinline__ void sum_tile(const Params &P, SegShared<TT::kWaves> 
     const int cpw_t = (int)span.cpw;
     const uint64_t wave_base = span.base + (uint64_t)wave * cpw_t * kChunkElems;
 
-    // ---- all inputs of my span: the flag word of my row per chunk first, then the values; and the flag word that
-    // follows the span (its lowest bit says whether the span's last position ends a segment) ----
-    uint32_t F[kCpw];
-    v4u raw[kCpw][2 * K];
-#pragma unroll
-    for (int c = 0; c < kCpw; ++c) {
-        F[c] = 0;
-        const uint64_t rs = wave_base + (uint64_t)c * kChunkElems + 32u * lane;
-        if (c < cpw_t && rs < n) F[c] = __builtin_nontemporal_load(P.fw + (rs >> 5));
+    // segment starts before my span (position 0 of the vector is not counted): those before my tile (the table holds
+    // them per tile, or, for long vectors, their prefix sums already) and those in the spans of the waves before mine.
+    // Asked for ahead of the values (loads come back in the order they went out), added up when the first end needs them.
+    uint32_t count_part = 0;
+    if (P.count_is_prefix) {
+        if (lane == 0) count_part = P.tile_count[tile];
+    } else {
+        for (uint32_t i = lane; i < tile; i += 64) count_part += P.tile_count[i];
     }
-    uint32_t next_word = 0;
-    const uint64_t span_end = wave_base + (uint64_t)cpw_t * kChunkElems;
-    if (span_end < n) next_word = P.fw[span_end >> 5];
+    if (lane < wave) count_part += P.span_count[(uint64_t)tile * kWaves + lane];
+    __builtin_amdgcn_sched_barrier(0);
+    SumSlot<TT> slot[kDepth];
 #pragma unroll
-    for (int c = 0; c < kCpw; ++c)
-        if (c < cpw_t) load_raw<TT, true>((const In *)P.x, wave_base + (uint64_t)c * kChunkElems, n, lane, raw[c]);
+    for (int i = 0; i < kDepth; ++i)
+        if (i < cpw_t) sum_load_slot<TT>(P, wave_base + (uint64_t)i * kChunkElems, lane, slot[i]);
 #if MMV_LOAD_PRIO
     __builtin_amdgcn_s_setprio(0);
 #endif
-    // bits beyond n do not count
-#pragma unroll
-    for (int c = 0; c < kCpw; ++c) {
-        const uint64_t rs = wave_base + (uint64_t)c * kChunkElems + 32u * lane;
-        if (rs + 32 > n) F[c] = rs < n ? (F[c] & ((1u << (uint32_t)(n - rs)) - 1u)) : 0u;
-    }
-    // number of segment starts before my tile, while the loads are in flight: either the table holds the prefix
-    // sums already, or (few tiles) wave 1 adds up the counts of the tiles before
-    if (wave == 1) {
-        uint32_t c = 0;
-        if (P.count_is_prefix) {
-            c = P.tile_count[tile];
-        } else {
-            for (uint32_t i = lane; i < tile; i += 64) c += P.tile_count[i];
-            c = wave_sum<uint32_t, true>(c);
-        }
-        if (lane == 0) sm.carry_c = c;
-    }
+    if (lane == 0) sm.late_on[wave] = 0;
+    const uint32_t count_carry = wave_sum<uint32_t, true>(count_part);
 
-    // ================= phase A: totals of the rows, their scans over the chunk, the chunk's aggregate =================
-    A ex_t[kCpw];           // per row: sum of the rows of the chunk before mine (speculative: flags ignored)
-    uint32_t ex_c[kCpw];    // per row: segment starts in the rows of the chunk before mine
-    A pre_v[kCpw];          // per chunk (the same in every lane): value carried into the chunk by the chunks of my span before it,
-    uint32_t pre_f[kCpw], pre_c[kCpw];   // whether one of them holds a flag, and their segment starts
-    A run_v = A(0);
-    uint32_t run_f = 0, run_c = 0;
+    // ================= the chunks of my span =================
+    A run_v = A(0);                 // value after the last flag of the chunks so far (their plain sum while run_f == 0)
+    uint32_t run_f = 0, run_c = 0;  // whether they hold a flag; their segment starts
+    bool head_flagged = false;      // the first position of my span starts a segment
+#pragma unroll 1
+    for (int c0 = 0; c0 < cpw_t; c0 += kDepth) {
 #pragma unroll
-    for (int c = 0; c < kCpw; ++c) {
-        ex_t[c] = pre_v[c] = A(0);
-        ex_c[c] = pre_f[c] = pre_c[c] = 0;
-        if (c < cpw_t) {
-            const uint64_t cb = wave_base + (uint64_t)c * kChunkElems;
-            if constexpr (K > 1) to_operand_layout<K>(raw[c], rows, lane);
-            // total of the row I own: the two lanes that hold a row's halves sit 32 lanes apart, so one swap of the
-            // half-waves of the two tiles' partial sums puts both halves of row `lane` into this lane
-            const A part0 = TilePart<TT>::run(raw[c]), part1 = TilePart<TT>::run(raw[c] + K);
-            const auto sw = __builtin_amdgcn_permlane32_swap(to_bits(part0), to_bits(part1), false, false);
-            const A tot = from_bits<A>((uint32_t)sw[0]) + from_bits<A>((uint32_t)sw[1]);
-            const uint32_t cnt = __popc(cb + 32u * lane == 0 ? (F[c] & ~1u) : F[c]);   // position 0 is not counted
-            const A inc_t = wave_inclusive_scan(tot);
-            const uint32_t inc_c = wave_inclusive_scan(cnt);
-            ex_t[c] = inc_t - tot;
-            ex_c[c] = inc_c - cnt;
-            const A chunk_total = read_lane(inc_t, 63);
-            const uint64_t rows_flagged = __ballot(F[c] != 0);
-            A chunk_agg = chunk_total;
-            if (rows_flagged) {
-                // what lies before the chunk's last flag: the rows before its row and the head of that row
-                const int r_star = 63 - __builtin_clzll((unsigned long long)rows_flagged);
-                const uint32_t f_star = (uint32_t)__builtin_amdgcn_readlane((int)F[c], r_star);
-                const int p_star = 31 - __builtin_clz(f_star);
-                A before = read_lane(ex_t[c], r_star);
-                if (p_star > 0) {
-                    const A hp = (r_star >> 5) ? HeadPart<TT>::run(raw[c] + K, p_star, h) : HeadPart<TT>::run(raw[c], p_star, h);
-                    before = (before + read_lane(hp, r_star & 31)) + read_lane(hp, (r_star & 31) + 32);
+        for (int i = 0; i < kDepth; ++i) {
+            const int c = c0 + i;
+            if (c < cpw_t) {
+                const uint64_t cb = wave_base + (uint64_t)c * kChunkElems;
+                const uint64_t row_start = cb + 32u * lane;
+                v4u(&raw)[2 * K] = slot[i].raw;
+                uint32_t F = slot[i].F;
+                if (row_start + 32 > n) F = row_start < n ? (F & ((1u << (uint32_t)(n - row_start)) - 1u)) : 0u;   // bits beyond n do not count
+                if (c == 0) head_flagged = (__builtin_amdgcn_readfirstlane(F) & 1u) != 0;
+                if constexpr (K > 1) to_operand_layout<K>(raw, rows, lane);
+                // total of the row I own: the two lanes that hold a row's halves sit 32 lanes apart, so one swap of the
+                // half-waves of the two tiles' partial sums puts both halves of row `lane` into this lane
+                const A part0 = TilePart<TT>::run(raw), part1 = TilePart<TT>::run(raw + K);
+                const auto sw = __builtin_amdgcn_permlane32_swap(to_bits(part0), to_bits(part1), false, false);
+                const A tot = from_bits<A>((uint32_t)sw[0]) + from_bits<A>((uint32_t)sw[1]);
+                const uint32_t Fc = row_start == 0 ? (F & ~1u) : F;   // position 0 is not counted
+                const uint32_t cnt = __popc(Fc);
+                A inc_t;
+                uint32_t inc_c;
+                ScanPair<TT>::run(tot, cnt, inc_t, inc_c);
+                const A ex_t = inc_t - tot;            // sum of the rows of the chunk before mine (speculative: flags ignored)
+                const uint32_t ex_c = inc_c - cnt;     // segment starts in the rows of the chunk before mine
+                const A chunk_total = read_lane(inc_t, 63);
+                const uint64_t rows_flagged = __ballot(F != 0);
+                A chunk_agg = chunk_total;
+                if (rows_flagged) {
+                    // what lies before the chunk's last flag: the rows before its row and the head of that row
+                    const int r_star = 63 - __builtin_clzll((unsigned long long)rows_flagged);
+                    const uint32_t f_star = (uint32_t)__builtin_amdgcn_readlane((int)F, r_star);
+                    const int p_star = 31 - __builtin_clz(f_star);
+                    A before = read_lane(ex_t, r_star);
+                    if (p_star > 0) {
+                        const A hp = (r_star >> 5) ? HeadPart<TT>::run(raw + K, p_star, h) : HeadPart<TT>::run(raw, p_star, h);
+                        before = (before + read_lane(hp, r_star & 31)) + read_lane(hp, (r_star & 31) + 32);
+                    }
+                    chunk_agg = chunk_total - before;
                 }
-                chunk_agg = chunk_total - before;
+
+                // ---- the segment ends of the chunk.  End mask of my row: bit p set iff position p + 1 starts a
+                // segment or p is the last element ----
+                uint32_t E = (F >> 1) | ((slot[i].Fnext & 1u) << 31);
+                if (row_start < n) {
+                    if (row_start + 32 >= n) {
+                        const uint32_t last = (uint32_t)(n - 1 - row_start);
+                        E = (E & ((1u << last) - 1u)) | (1u << last);
+                    }
+                } else {
+                    E = 0;
+                }
+                const uint64_t rows_with_ends = __ballot(E != 0);
+                if (rows_with_ends) {
+                    // row scans of the 32x32 tiles that hold an end, and of the first one also when an end of the
+                    // second may belong to a segment that starts there
+                    const bool need1 = (rows_with_ends >> 32) != 0;
+                    const bool need0 = (uint32_t)rows_with_ends != 0 || (need1 && (uint32_t)rows_flagged != 0);
+                    if (need0) {
+                        A acc[16];
+                        SpecMfma<TT>::run(raw, lane, acc);
+                        Rows::store(rows, 0, lane, acc);
+                    }
+                    if (need1) {
+                        A acc[16];
+                        SpecMfma<TT>::run(raw + K, lane, acc);
+                        Rows::store(rows, 1, lane, acc);
+                    }
+                    // a segment that ends in my row and has no flag there starts at the last flag of the last flagged
+                    // row r2 before mine (if there is one): what lies between is the rows from r2 on minus the head of r2
+                    const uint64_t rows_before = rows_flagged & ((1ull << lane) - 1ull);
+                    const int r2 = rows_before ? 63 - __builtin_clzll((unsigned long long)rows_before) : lane;
+                    const int st2 = 31 - __builtin_clz(__shfl(F, r2) | 1u);
+                    A across = ex_t - from_bits<A>(__shfl(to_bits(ex_t), r2));
+                    wave_lds_sync();
+                    if (st2 > 0) across -= Rows::x_bar(rows, r2, st2 - 1);
+
+                    const uint32_t count_base = count_carry + run_c + ex_c;
+                    while (E) {
+                        const int e = __builtin_ctz(E);
+                        E &= E - 1u;
+                        const uint32_t m = F & ((2u << e) - 1u);  // flags of my row at or before the end
+                        const uint32_t k = count_base + __popc(Fc & ((2u << e) - 1u));
+                        A v = Rows::x_bar(rows, lane, e);
+                        bool late = false;
+                        if (m) {
+                            const int st = 31 - __builtin_clz(m);
+                            if (st > 0) v -= Rows::x_bar(rows, lane, st - 1);   // x-bar(e) - x-bar(start - 1), both in my row
+                        } else if (rows_before) {
+                            v += across;           // the segment starts in an earlier row of the chunk
+                        } else {
+                            v += run_v + ex_t;     // the segment began before the chunk ...
+                            late = run_f == 0;     // ... and before my span
+                        }
+                        if (late) {
+                            sm.late_v[wave] = to_bits(v);
+                            sm.late_k[wave] = k;
+                            sm.late_on[wave] = 1u;
+                        } else if (k < P.out_cap) {
+                            ((A *)P.out)[k] = v;
+                        }
+                    }
+                    wave_lds_sync();  // the rows are read before the next chunk overwrites them
+                }
+                run_v = rows_flagged ? chunk_agg : run_v + chunk_total;
+                run_f |= rows_flagged ? 1u : 0u;
+                run_c += (uint32_t)__builtin_amdgcn_readlane((int)inc_c, 63);
             }
-            pre_v[c] = run_v;
-            pre_f[c] = run_f;
-            pre_c[c] = run_c;
-            run_v = rows_flagged ? chunk_agg : run_v + chunk_total;
-            run_f |= rows_flagged ? 1u : 0u;
-            run_c += (uint32_t)__builtin_amdgcn_readlane((int)inc_c, 63);
+            // the registers of this chunk take the chunk that many ahead
+            __builtin_amdgcn_sched_barrier(0);
+            if (c + kDepth < cpw_t) sum_load_slot<TT>(P, wave_base + (uint64_t)(c + kDepth) * kChunkElems, lane, slot[i]);
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
-    const bool head_flagged = (__builtin_amdgcn_readfirstlane(F[0]) & 1u) != 0;
     if (lane == 0) {
         sm.wave_v[wave] = to_bits(run_v);
         sm.wave_f[wave] = run_f;
-        sm.wave_c[wave] = run_c;
     }
+    // (short vectors: the number of segments is what the last wave of the last tile has counted)
+    if (!P.count_is_prefix && tile == P.num_tiles - 1 && wave == kWaves - 1 && lane == 0)
+        *P.nseg = (uint64_t)count_carry + run_c + 1u;
     __syncthreads();
 
     // ---- the waves of the tile ----
     A wex_v = A(0), tagg_v = A(0);
-    uint32_t wex_f = 0, wex_c = 0, tagg_f = 0, tagg_c = 0;
+    uint32_t wex_f = 0, tagg_f = 0;
 #pragma unroll
     for (int w = 0; w < kWaves; ++w) {
         if (w == wave) {
             wex_v = tagg_v;
             wex_f = tagg_f;
-            wex_c = tagg_c;
         }
         const A wv = from_bits<A>(sm.wave_v[w]);
         const uint32_t wf = sm.wave_f[w];
         tagg_v = wf ? wv : tagg_v + wv;
         tagg_f |= wf;
-        tagg_c += sm.wave_c[w];
     }
     wex_f = __builtin_amdgcn_readfirstlane(wex_f);
-    if (!P.count_is_prefix && tile == P.num_tiles - 1 && tid == 0) *P.nseg = (uint64_t)sm.carry_c + tagg_c + 1u;
-
     const bool final_now = tile == 0 || tagg_f;  // carry out does not depend on predecessors
     if (tid == 0) desc_store(P.desc_v + tile, final_now ? kStatusPrefix : kStatusAggregate, to_bits(tagg_v));
+
+    // ---- the output that was waiting for the sum carried into my span ----
+    const bool waiting = __builtin_amdgcn_readfirstlane(sm.late_on[wave]) != 0;
     A span_carry = wex_v;
-    const uint32_t count_carry = sm.carry_c;
-
-    // ================= phase B: the segment ends =================
-#pragma unroll 1
-    for (int pass = 0; pass < 2; ++pass) {
-        if (pass == 1) {
-            // carry of the predecessor tiles by decoupled look-back
-            A tile_carry = A(0);
-            if (wave == 0) {
-                if (tile > 0 && !head_flagged) tile_carry = lookback<A, true>(P.desc_v, (int)tile, lane, P.hdr);
-                if (lane == 0) {
-                    if (!final_now) desc_store(P.desc_v + tile, kStatusPrefix, to_bits(tile_carry + tagg_v));
-                    sm.carry_v = to_bits(tile_carry);
-                    __hip_atomic_store(&sm.ready, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
-                }
+    if (!wex_f) {
+        // carry of the predecessor tiles by decoupled look-back
+        A tile_carry = A(0);
+        if (wave == 0) {
+            if (tile > 0 && !head_flagged) tile_carry = lookback<A, true>(P.desc_v, (int)tile, lane, P.hdr);
+            if (lane == 0) {
+                if (!final_now) desc_store(P.desc_v + tile, kStatusPrefix, to_bits(tile_carry + tagg_v));
+                sm.carry_v = to_bits(tile_carry);
+                __hip_atomic_store(&sm.ready, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
             }
-            if (wave != 0 && !wex_f) {
-                while (__hip_atomic_load(&sm.ready, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) == 0)
-                    __builtin_amdgcn_s_sleep(1);
-                tile_carry = from_bits<A>(sm.carry_v);
-            }
-            if (!wex_f) span_carry = tile_carry + wex_v;
+        } else if (waiting) {
+            while (__hip_atomic_load(&sm.ready, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) == 0)
+                __builtin_amdgcn_s_sleep(1);
+            tile_carry = from_bits<A>(sm.carry_v);
         }
-#pragma unroll
-        for (int c = 0; c < kCpw; ++c) {
-            // a chunk is "open" when no flag of the tile precedes it: its first segment needs the carry of the tiles before
-            const bool behind_own_flag = __builtin_amdgcn_readfirstlane(pre_f[c]) != 0;
-            const bool chunk_open = !(wex_f || behind_own_flag);
-            if (c >= cpw_t || chunk_open != (pass == 1)) continue;
-            const uint64_t cb = wave_base + (uint64_t)c * kChunkElems;
-            const uint64_t row_start = cb + 32u * lane;
-            // end mask of my row: bit p set iff position p + 1 starts a segment or p is the last element
-            uint32_t next0 = dpp_or_zero<0x130, 0xF>(F[c]) & 1u;   // wave_shl 1: the word of the next row
-            if (lane == 63)
-                next0 = (c + 1 < kCpw && c + 1 < cpw_t ? (uint32_t)__builtin_amdgcn_readlane((int)F[c + 1 < kCpw ? c + 1 : c], 0) : next_word) & 1u;
-            uint32_t E = (F[c] >> 1) | (next0 << 31);
-            if (row_start < n) {
-                if (row_start + 32 >= n) {
-                    const uint32_t last = (uint32_t)(n - 1 - row_start);
-                    E = (E & ((1u << last) - 1u)) | (1u << last);
-                }
-            } else {
-                E = 0;
-            }
-            const uint64_t rows_with_ends = __ballot(E != 0);
-            if (rows_with_ends == 0) continue;
-            const uint64_t rows_flagged = __ballot(F[c] != 0);
-            // row scans of the 32x32 tiles that hold an end, and of the first one also when an end of the second
-            // may belong to a segment that starts there
-            const bool need1 = (rows_with_ends >> 32) != 0;
-            const bool need0 = (uint32_t)rows_with_ends != 0 || (need1 && (uint32_t)rows_flagged != 0);
-            if (need0) {
-                A acc[16];
-                SpecMfma<TT>::run(raw[c], lane, acc);
-                store_spec_rows(rows, 0, lane, acc);
-            }
-            if (need1) {
-                A acc[16];
-                SpecMfma<TT>::run(raw[c] + K, lane, acc);
-                store_spec_rows(rows, 1, lane, acc);
-            }
-            rows[lane * kRowStride + kSlotF] = F[c];
-            rows[lane * kRowStride + kSlotPrefix] = to_bits(ex_t[c]);
-            wave_lds_sync();
-
-            const A carry_chunk = behind_own_flag ? pre_v[c] : span_carry + pre_v[c];   // into the chunk's first segment
-            const uint64_t count_base = (uint64_t)count_carry + wex_c + pre_c[c] + ex_c[c];
-            const uint32_t Fc = row_start == 0 ? (F[c] & ~1u) : F[c];  // position 0 is not counted
-            const uint64_t rows_before = rows_flagged & ((1ull << lane) - 1ull);   // flagged rows before mine
-            const uint32_t *rp = rows + lane * kRowStride + kRowData;
-            while (E) {
-                const int e = __builtin_ctz(E);
-                E &= E - 1u;
-                const uint32_t m = F[c] & ((2u << e) - 1u);  // flags of my row at or before the end
-                A v = from_bits<A>(rp[e]);
-                if (m) {
-                    const int st = 31 - __builtin_clz(m);
-                    if (st > 0) v -= from_bits<A>(rp[st - 1]);   // x-bar(e) - x-bar(start - 1), both in my row
-                } else if (rows_before) {
-                    // the segment starts in an earlier row r2 of the chunk, at that row's last flag
-                    const int r2 = 63 - __builtin_clzll((unsigned long long)rows_before);
-                    const uint32_t *rq = rows + r2 * kRowStride;
-                    const int st = 31 - __builtin_clz(rq[kSlotF]);
-                    v += ex_t[c] - from_bits<A>(rq[kSlotPrefix]);
-                    if (st > 0) v -= from_bits<A>(rq[kRowData + st - 1]);
-                } else {
-                    v += carry_chunk + ex_t[c];                   // the segment began before the chunk
-                }
-                const uint64_t k = count_base + __popc(Fc & ((2u << e) - 1u));
-                if (k < P.out_cap) ((A *)P.out)[k] = v;
-            }
-            wave_lds_sync();  // the rows are read before the next chunk overwrites them
-        }
+        span_carry = tile_carry + wex_v;
+    }
+    if (waiting && lane == 0) {
+        const uint32_t k = sm.late_k[wave];
+        if (k < P.out_cap) ((A *)P.out)[k] = from_bits<A>(sm.late_v[wave]) + span_carry;
     }
 }
 

@@ -76,10 +76,19 @@ namespace {
 #define MMV_CHUNK_SUM 1   // 1: the segmented sum of 8- and 16-bit inputs (matrix-core variant) speculates over whole chunks
 #endif
 #ifndef MMV_SUM_CPW_I8
-#define MMV_SUM_CPW_I8 4    // chunks per wave of the chunk-speculating segmented sum, 8-bit inputs
+#define MMV_SUM_CPW_I8 8    // most chunks per wave of the chunk-speculating segmented sum, 8-bit inputs
 #endif
 #ifndef MMV_SUM_CPW_F16
-#define MMV_SUM_CPW_F16 2   // ... 16-bit inputs
+#define MMV_SUM_CPW_F16 4   // ... 16-bit inputs
+#endif
+#ifndef MMV_SUM_WAVES_PER_SIMD_I8
+#define MMV_SUM_WAVES_PER_SIMD_I8 8   // register budget of the segmented sum of 8-bit inputs: 512 / 8 = 64 VGPRs per lane (four workgroups per compute unit)
+#endif
+#ifndef MMV_SUM_LOAD_DEPTH_I8
+#define MMV_SUM_LOAD_DEPTH_I8 2   // chunks of a wave of that sum whose loads are in flight at once, 8-bit inputs (3: 73 registers, 4: spills at 80)
+#endif
+#ifndef MMV_SUM_LOAD_DEPTH_F16
+#define MMV_SUM_LOAD_DEPTH_F16 2   // ... 16-bit inputs
 #endif
 #ifndef MMV_MIN_TILES
 #define MMV_MIN_TILES 512   // workgroups resident at once: 2 per compute unit (LDS)
@@ -110,6 +119,7 @@ constexpr uint32_t kMaxSpins = 1u << 20;        // bounded wait, then the status
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+typedef unsigned int v2u __attribute__((ext_vector_type(2)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef float v16f __attribute__((ext_vector_type(16)));
@@ -188,6 +198,7 @@ struct Params {
     uint64_t *desc_v;       // value descriptors, one per tile
     const uint32_t *tile_count;  // sum: segment starts per tile (position 0 not counted), or ...
     uint32_t count_is_prefix;    // ... their exclusive prefix sums already (long vectors)
+    const uint32_t *span_count;  // sum of 8- and 16-bit inputs: segment starts per wave span (kWaves of them per tile)
     uint32_t num_tiles;
     TileRegions reg;        // which elements a tile covers
     uint32_t first_round;   // workgroups [0, first_round) are resident together from the start and take the tile
