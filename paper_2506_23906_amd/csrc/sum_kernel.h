@@ -349,29 +349,31 @@ __device__ __forceinline__ void sum_tile(const Params &P, SumShared<TT> &sm, con
                     if (st2 > 0) across -= Rows::x_bar(rows, r2, st2 - 1);
 
                     const uint32_t count_base = count_carry + run_c + ex_c;
+                    // what an end of my row adds when no flag of the row precedes it: the rows from the last flagged
+                    // row before mine on, or, without such a row, the rows of the chunk before mine and what the
+                    // chunks before carried in
+                    const A open_add = rows_before ? across : run_v + ex_t;
+                    // the one end whose segment began before my span (no flag of the span before it): the first end
+                    // of the chunk, if it is that; put aside for the end of the tile
+                    if (run_f == 0 && rows_before == 0 && E != 0) {
+                        const int e = __builtin_ctz(E);
+                        if ((F & ((2u << e) - 1u)) == 0) {
+                            sm.late_v[wave] = to_bits(Rows::x_bar(rows, lane, e) + open_add);
+                            sm.late_k[wave] = count_base;
+                            sm.late_on[wave] = 1u;
+                            E &= E - 1u;
+                        }
+                    }
                     while (E) {
                         const int e = __builtin_ctz(E);
                         E &= E - 1u;
-                        const uint32_t m = F & ((2u << e) - 1u);  // flags of my row at or before the end
-                        const uint32_t k = count_base + __popc(Fc & ((2u << e) - 1u));
-                        A v = Rows::x_bar(rows, lane, e);
-                        bool late = false;
-                        if (m) {
-                            const int st = 31 - __builtin_clz(m);
-                            if (st > 0) v -= Rows::x_bar(rows, lane, st - 1);   // x-bar(e) - x-bar(start - 1), both in my row
-                        } else if (rows_before) {
-                            v += across;           // the segment starts in an earlier row of the chunk
-                        } else {
-                            v += run_v + ex_t;     // the segment began before the chunk ...
-                            late = run_f == 0;     // ... and before my span
-                        }
-                        if (late) {
-                            sm.late_v[wave] = to_bits(v);
-                            sm.late_k[wave] = k;
-                            sm.late_on[wave] = 1u;
-                        } else if (k < P.out_cap) {
-                            ((A *)P.out)[k] = v;
-                        }
+                        const uint32_t upto = (2u << e) - 1u;
+                        const uint32_t m = F & upto;                 // flags of my row at or before the end
+                        const uint32_t k = count_base + __popc(Fc & upto);
+                        const int st = 31 - __builtin_clz(m | 1u);   // where the segment starts, if in my row (0 also without a flag)
+                        const A head = Rows::x_bar(rows, lane, st > 0 ? st - 1 : 0);
+                        const A v = (Rows::x_bar(rows, lane, e) - (st > 0 ? head : A(0))) + (m ? A(0) : open_add);
+                        if (k < P.out_cap) ((A *)P.out)[k] = v;
                     }
                     wave_lds_sync();  // the rows are read before the next chunk overwrites them
                 }

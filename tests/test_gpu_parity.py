@@ -324,6 +324,21 @@ def test_workload2_f16_geometric(log2n, variant):
         check_scan(run_segscan(x, f, variant), x, f)
 
 
+@pytest.mark.parametrize("density", [2e-5, 1e-3, 0.05])
+@pytest.mark.parametrize("dtype", [np.int8, np.float16])
+def test_sums_longer_than_one_round_of_workgroups(dtype, density):
+    """The segmented sum of 8- and 16-bit inputs has tiles of its own (longer: a wave streams through its span), so its
+    plan of short tiles at both ends and full ones between them begins at longer vectors than that of the scan."""
+    rng = np.random.default_rng(78)
+    full = B.mmv_tile_elems(B.MMV_OP_SEGSUM, B._DTYPES[torch.from_numpy(np.zeros(1, dtype=dtype)).dtype], 1 << 40)
+    for n in (512 * full + 1, 517 * full + 54321):
+        x = random_values(rng, n, dtype)
+        f = W.uniform_density_flags(n, density, seed=n % 1000)
+        print("long sum", dtype.__name__, density, n, flush=True)
+        out, nseg = run_segsum(x, f, "mfma")
+        check_sum(out, nseg, x, f)
+
+
 @pytest.mark.parametrize("variant", VARIANTS)
 @pytest.mark.parametrize("log2n", [22, 28])
 def test_workload3_i8_uniform_len(log2n, variant):
