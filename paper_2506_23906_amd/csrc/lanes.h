@@ -75,14 +75,36 @@ template <typename T, bool kAlu = true> __device__ __forceinline__ T wave_sum(T 
 // (Polling 128 or 256 descriptors per round trip was measured 3-9 % slower on long
 // chains: the polls are served by the memory side and compete with the streams,
 // and in steady state the nearest "prefix" is within 64 tiles anyway.)
-template <typename T, bool kAlu = true>
-__device__ T lookback(const uint64_t *desc, int tile, int lane, uint32_t *hdr) {
+// kPolled windows of 64 descriptors may have been loaded by the caller itself, some time ago (lookback_poll: lane l
+// of window w holds the descriptor of tile  tile - 1 - 64 w - l); they are used as far as they suffice, then the loop
+// polls as usual.
+template <int kWindows>
+__device__ __forceinline__ void lookback_poll(const uint64_t *desc, int tile, int lane, uint64_t (&polled)[kWindows]) {
+#pragma unroll
+    for (int w = 0; w < kWindows; ++w) {
+        const int idx = tile - 1 - 64 * w - lane;
+        polled[w] = idx >= 0 ? desc_load(desc + idx) : (kStatusPrefix << 62);
+    }
+}
+template <typename T, bool kAlu, int kPolled>
+__device__ T lookback_from(const uint64_t *desc, int tile, int lane, uint32_t *hdr, const uint64_t *polled) {
     T carry = T(0);
     int pos = tile - 1;
     uint32_t spins = 0;
+    int window = 0;     // windows done
+    bool fresh = true;  // the polled copy of this window has not been tried
     while (true) {
         const int idx = pos - lane;
-        const uint64_t d = idx >= 0 ? desc_load(desc + idx) : (kStatusPrefix << 62);
+        uint64_t d = 0;
+        bool have = false;
+#pragma unroll
+        for (int w = 0; w < kPolled; ++w)
+            if (fresh && window == w) {
+                d = polled[w];
+                have = true;
+            }
+        if (!have) d = idx >= 0 ? desc_load(desc + idx) : (kStatusPrefix << 62);
+        fresh = false;
         const uint32_t st = (uint32_t)(d >> 62);
         const uint64_t invalid = __ballot(st == kStatusInvalid);
         const uint64_t stop = __ballot(st == kStatusPrefix);
@@ -100,8 +122,14 @@ __device__ T lookback(const uint64_t *desc, int tile, int lane, uint32_t *hdr) {
         carry += wave_sum<T, kAlu>(v);
         if (stop) break;
         pos -= 64;
+        ++window;
+        fresh = true;
     }
     return carry;
+}
+template <typename T, bool kAlu = true>
+__device__ T lookback(const uint64_t *desc, int tile, int lane, uint32_t *hdr) {
+    return lookback_from<T, kAlu, 0>(desc, tile, lane, hdr, nullptr);
 }
 
 }  // namespace

@@ -98,6 +98,9 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
     constexpr int kEarlyMode = !kScanLike ? 0 : (sizeof(In) == 1 ? MMV_EARLY_I8 : (sizeof(In) == 2 ? MMV_EARLY_F16 : MMV_EARLY_F32));
     constexpr bool kEarly = kEarlyMode != 0;
     constexpr bool kEarlyLookback = kEarlyMode == 2;
+    // mode 3: that wave asks for the descriptors of the tiles before at the end of its phase A and looks at them after
+    // the barrier (a round trip to memory takes 3 to 4 us while the chip streams, whatever it asks for)
+    constexpr bool kAsyncLookback = kEarlyMode == 3;
 
     // the wave index as a scalar: everything derived from it (the wave's span, chunk bases, the
     // "whole chunk inside the vector" tests, base addresses of loads and stores) then lives in scalar
@@ -149,6 +152,7 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
             if (rs + 32 > n) F[c] = rs < n ? (F[c] & ((1u << (uint32_t)(n - rs)) - 1u)) : 0u;
         }
     }
+    bool i_published = false;   // (kEarly) my wave has published the sum of a tile without flags
     if constexpr (kEarly) {
         uint32_t any = 0;
 #pragma unroll
@@ -177,6 +181,7 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
                 flagged |= sm.early_f[w];
             }
             if (!flagged) {
+                i_published = true;
                 if (lane == 0) desc_store(P.desc_v + tile, kStatusAggregate, to_bits(total));
                 if constexpr (kEarlyLookback) {
                     // ... and it looks back for the carry of the tiles before right away, so that the tile's own
@@ -431,6 +436,10 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
         sm.wave_f[wave] = run_f;
         sm.wave_c[wave] = run_c;
     }
+    uint64_t polled[MMV_POLL_WINDOWS] = {};
+    if constexpr (kAsyncLookback) {
+        if (i_published) lookback_poll(P.desc_v, (int)tile, lane, polled);
+    }
     __syncthreads();
 
     // ---- step 5b: waves of the tile ----
@@ -476,7 +485,17 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
             // ---- step 5c, second half: carry of the predecessor tiles by decoupled look-back ----
             A tile_carry = A(0);
             // (a tile without flags, other than tile 0, has looked back already where kEarly is set)
-            const bool looked_back = kEarlyLookback && !final_now;
+            const bool looked_back = (kEarlyLookback || kAsyncLookback) && !final_now;
+            if constexpr (kAsyncLookback) {
+                if (i_published) {
+                    tile_carry = lookback_from<A, kAluLanes, MMV_POLL_WINDOWS>(P.desc_v, (int)tile, lane, P.hdr, polled);
+                    if (lane == 0) {
+                        desc_store(P.desc_v + tile, kStatusPrefix, to_bits(tile_carry + tagg_v));
+                        sm.carry_v = to_bits(tile_carry);
+                        __hip_atomic_store(&sm.ready, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    }
+                }
+            }
             if (wave == 0 && !looked_back) {
                 if (tile > 0 && !head_flagged) tile_carry = lookback<A, kAluLanes>(P.desc_v, (int)tile, lane, P.hdr);
                 if (lane == 0) {

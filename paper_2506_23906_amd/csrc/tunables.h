@@ -59,18 +59,24 @@ namespace {
 #endif
 // Scan kernels, tiles without any flag: 0 = the aggregate is published after phase A, as for every other tile;
 // 1 = the plain sum is published as soon as the tile's loads have landed; 2 = and the wave that publishes it looks
-// back for the carry at once.  Per input width (measured best on MI355X).
+// back for the carry at once; 3 = that wave asks for the descriptors of the tiles before when its phase A is done and
+// looks at them after the barrier (a round trip to memory takes 3 to 4 us while the chip streams, whoever has
+// published what; 2 makes the wave late for the barrier).  Per input width (measured best on MI355X; 32-bit inputs:
+// 3 makes the vector without flags 5 % faster and every vector with flags 2 % slower).
 #ifndef MMV_EARLY_I8
-#define MMV_EARLY_I8 2
+#define MMV_EARLY_I8 3
 #endif
 #ifndef MMV_EARLY_F16
-#define MMV_EARLY_F16 1
+#define MMV_EARLY_F16 3
 #endif
 #ifndef MMV_EARLY_F32
 #define MMV_EARLY_F32 0
 #endif
 #ifndef MMV_EXACT_STARTS
 #define MMV_EXACT_STARTS 1   // 1: fp32 scans give a position that starts a segment its input bit for bit
+#endif
+#ifndef MMV_POLL_WINDOWS
+#define MMV_POLL_WINDOWS 1   // windows of 64 tile descriptors that a look-back started ahead of time asks for at once (2 and 4: 3 to 5 % slower, the descriptor loads compete with the streams)
 #endif
 #ifndef MMV_CHUNK_SUM
 #define MMV_CHUNK_SUM 1   // 1: the segmented sum of 8- and 16-bit inputs (matrix-core variant) speculates over whole chunks
