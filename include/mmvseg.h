@@ -291,7 +291,9 @@ const char *mmv_status_string(mmv_status s);
 /* Elements per workgroup tile for an operation, input type and length (tiles are
  * smaller for short inputs so that every compute unit gets one).  For tests that want
  * to straddle tile borders and for sizing: the workspace holds one 8-byte descriptor
- * per tile.  0 for invalid arguments. */
+ * per tile (the segmented sum 40 more bytes of counts per tile).  The value is that
+ * of the matrix-core variant, whose segmented sum of 8- and 16-bit inputs has longer
+ * tiles than the scan.  0 for invalid arguments. */
 uint32_t mmv_tile_elems(mmv_op op, mmv_dtype dt, uint64_t n);
 
 #ifdef __cplusplus
