@@ -31,13 +31,24 @@ __global__ __launch_bounds__(256) void count_tiles_kernel(uint32_t *zero, uint64
     const uint64_t last_word = (n + 31) >> 5;
     uint32_t mine = 0;   // the spans are dealt to the four waves in turn
     for (uint32_t sp = wave; sp < spans; sp += 4) {
-        const uint64_t w0 = (span.base >> 5) + sp * span_words;   // tiles and spans begin on word borders
+        const uint64_t w0 = (span.base >> 5) + sp * span_words;   // tiles and spans begin on word borders, spans are multiples of 64 words
         uint32_t sum = 0;
-        for (uint64_t w = w0 + lane; w < w0 + span_words && w < last_word; w += 64) {
-            uint32_t v = fw[w];
-            if (w == 0) v &= ~1u;
-            if ((w + 1) * 32 > n) v &= (1u << (uint32_t)(n - w * 32)) - 1u;
-            sum += __popc(v);
+        for (uint64_t w = w0 + 4 * lane; w < w0 + span_words && w < last_word; w += 256) {
+            // four words at a time (the workspace behind the caller's words is not ours to read: the last ones singly)
+            uint32_t v[4] = {0, 0, 0, 0};
+            if (w + 4 <= last_word) {
+                const v4u q = *reinterpret_cast<const v4u *>(fw + w);
+                v[0] = q[0], v[1] = q[1], v[2] = q[2], v[3] = q[3];
+            } else {
+                for (int j = 0; j < 4 && w + j < last_word; ++j) v[j] = fw[w + j];
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint64_t wj = w + j;
+                if (wj == 0) v[j] &= ~1u;
+                if ((wj + 1) * 32 > n) v[j] = wj * 32 < n ? (v[j] & ((1u << (uint32_t)(n - wj * 32)) - 1u)) : 0u;
+                sum += __popc(v[j]);
+            }
         }
         sum = wave_sum(sum);
         if (span_cnt && lane == 0) span_cnt[(uint64_t)b * spans + sp] = sum;
