@@ -27,14 +27,9 @@ constexpr uint64_t kResident = MMV_MIN_TILES;   // workgroups resident at once (
 #endif
 constexpr uint64_t kCountSumTiles = 2048;        // up to this many tiles the segmented sum needs no prefix kernel
 inline bool is_spmv(mmv_op op) { return op == MMV_OP_SPMV_COO || op == MMV_OP_SPMV_CSR; }
-inline int max_cpw(mmv_op op, mmv_dtype dt, bool mfma) {
+// Most chunks per wave of the tile body that carries its pair from row to row (seg_tile).
+inline int row_form_cpw(mmv_op op, mmv_dtype dt, bool mfma) {
     if (is_spmv(op)) return TSpmv::kMaxCpw;
-    if (op == MMV_OP_SEGSUM && mfma) {   // the segmented sum that speculates over whole chunks takes longer tiles
-        if (dt == MMV_I8_I32 && chunk_sum_kernel<TI8, kSum, true>()) return sum_cpw<TI8>();
-        if (dt == MMV_U8_XOR && chunk_sum_kernel<TX8, kSum, true>()) return sum_cpw<TX8>();
-        if (dt == MMV_F16_F32 && chunk_sum_kernel<TF16, kSum, true>()) return sum_cpw<TF16>();
-        if (dt == MMV_BF16_F32 && chunk_sum_kernel<TBF16, kSum, true>()) return sum_cpw<TBF16>();
-    }
     switch (dt) {
         case MMV_F32_F32: return TF32::kMaxCpw;
         case MMV_F16_F32: return TF16::kMaxCpw;
@@ -44,6 +39,16 @@ inline int max_cpw(mmv_op op, mmv_dtype dt, bool mfma) {
         default: break;
     }
     return 1;
+}
+// Most chunks per wave of the segmented sum that speculates over whole chunks and streams through its spans
+// (sum_tile; 0: this operation, type or variant has no such form).
+inline int chunk_form_cpw(mmv_op op, mmv_dtype dt, bool mfma) {
+    if (op != MMV_OP_SEGSUM || !mfma) return 0;
+    if (dt == MMV_I8_I32 && chunk_sum_kernel<TI8, kSum, true>()) return sum_cpw<TI8>();
+    if (dt == MMV_U8_XOR && chunk_sum_kernel<TX8, kSum, true>()) return sum_cpw<TX8>();
+    if (dt == MMV_F16_F32 && chunk_sum_kernel<TF16, kSum, true>()) return sum_cpw<TF16>();
+    if (dt == MMV_BF16_F32 && chunk_sum_kernel<TBF16, kSum, true>()) return sum_cpw<TBF16>();
+    return 0;
 }
 inline int waves_of(mmv_op op, mmv_dtype dt) {
     if (is_spmv(op)) return TSpmv::kWaves;
@@ -62,11 +67,18 @@ struct TilePlan {
     uint64_t tiles;        // all tiles (reg.num_tiles holds it when it fits 31 bits)
     uint32_t unit;         // elements of one chunk per wave
     uint32_t body_elems;   // elements of a tile in the middle of the vector
+    bool chunk_form;       // segmented sum: the kernel that streams through long spans (sum_kernel) takes it
 };
 inline TilePlan tile_plan(mmv_op op, mmv_dtype dt, uint64_t n, bool mfma = true) {
     TilePlan p = {};
     const uint64_t unit = (uint64_t)waves_of(op, dt) * kChunkElems;  // one chunk per wave
-    const int cpw = max_cpw(op, dt, mfma);
+    // A sum that fits one round of workgroups is bound by the life of one tile, and the tile that holds all its
+    // values, publishes its aggregate and then walks its ends has the shorter life (workload 2, fp16 2^24: 12.4
+    // against 15.5 us); longer vectors go to the kernel that streams.
+    int cpw = row_form_cpw(op, dt, mfma);
+    const int chunk_cpw = chunk_form_cpw(op, dt, mfma);
+    p.chunk_form = chunk_cpw > 0 && (MMV_SHORT_SUMS_ROW_FORM == 0 || n > MMV_SHORT_SUMS_ROW_FORM * kResident * unit * (uint64_t)cpw);
+    if (p.chunk_form) cpw = chunk_cpw;
     p.unit = (uint32_t)unit;
     TileRegions &R = p.reg;
     uint64_t tiles = 0, at = 0;
@@ -254,14 +266,13 @@ uint32_t resident_workgroups(const void *kernel, int threads, std::atomic<uint32
     return value;
 }
 
-template <typename TT, int kOp, bool kMfma> hipError_t launch_variant(Params P, hipStream_t s) {
-    static std::atomic<uint32_t> occupancy[kMaxDevices];
-    void (*kernel)(Params, const uint32_t *);
-    if constexpr (chunk_sum_kernel<TT, kOp, kMfma>())
-        kernel = sum_kernel<TT>;
-    else
-        kernel = seg_kernel<TT, kOp, kMfma>;
-    const uint32_t resident = resident_workgroups((const void *)kernel, TT::kWaves * 64, occupancy);
+template <typename TT, int kOp, bool kMfma> hipError_t launch_variant(Params P, bool chunk_form, hipStream_t s) {
+    static std::atomic<uint32_t> occupancy[2][kMaxDevices];
+    void (*kernel)(Params, const uint32_t *) = seg_kernel<TT, kOp, kMfma>;
+    if constexpr (chunk_sum_kernel<TT, kOp, kMfma>()) {
+        if (chunk_form) kernel = sum_kernel<TT>;
+    }
+    const uint32_t resident = resident_workgroups((const void *)kernel, TT::kWaves * 64, occupancy[chunk_form ? 1 : 0]);
     P.first_round = P.num_tiles < resident ? P.num_tiles : resident;
     // SpMV: the workgroups of the first round start spread over about one tile time.  Started together
     // they stay in step (load, gather, compute all at the same time) and the memory pipe idles half the
@@ -280,9 +291,9 @@ hipError_t launch_seg(Params P, mmv_variant v, hipStream_t s) {
     P.reg = plan.reg;
     if (tl_ev_start && hipEventRecord(tl_ev_start, s) != hipSuccess) return hipErrorUnknown;
     if (v == MMV_VARIANT_MFMA) {
-        if (launch_variant<TT, kOp, true>(P, s) != hipSuccess) return hipErrorUnknown;
+        if (launch_variant<TT, kOp, true>(P, plan.chunk_form, s) != hipSuccess) return hipErrorUnknown;
     } else {
-        if (launch_variant<TT, kOp, false>(P, s) != hipSuccess) return hipErrorUnknown;
+        if (launch_variant<TT, kOp, false>(P, plan.chunk_form, s) != hipSuccess) return hipErrorUnknown;
     }
     const hipError_t e = hipGetLastError();
     if (tl_ev_stop && hipEventRecord(tl_ev_stop, s) != hipSuccess) return hipErrorUnknown;

@@ -32,7 +32,6 @@ template <typename Shared> __device__ __forceinline__ uint32_t take_tile(const P
 
 template <typename TT, int kOp, bool kMfma>
 __global__ __launch_bounds__(TT::kWaves * 64, MMV_MIN_WAVES_PER_SIMD) void seg_kernel(Params P, const uint32_t *__restrict__ hints) {
-    static_assert(!chunk_sum_kernel<TT, kOp, kMfma>(), "that sum has a kernel of its own");
     __shared__ SegShared<TT::kWaves> sm;
     constexpr bool kProduct = kOp == kSpmv || kOp == kSpmvCsr;
     // A workgroup that starts competes with the ones in the middle of their arithmetic: its ticket

@@ -81,6 +81,9 @@ namespace {
 #ifndef MMV_CHUNK_SUM
 #define MMV_CHUNK_SUM 1   // 1: the segmented sum of 8- and 16-bit inputs (matrix-core variant) speculates over whole chunks
 #endif
+#ifndef MMV_SHORT_SUMS_ROW_FORM
+#define MMV_SHORT_SUMS_ROW_FORM 1   // 1: sums that fit one round of workgroups use the scan's tile body (see tile_plan)
+#endif
 #ifndef MMV_SUM_CPW_I8
 #define MMV_SUM_CPW_I8 8    // most chunks per wave of the chunk-speculating segmented sum, 8-bit inputs
 #endif
