@@ -140,6 +140,9 @@ def main() -> int:
     ap.add_argument("--report", default=None, help="also time every workload and write JSON lines here")
     ap.add_argument("--copy-only", action="store_true",
                     help="run only the streaming copy reference (1 GiB in, 1 GiB out), for counter calibration")
+    ap.add_argument("--copy-mix", default="1024:1024", metavar="IN:OUT",
+                    help="with --copy-only: MiB read and MiB written per launch (256:1024 = the scan's 1:4 mix, "
+                         "1024:0 = read only, 0:1024 = write only)")
     ap.add_argument("--segsum-only", type=float, default=None, metavar="DENSITY",
                     help="run only mmv_segsum on the int8 values with uniformly random flags of this density "
                          "(--steps calls, --variant), for counter runs; prints the kernel time")
@@ -182,12 +185,19 @@ def main() -> int:
                           "gb_s_kernel": nbytes / kernel_ms / 1e6, "frac_of_peak_kernel": nbytes / kernel_ms / 1e6 / HBM_PEAK_GBS}))
         return 0
     if args.copy_only:
-        src = torch.zeros(1 << 30, dtype=torch.uint8, device="cuda")
-        dst = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        in_bytes, out_bytes = (int(v) << 20 for v in args.copy_mix.split(":"))
+        src = torch.zeros(max(in_bytes, 16), dtype=torch.uint8, device="cuda")
+        dst = torch.empty(max(out_bytes, 16), dtype=torch.uint8, device="cuda")
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        B.mmv_stream_copy(src, dst, in_bytes, out_bytes)
+        a.record()
         for _ in range(args.steps):
-            B.mmv_stream_copy(src, dst)
+            B.mmv_stream_copy(src, dst, in_bytes, out_bytes)
+        b.record()
         torch.cuda.synchronize()
-        print(json.dumps({"copy_only": True, "in_bytes": 1 << 30, "out_bytes": 1 << 30, "launches": args.steps}))
+        ms = a.elapsed_time(b) / args.steps
+        print(json.dumps({"copy_only": True, "in_bytes": in_bytes, "out_bytes": out_bytes, "launches": args.steps + 1,
+                          "ms_per_launch": ms, "gb_s": (in_bytes + out_bytes) / ms / 1e6}))
         return 0
     events = HipEvents()
 

@@ -99,7 +99,7 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
     constexpr bool kEarly = kEarlyMode != 0;
     constexpr bool kEarlyLookback = kEarlyMode == 2;
     // mode 3: that wave asks for the descriptors of the tiles before at the end of its phase A and looks at them after
-    // the barrier (a round trip to memory takes 3 to 4 us while the chip streams, whatever it asks for)
+    // the barrier (the look-back takes 3 to 4 us whatever has been published: the poll is under way meanwhile)
     constexpr bool kAsyncLookback = kEarlyMode == 3;
 
     // the wave index as a scalar: everything derived from it (the wave's span, chunk bases, the

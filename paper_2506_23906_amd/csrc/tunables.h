@@ -60,8 +60,8 @@ namespace {
 // Scan kernels, tiles without any flag: 0 = the aggregate is published after phase A, as for every other tile;
 // 1 = the plain sum is published as soon as the tile's loads have landed; 2 = and the wave that publishes it looks
 // back for the carry at once; 3 = that wave asks for the descriptors of the tiles before when its phase A is done and
-// looks at them after the barrier (a round trip to memory takes 3 to 4 us while the chip streams, whoever has
-// published what; 2 makes the wave late for the barrier).  Per input width (measured best on MI355X; 32-bit inputs:
+// looks at them after the barrier (the look-back takes 3 to 4 us whoever has published what, so it pays to have the
+// poll under way early; 2 makes the wave late for the barrier).  Per input width (measured best on MI355X; 32-bit inputs:
 // 3 makes the vector without flags 5 % faster and every vector with flags 2 % slower).
 #ifndef MMV_EARLY_I8
 #define MMV_EARLY_I8 3
