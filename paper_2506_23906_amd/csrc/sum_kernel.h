@@ -65,29 +65,25 @@ template <> struct TilePart<TBF16> : TilePartHalf<true> {};
 // Sum of the elements a lane holds of one 32x32 tile that lie at positions below p of their row (p is the same
 // for all lanes, so the masks of both half-waves are made on the scalar unit and a lane picks its own).
 template <typename TT> struct HeadPart;
-__device__ __forceinline__ uint32_t low_bytes(int count, uint32_t ones) {   // `ones` in the first `count` of 4 bytes
-    const int nb = count < 0 ? 0 : (count > 4 ? 4 : count);
-    return nb == 4 ? ones : (ones & ((1u << (8 * nb)) - 1u));
-}
+// (bytes: bit i of `below` says whether position i lies below p; the four bits of a word's positions are spread to
+// the low bits of its four bytes by one multiplication -- the copies of the four bits, 7 places apart, do not overlap)
+__device__ __forceinline__ uint32_t byte_mask_of_bits(uint32_t bits4) { return (bits4 * 0x00204081u) & 0x01010101u; }
 template <> struct HeadPart<TI8> {
     static __device__ __forceinline__ uint32_t run(const v4u *raw, int p, int h) {
+        const uint32_t mine = ((1u << p) - 1u) >> (16 * h);   // half h holds positions 16 h + 4 d .. + 3 in word d; p < 32
         int s = 0;
 #pragma unroll
-        for (int d = 0; d < 4; ++d) {   // half h holds positions 16 h + 4 d .. + 3 in word d
-            const uint32_t m0 = low_bytes(p - 4 * d, 0x01010101u), m1 = low_bytes(p - 16 - 4 * d, 0x01010101u);
-            s = __builtin_amdgcn_sdot4((int)raw[0][d], (int)(h ? m1 : m0), s, false);
-        }
+        for (int d = 0; d < 4; ++d)
+            s = __builtin_amdgcn_sdot4((int)raw[0][d], (int)byte_mask_of_bits((mine >> (4 * d)) & 0xFu), s, false);
         return (uint32_t)s;
     }
 };
 template <> struct HeadPart<TX8> {
     static __device__ __forceinline__ XorWord run(const v4u *raw, int p, int h) {
+        const uint32_t mine = ((1u << p) - 1u) >> (16 * h);
         uint32_t x = 0;
 #pragma unroll
-        for (int d = 0; d < 4; ++d) {
-            const uint32_t m0 = low_bytes(p - 4 * d, 0xFFFFFFFFu), m1 = low_bytes(p - 16 - 4 * d, 0xFFFFFFFFu);
-            x ^= raw[0][d] & (h ? m1 : m0);
-        }
+        for (int d = 0; d < 4; ++d) x ^= raw[0][d] & (byte_mask_of_bits((mine >> (4 * d)) & 0xFu) * 0xFFu);
         x ^= x >> 16;
         x ^= x >> 8;
         return XorWord(x & 0xFFu);
@@ -98,15 +94,16 @@ template <bool kBf16> struct HeadPartHalf {
         typedef _Float16 v2h __attribute__((ext_vector_type(2)));
         typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
         constexpr uint32_t kOne = kBf16 ? 0x3F80u : 0x3C00u;
+        // word ks of half h holds positions 16 ks + 8 h + 2 d and + 1 in dword d; the two bits that say whether they lie
+        // below p become a 1.0 in the low and in the high half of the mask word
+        const uint32_t mine = ((1u << p) - 1u) >> (8 * h);   // p < 32
         float s = 0.0f;
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-            for (int d = 0; d < 4; ++d) {   // word ks of half h holds positions 16 ks + 8 h + 2 d and + 1 in dword d
-                const int q0 = 16 * ks + 2 * d, q1 = q0 + 8;
-                const uint32_t m0 = (q0 < p ? kOne : 0u) | (q0 + 1 < p ? kOne << 16 : 0u);
-                const uint32_t m1 = (q1 < p ? kOne : 0u) | (q1 + 1 < p ? kOne << 16 : 0u);
-                const uint32_t mask = h ? m1 : m0;
+            for (int d = 0; d < 4; ++d) {
+                const uint32_t two = (mine >> (16 * ks + 2 * d)) & 3u;
+                const uint32_t mask = ((two * 0x8001u) & 0x10001u) * kOne;
                 const uint32_t pair = raw[ks][d];
                 if (kBf16)
                     s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(v2bf, pair), __builtin_bit_cast(v2bf, mask), s, false);
