@@ -324,19 +324,42 @@ def test_workload2_f16_geometric(log2n, variant):
         check_scan(run_segscan(x, f, variant), x, f)
 
 
-@pytest.mark.parametrize("density", [2e-5, 1e-3, 0.05])
+@pytest.mark.parametrize("density", [0.0, 1e-7, 2e-5, 1e-3, 0.05])
 @pytest.mark.parametrize("dtype", [np.int8, np.float16])
 def test_sums_longer_than_one_round_of_workgroups(dtype, density):
-    """The segmented sum of 8- and 16-bit inputs has tiles of its own (longer: a wave streams through its span), so its
-    plan of short tiles at both ends and full ones between them begins at longer vectors than that of the scan."""
+    """The segmented sum of 8- and 16-bit inputs has a kernel and tiles of its own on vectors longer than one round of
+    workgroups (longer tiles: a wave streams through its span), with short tiles at both ends and full ones between
+    them.  Densities from no flag at all (one segment: every tile hands on a plain sum, the one output waits for the
+    carry of all tiles) over a handful of flags (most tiles without one) to a flag in every row."""
     rng = np.random.default_rng(78)
     full = B.mmv_tile_elems(B.MMV_OP_SEGSUM, B._DTYPES[torch.from_numpy(np.zeros(1, dtype=dtype)).dtype], 1 << 40)
     for n in (512 * full + 1, 517 * full + 54321):
         x = random_values(rng, n, dtype)
         f = W.uniform_density_flags(n, density, seed=n % 1000)
-        print("long sum", dtype.__name__, density, n, flush=True)
+        print("long sum", dtype.__name__, density, n, int(f.sum()), flush=True)
         out, nseg = run_segsum(x, f, "mfma")
         check_sum(out, nseg, x, f)
+
+
+def test_long_sum_with_an_output_array_that_is_too_short():
+    """The streaming sum kernel writes its outputs as it goes, and the one per wave that waits for a carry at the end of
+    the tile: none of them may land beyond the capacity the caller gave, and the count is the true one."""
+    rng = np.random.default_rng(79)
+    n = 520 * B.mmv_tile_elems(B.MMV_OP_SEGSUM, B.MMV_I8_I32, 1 << 40) + 77
+    x = random_values(rng, n, np.int8)
+    f = W.uniform_density_flags(n, 1e-4, seed=5)
+    want = oracle.segsum(x, f)
+    cap, guard = len(want) // 2, 4096
+    whole = torch.full((cap + guard,), -77, dtype=torch.int32, device="cuda")
+    nseg = torch.full((1,), -1, dtype=torch.int64, device="cuda")
+    ws = B.new_workspace(B.MMV_OP_SEGSUM, B.MMV_I8_I32, B.MMV_FLAGS_PACKED32, n)
+    B.mmv_segsum(dev(x), packed_dev(f), n=n, out=whole[:cap], nseg=nseg, variant="mfma", ws=ws)
+    torch.cuda.synchronize()
+    assert B.mmv_workspace_status(ws) == 0
+    got = whole.cpu().numpy()
+    assert int(nseg.item()) == len(want)
+    assert np.array_equal(got[:cap], want[:cap])
+    assert np.all(got[cap:] == -77), "an output beyond the capacity was written"
 
 
 @pytest.mark.parametrize("variant", VARIANTS)
