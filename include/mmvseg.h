@@ -293,7 +293,8 @@ const char *mmv_status_string(mmv_status s);
  * to straddle tile borders and for sizing: the workspace holds one 8-byte descriptor
  * per tile (the segmented sum 40 more bytes of counts per tile).  The value is that
  * of the matrix-core variant, whose segmented sum of 8- and 16-bit inputs has longer
- * tiles than the scan.  0 for invalid arguments. */
+ * tiles than the scan; mmv_scan of 16-bit inputs has longer tiles than mmv_segscan.
+ * 0 for invalid arguments. */
 uint32_t mmv_tile_elems(mmv_op op, mmv_dtype dt, uint64_t n);
 
 #ifdef __cplusplus

@@ -30,12 +30,15 @@ inline bool is_spmv(mmv_op op) { return op == MMV_OP_SPMV_COO || op == MMV_OP_SP
 // Most chunks per wave of the tile body that carries its pair from row to row (seg_tile).
 inline int row_form_cpw(mmv_op op, mmv_dtype dt, bool mfma) {
     if (is_spmv(op)) return TSpmv::kMaxCpw;
+    const bool plain = op == MMV_OP_SCAN;
     switch (dt) {
-        case MMV_F32_F32: return TF32::kMaxCpw;
-        case MMV_F16_F32: return TF16::kMaxCpw;
-        case MMV_BF16_F32: return TBF16::kMaxCpw;
-        case MMV_I8_I32: return TI8::kMaxCpw;
-        case MMV_U8_XOR: return mfma ? chunks_per_wave<TX8, true>() : chunks_per_wave<TX8, false>();
+        case MMV_F32_F32: return plain ? chunks_per_wave<TF32, kPlainScan, true>() : TF32::kMaxCpw;
+        case MMV_F16_F32: return plain ? chunks_per_wave<TF16, kPlainScan, true>() : TF16::kMaxCpw;
+        case MMV_BF16_F32: return plain ? chunks_per_wave<TBF16, kPlainScan, true>() : TBF16::kMaxCpw;
+        case MMV_I8_I32: return plain ? chunks_per_wave<TI8, kPlainScan, true>() : TI8::kMaxCpw;
+        case MMV_U8_XOR:
+            if (plain) return mfma ? chunks_per_wave<TX8, kPlainScan, true>() : chunks_per_wave<TX8, kPlainScan, false>();
+            return mfma ? chunks_per_wave<TX8, kScan, true>() : chunks_per_wave<TX8, kScan, false>();
         default: break;
     }
     return 1;

@@ -37,10 +37,6 @@ struct TX8 {
     static constexpr int kWaves = MMV_WAVES;
     static constexpr mmv_dtype kDtype = MMV_U8_XOR;
 };
-// Most chunks a wave of seg_tile takes.  Bytes under exclusive or in the matrix-core variant hold four accumulators
-// of bit-plane sums per tile next to the raw words: two chunks fit the registers, four spill.
-template <typename TT, bool kMfma> constexpr int chunks_per_wave() { return TT::kMaxCpw; }
-template <> constexpr int chunks_per_wave<TX8, true>() { return MMV_CPW_X8_MFMA; }
 
 struct TF16 {
     typedef _Float16 in_t;
@@ -73,6 +69,16 @@ struct TSpmv : TF32 {  // COO SpMV: values and column indices both sit in regist
     static constexpr int kMaxCpw = MMV_CPW_SPMV;
     static constexpr int kWaves = MMV_WAVES_SPMV;
 };
+// Most chunks a wave of seg_tile takes.  Bytes under exclusive or in the matrix-core variant hold four accumulators
+// of bit-plane sums per tile next to the raw words: two chunks fit the registers, four spill.  The scan without a
+// flag vector keeps no flag words and no carried flags, which leaves room for longer tiles of 16- and 32-bit inputs.
+template <typename TT, int kOp, bool kMfma> constexpr int chunks_per_wave() {
+    if (TT::kDtype == MMV_U8_XOR && kMfma) return MMV_CPW_X8_MFMA;
+    if (kOp == kPlainScan && sizeof(typename TT::in_t) == 2) return MMV_CPW_F16_SCAN;
+    if (kOp == kPlainScan && sizeof(typename TT::in_t) == 4) return MMV_CPW_F32_SCAN;
+    return TT::kMaxCpw;
+}
+
 struct TInt {  // column indices of the COO matrix, loaded in the same layout as its values
     typedef int32_t in_t;
     static constexpr int kEpl = 4;

@@ -30,6 +30,16 @@ namespace {
 #ifndef MMV_CPW_F32
 #define MMV_CPW_F32 1    // most chunks per wave, fp32 inputs (2 spills registers)
 #endif
+// The scan without a flag vector (mmv_scan): every tile waits for the carry of the tiles before, so longer tiles
+// pay.  n = 2^28, % of peak: 16-bit inputs 3 chunks 70.8, 2 chunks 67 (4 spill); fp32 2 chunks 70.5 (shuffle 73.6)
+// although 24 bytes per lane spill, 1 chunk 60.6 (62.1); bytes: 5 or 6 chunks 66.7 against 74.5 with 4.
+// With flags the longer tiles lose (16-bit 78.5 -> 72 %; fp32 72 -> 62 %, 88 bytes spilled).
+#ifndef MMV_CPW_F16_SCAN
+#define MMV_CPW_F16_SCAN 3
+#endif
+#ifndef MMV_CPW_F32_SCAN
+#define MMV_CPW_F32_SCAN 2
+#endif
 #ifndef MMV_CPW_SPMV
 #define MMV_CPW_SPMV 1
 #endif
@@ -71,6 +81,9 @@ namespace {
 #endif
 #ifndef MMV_EARLY_F32
 #define MMV_EARLY_F32 0
+#endif
+#ifndef MMV_EARLY_F32_SCAN
+#define MMV_EARLY_F32_SCAN 3   // mmv_scan of 32-bit inputs: no tile has a flag, so nothing is there to lose
 #endif
 #ifndef MMV_EXACT_STARTS
 #define MMV_EXACT_STARTS 1   // 1: fp32 scans give a position that starts a segment its input bit for bit
