@@ -25,7 +25,12 @@ constexpr uint64_t kResident = MMV_MIN_TILES;   // workgroups resident at once (
 #ifndef MMV_TAIL_TILES
 #define MMV_TAIL_TILES 128   // tiles of one chunk per wave at the very end (the last of them is ragged)
 #endif
-constexpr uint64_t kCountSumTiles = 2048;        // up to this many tiles the segmented sum needs no prefix kernel
+// Up to this many tiles the segmented sum needs no prefix kernel: every wave of the main kernel adds up the counts of
+// the tiles before its own.  That loop costs in proportion to the number of tiles (1224 tiles: 5.6 us of a 42 us
+// kernel; 2448: 15 us), the prefix kernel 3 us of the call.
+constexpr uint64_t kCountSumTiles = 768;
+// CSR SpMV: one wave per tile adds up (959 tiles: the loop 1.4 us of the kernel, the prefix kernel 3 us of the call)
+constexpr uint64_t kCountSumTilesCsr = 2048;
 inline bool is_spmv(mmv_op op) { return op == MMV_OP_SPMV_COO || op == MMV_OP_SPMV_CSR; }
 // Most chunks per wave of the tile body that carries its pair from row to row (seg_tile).
 inline int row_form_cpw(mmv_op op, mmv_dtype dt, bool mfma) {

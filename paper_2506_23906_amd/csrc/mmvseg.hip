@@ -388,7 +388,7 @@ mmv_status mmv_spmv_csr(uint64_t n_rows, uint64_t n_cols, uint64_t nnz, const in
     P.hdr = (uint32_t *)(ws + C.main_ws);
     P.desc_v = (uint64_t *)(ws + C.main_ws + L.desc_v);
     P.fw = fw;
-    P.count_is_prefix = plan.tiles > kCountSumTiles ? 1u : 0u;
+    P.count_is_prefix = plan.tiles > kCountSumTilesCsr ? 1u : 0u;
     if (P.count_is_prefix) {
         scan_counts_kernel<<<1, 1024, 0, s>>>(tile_count, (uint32_t)plan.tiles, (uint64_t *)(ws + C.rowcount));
         if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;

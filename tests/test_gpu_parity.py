@@ -333,7 +333,9 @@ def test_sums_longer_than_one_round_of_workgroups(dtype, density):
     carry of all tiles) over a handful of flags (most tiles without one) to a flag in every row."""
     rng = np.random.default_rng(78)
     full = B.mmv_tile_elems(B.MMV_OP_SEGSUM, B._DTYPES[torch.from_numpy(np.zeros(1, dtype=dtype)).dtype], 1 << 40)
-    for n in (512 * full + 1, 517 * full + 54321):
+    # beyond 768 tiles a small kernel turns the per-tile counts of segment starts into prefix sums first
+    sizes = (512 * full + 1, 517 * full + 54321) + ((1100 * full + 77,) if density in (2e-5, 0.05) else ())
+    for n in sizes:
         x = random_values(rng, n, dtype)
         f = W.uniform_density_flags(n, density, seed=n % 1000)
         print("long sum", dtype.__name__, density, n, int(f.sum()), flush=True)
