@@ -474,7 +474,13 @@ def write_report(args, events: HipEvents) -> None:
     for variant in ("mfma", "shuffle"):
         run("scan (unsegmented) f16 n=2^%d %s" % (args.log2n, variant), n, n * 6,
             lambda: B.mmv_scan(xh, n=n, z=zf, variant=variant, ws=wsh), wsh, steps=30)
-    del xh, zf
+    del xh
+    xf = torch.from_numpy(np.random.default_rng(4).standard_normal(n, dtype=np.float32)).cuda()
+    ws32 = B.new_workspace(B.MMV_OP_SCAN, B.MMV_F32_F32, B.MMV_FLAGS_PACKED32, n)
+    for variant in ("mfma", "shuffle"):
+        run("scan (unsegmented) f32 n=2^%d %s" % (args.log2n, variant), n, n * 8,
+            lambda: B.mmv_scan(xf, n=n, z=zf, variant=variant, ws=ws32), ws32, steps=30)
+    del xf, zf
 
     # the primitives of Algorithms SCD / SSCR one by one, the un-fused compositions and the fused
     # calls, on uniformly random flags at the densities the paper's breakdown uses
