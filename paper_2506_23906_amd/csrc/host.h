@@ -37,7 +37,7 @@ inline int row_form_cpw(mmv_op op, mmv_dtype dt, bool mfma) {
     if (is_spmv(op)) return TSpmv::kMaxCpw;
     const bool plain = op == MMV_OP_SCAN;
     switch (dt) {
-        case MMV_F32_F32: return plain ? chunks_per_wave<TF32, kPlainScan, true>() : TF32::kMaxCpw;
+        case MMV_F32_F32: return plain ? chunks_per_wave<TF32, kPlainScan, true>() : op == MMV_OP_SEGSUM ? (mfma ? chunks_per_wave<TF32, kSum, true>() : chunks_per_wave<TF32, kSum, false>()) : TF32::kMaxCpw;
         case MMV_F16_F32: return plain ? chunks_per_wave<TF16, kPlainScan, true>() : TF16::kMaxCpw;
         case MMV_BF16_F32: return plain ? chunks_per_wave<TBF16, kPlainScan, true>() : TBF16::kMaxCpw;
         case MMV_I8_I32: return plain ? chunks_per_wave<TI8, kPlainScan, true>() : TI8::kMaxCpw;

@@ -71,11 +71,13 @@ struct TSpmv : TF32 {  // COO SpMV: values and column indices both sit in regist
 };
 // Most chunks a wave of seg_tile takes.  Bytes under exclusive or in the matrix-core variant hold four accumulators
 // of bit-plane sums per tile next to the raw words: two chunks fit the registers, four spill.  The scan without a
-// flag vector keeps no flag words and no carried flags, which leaves room for longer tiles of 16- and 32-bit inputs.
+// flag vector keeps no flag words and no carried flags, which leaves room for longer tiles of 16- and 32-bit inputs; so does
+// the segmented sum of fp32 values in the variant without the matrix cores.
 template <typename TT, int kOp, bool kMfma> constexpr int chunks_per_wave() {
     if (TT::kDtype == MMV_U8_XOR && kMfma) return MMV_CPW_X8_MFMA;
     if (kOp == kPlainScan && sizeof(typename TT::in_t) == 2) return MMV_CPW_F16_SCAN;
     if (kOp == kPlainScan && sizeof(typename TT::in_t) == 4) return MMV_CPW_F32_SCAN;
+    if (kOp == kSum && TT::kDtype == MMV_F32_F32 && !kMfma) return MMV_CPW_F32_SUM_SHUFFLE;
     return TT::kMaxCpw;
 }
 

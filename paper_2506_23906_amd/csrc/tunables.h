@@ -40,6 +40,13 @@ namespace {
 #ifndef MMV_CPW_F32_SCAN
 #define MMV_CPW_F32_SCAN 2
 #endif
+// Segmented sum of fp32 values without the matrix cores: two chunks per wave fit the registers (111) and halve the
+// tickets, barriers and look-backs per element: n = 2^28 52 -> 73 % of peak.  On the matrix cores two chunks spill
+// (the three-way split of a chunk and its 16 accumulators beside the other chunk's 32 registers: 40 to 144 bytes
+// per lane however the loops are shaped) and end at 46 to 50 %, so that variant keeps one.
+#ifndef MMV_CPW_F32_SUM_SHUFFLE
+#define MMV_CPW_F32_SUM_SHUFFLE 2
+#endif
 #ifndef MMV_CPW_SPMV
 #define MMV_CPW_SPMV 1
 #endif

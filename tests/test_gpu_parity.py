@@ -343,6 +343,20 @@ def test_sums_longer_than_one_round_of_workgroups(dtype, density):
         check_sum(out, nseg, x, f)
 
 
+def test_fp32_sums_without_matrix_cores_longer_than_one_round_of_workgroups():
+    """The segmented sum of fp32 values in the variant without the matrix cores takes two chunks per wave (tiles twice
+    as long as those of the other fp32 kernels), so its vectors need twice the length to go beyond one round of
+    workgroups, to tiles taken by ticket and to tiles of growing and shrinking length."""
+    rng = np.random.default_rng(79)
+    full = 2 * B.mmv_tile_elems(B.MMV_OP_SEGSUM, B.MMV_F32_F32, 1 << 40)
+    for n, density in ((512 * full + 1, 2e-5), (517 * full + 54321, 1e-3), (800 * full + 77, 0.05)):
+        x = random_values(rng, n, np.float32)
+        f = W.uniform_density_flags(n, density, seed=n % 1000)
+        print("long fp32 sum", n, density, flush=True)
+        out, nseg = run_segsum(x, f, "shuffle")
+        check_sum(out, nseg, x, f)
+
+
 def test_long_sum_with_an_output_array_that_is_too_short():
     """The streaming sum kernel writes its outputs as it goes, and the one per wave that waits for a carry at the end of
     the tile: none of them may land beyond the capacity the caller gave, and the count is the true one."""
