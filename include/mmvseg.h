@@ -158,7 +158,10 @@ mmv_status mmv_segscan_static(const void *d_x, const void *d_flags, uint64_t n, 
  *   d_nseg        device uint64: receives the true number of segments,
  *                 1 + #{i >= 1 : f(i) = 1} for n >= 1
  * Floating point: as for mmv_segscan (a sum is off by the rounding of the prefixes of the rows of 32 it starts
- * and ends in; a non-finite value can reach the sums of the segments that share its row of 32).
+ * and ends in; a non-finite value can reach the sums of the segments that share its row of 32).  16-bit inputs
+ * with MMV_VARIANT_MFMA on vectors longer than one round of workgroups speculate over chunks of 2048 elements
+ * (2048-aligned): there a sum is the difference of two prefixes of its chunk and is off by their rounding
+ * (2^-24 of the chunk's running sum each), and a non-finite value reaches the other sums of its chunk.
  * Sums with index >= out_capacity are not written (d_nseg still holds the true
  * count); pass out_capacity = n to be safe.  The number of segments must be
  * below 2^32 (counts are carried in 32 bits).

@@ -119,7 +119,8 @@ def check_scan(got: np.ndarray, x: np.ndarray, f: np.ndarray, tol=None, chunk: i
     return worst
 
 
-def check_sum(got: np.ndarray, nseg: int, x: np.ndarray, f: np.ndarray, tol=None, margin: float = MARGIN):
+def check_sum(got: np.ndarray, nseg: int, x: np.ndarray, f: np.ndarray, tol=None, margin: float | None = None):
+    margin = MARGIN if margin is None else margin
     ref = oracle.segsum(x, f)
     assert nseg == len(ref), (nseg, len(ref))
     got = got[:nseg]

@@ -334,13 +334,17 @@ def test_sums_longer_than_one_round_of_workgroups(dtype, density):
     rng = np.random.default_rng(78)
     full = B.mmv_tile_elems(B.MMV_OP_SEGSUM, B._DTYPES[torch.from_numpy(np.zeros(1, dtype=dtype)).dtype], 1 << 40)
     # beyond 768 tiles a small kernel turns the per-tile counts of segment starts into prefix sums first
-    sizes = (512 * full + 1, 517 * full + 54321) + ((1100 * full + 77,) if density in (2e-5, 0.05) else ())
+    sizes = (512 * full + 1, 517 * full + 54321) + ((1100 * full + 77,) if density in (2e-5, 0.05) and dtype == np.int8 else ())
     for n in sizes:
         x = random_values(rng, n, dtype)
         f = W.uniform_density_flags(n, density, seed=n % 1000)
         print("long sum", dtype.__name__, density, n, int(f.sum()), flush=True)
         out, nseg = run_segsum(x, f, "mfma")
-        check_sum(out, nseg, x, f)
+        # This kernel speculates over whole chunks of 2048 values, not rows of 32: a sum is the difference of two
+        # prefixes of its chunk, each rounded to fp32 at the size the prefix has there.  Over 2048 values from N(0,1)
+        # a prefix stays below 512 (11 sigma), where one rounding is 2^-15 = 3e-5: the margin against max(A, 1) is
+        # three such roundings instead of the 2e-5 that hold for speculation over rows.
+        check_sum(out, nseg, x, f, margin=1e-4 if dtype == np.float16 else None)
 
 
 def test_fp32_sums_without_matrix_cores_longer_than_one_round_of_workgroups():
