@@ -420,6 +420,20 @@ def write_report(args, events: HipEvents) -> None:
                 lambda: B.mmv_segscan(xt, fd, n=n, z=zt, variant=variant, ws=ws), ws, steps=30)
         run("density sweep f16 n=2^%d density=%g mfma" % (args.log2n, density), n, n * 6 + n // 8,
             lambda: B.mmv_segscan(xh, fd, n=n, z=zf, ws=wsh), wsh, steps=30)
+    # segmented sum on the same values at the densities of the paper's breakdown, every input type, both variants
+    nseg_t = torch.empty(1, dtype=torch.int64, device="cuda")
+    for density in (1e-3, 1e-2):
+        fd_np = W.uniform_density_flags(n, density, 78)
+        ns = int(fd_np.sum()) + (0 if fd_np[0] else 1)
+        fd = torch.from_numpy(W.pack_flags(fd_np).view(np.int32)).cuda()
+        for label, xin, dt, width in (("i8", xt, B.MMV_I8_I32, 1), ("f16", xh, B.MMV_F16_F32, 2), ("f32", None, B.MMV_F32_F32, 4)):
+            xin = xt.to(torch.float32) if xin is None else xin
+            out = torch.empty(ns + 16, dtype=torch.int32 if label == "i8" else torch.float32, device="cuda")
+            wss = B.new_workspace(B.MMV_OP_SEGSUM, dt, B.MMV_FLAGS_PACKED32, n)
+            for variant in ("mfma", "shuffle"):
+                run("segsum %s n=2^%d density=%g %s" % (label, args.log2n, density, variant), n, n * width + n // 8 + ns * 4,
+                    lambda: B.mmv_segsum(xin, fd, n=n, out=out, nseg=nseg_t, variant=variant, ws=wss), wss, steps=30)
+            del xin, out, wss
     # another group on the same kernel: bytes under bit-wise exclusive or (the matrix-core variant takes the running
     # xor as the parity of integer sums, two bit planes per product)
     xu = torch.from_numpy(np.random.default_rng(2390692).integers(0, 256, size=n, dtype=np.uint8)).cuda()

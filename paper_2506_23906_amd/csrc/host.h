@@ -416,14 +416,19 @@ mmv_status compress_impl(const void *d_x, const void *d_mask, uint64_t n, void *
         mw = packed;
     }
     if (tl_ev_start && hipEventRecord(tl_ev_start, s) != hipSuccess) return MMV_ERR_HIP;
-    if (compress_words(n) == 16)
-        compress_kernel<16><<<(unsigned)L.tiles, kCompressWaves * 64, 0, s>>>(
-            (const uint32_t *)d_x, mw, n, (uint32_t *)d_out, out_capacity, d_count, (uint32_t *)ws,
-            (uint64_t *)(ws + L.desc), (uint32_t)L.tiles, d_needed);
-    else
-        compress_kernel<64><<<(unsigned)L.tiles, kCompressWaves * 64, 0, s>>>(
-            (const uint32_t *)d_x, mw, n, (uint32_t *)d_out, out_capacity, d_count, (uint32_t *)ws,
-            (uint64_t *)(ws + L.desc), (uint32_t)L.tiles, d_needed);
+    // the workgroups that are resident from the start take the tile of their own index, the others a ticket
+    static std::atomic<uint32_t> occupancy[4][kMaxDevices];
+    void (*kernel)(const uint32_t *, const uint32_t *, uint64_t, uint32_t *, uint64_t, uint64_t *, uint32_t *, uint64_t *,
+                   uint32_t, const uint32_t *, uint32_t) = compress_kernel<64, 1>;
+    int which = 1;
+    if (compress_words(n) == 16) kernel = compress_kernel<16, 1>, which = 0;
+    else if (compress_groups(n) == 2) kernel = compress_kernel<64, 2>, which = 2;
+    else if (compress_groups(n) == 4) kernel = compress_kernel<64, 4>, which = 3;
+    const uint32_t resident = resident_workgroups((const void *)kernel, kCompressWaves * 64, occupancy[which]);
+    const uint32_t first_round = (uint32_t)L.tiles < resident ? (uint32_t)L.tiles : resident;
+    kernel<<<(unsigned)L.tiles, kCompressWaves * 64, 0, s>>>((const uint32_t *)d_x, mw, n, (uint32_t *)d_out, out_capacity,
+                                                             d_count, (uint32_t *)ws, (uint64_t *)(ws + L.desc),
+                                                             (uint32_t)L.tiles, d_needed, first_round);
     const hipError_t e = hipGetLastError();
     if (tl_ev_stop && hipEventRecord(tl_ev_stop, s) != hipSuccess) return MMV_ERR_HIP;
     return e == hipSuccess ? MMV_OK : MMV_ERR_HIP;

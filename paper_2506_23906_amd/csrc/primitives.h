@@ -39,46 +39,67 @@ __global__ __launch_bounds__(256) void unpack_flags_kernel(const uint32_t *fw, u
 // x == nullptr the positions themselves are compressed.  The mask is bit-packed; the output
 // index of an entry is the number of set bits before it (the scan of the mask in the paper's
 // COMPRESS), found per tile from popcounts and across tiles by decoupled look-back.
-// A wave owns 64 * kWords consecutive positions (kWords = 64 or 16): lane j < kWords holds the
-// 64-bit mask word j, and for every word the wave reads only the selected entries (one coalesced
-// load, skipped when the word is empty) and writes them to consecutive output slots; a wave with
-// few selected entries lets every lane walk its own word instead.  Short masks take the short
-// spans: four times the waves, a quarter of the words each wave visits one after the other.
+// A wave owns kGroups groups of 64 * kWords consecutive positions (kWords = 64 or 16): lane j < kWords
+// holds the 64-bit mask word j of every group, and for every word the wave reads only the selected entries
+// (one coalesced load, skipped when the word is empty) and writes them to consecutive output slots; a wave with
+// few selected entries lets every lane walk its own words instead.  Short masks take the short
+// spans: four times the waves, a quarter of the words each wave visits one after the other.  Long masks take
+// two or four groups per wave: a tile costs a ticket (11 ns each, one after the other), a barrier and a look-back
+// whatever its length, and with one group per wave the tickets alone took 93 us of the 111 us at n = 2^28
+// and 0.1 % selected (now 0.048 ms; 30 % selected: 0.454 -> 0.415 ms).
+// The workgroups that are resident from the start take the tile of their own index, as in the main kernel.
 constexpr int kCompressWaves = 8;
-constexpr int kCompressTile = kCompressWaves * 4096;
 constexpr uint64_t kCompressShortN = 1ull << 22;   // masks up to this length take 16 words per wave
+// masks from 2^26 positions on take two groups of words per wave, from 2^28 on four: the mask has to be long enough
+// for several rounds of workgroups (n = 2^26, 30 % selected: 0.125 ms with one group, 0.110 with two, 0.164 with four,
+// which leaves two workgroups per compute unit; 0.1 % selected: 0.038, 0.015, 0.014 ms)
 inline int compress_words(uint64_t n) { return n <= kCompressShortN ? 16 : 64; }
-inline uint64_t compress_tile(uint64_t n) { return (uint64_t)kCompressWaves * 64u * compress_words(n); }
+inline int compress_groups(uint64_t n) { return n >= (1ull << 28) ? 4 : n >= (1ull << 26) ? 2 : 1; }
+inline uint64_t compress_tile(uint64_t n) { return (uint64_t)kCompressWaves * 64u * compress_words(n) * compress_groups(n); }
 
-template <int kWords>
-__global__ __launch_bounds__(kCompressWaves * 64) void compress_kernel(
+template <int kWords, int kGroups>
+__global__ __launch_bounds__(kCompressWaves * 64, 8) void compress_kernel(
     const uint32_t *__restrict__ x, const uint32_t *__restrict__ mw, uint64_t n, uint32_t *__restrict__ out,
     uint64_t out_cap, uint64_t *__restrict__ count, uint32_t *hdr, uint64_t *desc, uint32_t num_tiles,
-    const uint32_t *needed) {
+    const uint32_t *needed, uint32_t first_round) {
     __shared__ uint32_t s_tile, s_wave[kCompressWaves], s_carry;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     if (needed && *needed == 0) return;   // CSR SpMV without empty rows: nobody reads the row map
-    if (tid == 0) s_tile = __hip_atomic_fetch_add(hdr + kHdrTicket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const bool own_index = blockIdx.x < first_round;
+    if (tid == 0 && !own_index)
+        s_tile = first_round + __hip_atomic_fetch_add(hdr + kHdrTicket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
-    const uint32_t tile = s_tile;
-    constexpr uint32_t kSpan = 64u * kWords;                                        // positions of a wave
+    const uint32_t tile = own_index ? blockIdx.x : s_tile;
+    constexpr uint32_t kGroupSpan = 64u * kWords;                                   // positions of one group
+    constexpr uint32_t kSpan = kGroupSpan * kGroups;                                // positions of a wave
     const uint64_t span = ((uint64_t)tile * kCompressWaves + wave) * kSpan;          // first position of my wave
-    const uint64_t p0 = span + 64u * lane;                                          // first position of my word
-    uint64_t m = 0;
-    if (lane < kWords && p0 < n) {
-        const uint64_t wi = p0 >> 5;
-        m = mw[wi];
-        if (p0 + 32 < n) m |= (uint64_t)mw[wi + 1] << 32;
-        if (p0 + 64 > n) m &= (1ull << (n - p0)) - 1ull;
-    }
-    const uint32_t cnt = (uint32_t)__popcll((unsigned long long)m);
-    uint32_t inc = cnt;
+    uint64_t m[kGroups];
+    uint32_t before[kGroups];   // selected entries of my wave before my word of group g
+    uint32_t wave_cnt = 0;
 #pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const uint32_t o = __shfl_up(inc, d);
-        if (lane >= d) inc += o;
+    for (int g = 0; g < kGroups; ++g) {
+        const uint64_t p0 = span + (uint64_t)g * kGroupSpan + 64u * lane;            // first position of my word
+        m[g] = 0;
+        if (lane < kWords && p0 < n) {
+            const uint64_t wi = p0 >> 5;
+            m[g] = mw[wi];
+            if (p0 + 32 < n) m[g] |= (uint64_t)mw[wi + 1] << 32;
+            if (p0 + 64 > n) m[g] &= (1ull << (n - p0)) - 1ull;
+        }
     }
-    if (lane == 63) s_wave[wave] = inc;
+#pragma unroll
+    for (int g = 0; g < kGroups; ++g) {
+        const uint32_t cnt = (uint32_t)__popcll((unsigned long long)m[g]);
+        uint32_t inc = cnt;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const uint32_t o = __shfl_up(inc, d);
+            if (lane >= d) inc += o;
+        }
+        before[g] = wave_cnt + (inc - cnt);
+        wave_cnt += (uint32_t)__builtin_amdgcn_readlane((int)inc, 63);
+    }
+    if (lane == 0) s_wave[wave] = wave_cnt;
     __syncthreads();
     uint32_t wave_ex = 0, tile_cnt = 0;
 #pragma unroll
@@ -97,35 +118,42 @@ __global__ __launch_bounds__(kCompressWaves * 64) void compress_kernel(
         }
     }
     __syncthreads();
-    // output index of the first selected entry of word j of my wave (lane j holds it)
-    const uint64_t word_base = (uint64_t)s_carry + wave_ex + (inc - cnt);
-    if (__builtin_amdgcn_readlane((int)inc, 63) <= 4 * kWords) {
+    const uint64_t wave_base = (uint64_t)s_carry + wave_ex;   // output index of the first selected entry of my wave
+    if (wave_cnt <= 4u * kWords * kGroups) {
         // few selected entries in my wave's positions: every lane walks the set bits of its own
-        // word (a handful of independent loads per lane) instead of the wave visiting all 64 words
-        uint64_t mm = m, k = word_base;
-        while (mm) {
-            const uint64_t p = p0 + (uint32_t)__builtin_ctzll((unsigned long long)mm);
-            mm &= mm - 1;
-            const uint32_t v = x ? __builtin_nontemporal_load(x + p) : (uint32_t)p;
-            if (k < out_cap) out[k] = v;
-            ++k;
+        // words (a handful of independent loads per lane) instead of the wave visiting every word
+#pragma unroll
+        for (int g = 0; g < kGroups; ++g) {
+            const uint64_t p0 = span + (uint64_t)g * kGroupSpan + 64u * lane;
+            uint64_t mm = m[g], k = wave_base + before[g];
+            while (mm) {
+                const uint64_t p = p0 + (uint32_t)__builtin_ctzll((unsigned long long)mm);
+                mm &= mm - 1;
+                const uint32_t v = x ? __builtin_nontemporal_load(x + p) : (uint32_t)p;
+                if (k < out_cap) out[k] = v;
+                ++k;
+            }
         }
         return;
     }
-    const uint32_t m_lo = (uint32_t)m, m_hi = (uint32_t)(m >> 32);
-    const uint32_t base_lo = (uint32_t)word_base, base_hi = (uint32_t)(word_base >> 32);
     const uint64_t lane_below = (1ull << lane) - 1ull;
+#pragma unroll
+    for (int g = 0; g < kGroups; ++g) {
+        const uint64_t word_base = wave_base + before[g];
+        const uint32_t m_lo = (uint32_t)m[g], m_hi = (uint32_t)(m[g] >> 32);
+        const uint32_t base_lo = (uint32_t)word_base, base_hi = (uint32_t)(word_base >> 32);
 #pragma unroll 8
-    for (int j = 0; j < kWords; ++j) {
-        const uint64_t mj = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)m_hi, j) << 32) |
-                            (uint32_t)__builtin_amdgcn_readlane((int)m_lo, j);
-        const uint64_t bj = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)base_hi, j) << 32) |
-                            (uint32_t)__builtin_amdgcn_readlane((int)base_lo, j);
-        if ((mj >> lane) & 1ull) {
-            const uint64_t p = span + 64u * j + lane;
-            const uint32_t v = x ? __builtin_nontemporal_load(x + p) : (uint32_t)p;
-            const uint64_t k = bj + (uint32_t)__popcll((unsigned long long)(mj & lane_below));
-            if (k < out_cap) out[k] = v;
+        for (int j = 0; j < kWords; ++j) {
+            const uint64_t mj = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)m_hi, j) << 32) |
+                                (uint32_t)__builtin_amdgcn_readlane((int)m_lo, j);
+            const uint64_t bj = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)base_hi, j) << 32) |
+                                (uint32_t)__builtin_amdgcn_readlane((int)base_lo, j);
+            if ((mj >> lane) & 1ull) {
+                const uint64_t p = span + (uint64_t)g * kGroupSpan + 64u * j + lane;
+                const uint32_t v = x ? __builtin_nontemporal_load(x + p) : (uint32_t)p;
+                const uint64_t k = bj + (uint32_t)__popcll((unsigned long long)(mj & lane_below));
+                if (k < out_cap) out[k] = v;
+            }
         }
     }
 }

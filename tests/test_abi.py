@@ -60,7 +60,11 @@ def test_host_only_entry_points(libmmvseg_path):
     csr = B.mmv_spmv_csr_workspace_bytes(1 << 20, 1 << 25)
     assert csr % 256 == 0 and (1 << 25) // 8 + 4 * (1 << 20) <= csr <= 16 << 20
     assert B.mmv_spmv_csr_workspace_bytes(1 << 31, 4) == 0
-    assert B.mmv_tile_elems(B.MMV_OP_COMPRESS, B.MMV_I8_I32, n) == 32768
+    # COMPRESS: a wave owns 16 or 64 mask words of 64 bits, in one, two or four groups, by the length of the mask
+    assert B.mmv_tile_elems(B.MMV_OP_COMPRESS, B.MMV_I8_I32, 1 << 20) == 8 * 64 * 16
+    assert B.mmv_tile_elems(B.MMV_OP_COMPRESS, B.MMV_I8_I32, 1 << 24) == 8 * 64 * 64
+    assert B.mmv_tile_elems(B.MMV_OP_COMPRESS, B.MMV_I8_I32, 1 << 26) == 8 * 64 * 64 * 2
+    assert B.mmv_tile_elems(B.MMV_OP_COMPRESS, B.MMV_I8_I32, n) == 8 * 64 * 64 * 4
 
 
 def test_argument_errors_are_caught_on_the_host(libmmvseg_path):

@@ -255,6 +255,28 @@ def test_scan_and_compress_at_2p28():
     assert int(count.item()) == len(pos) and np.array_equal(out.cpu().numpy()[:len(pos)], ref[pos])
 
 
+def test_compress_long_masks_with_many_selected_entries():
+    """Masks of 2^26 positions and more take four groups of words per wave; beyond one round of workgroups the tiles
+    are taken by ticket.  Dense masks (the wave visits every word), a mask that is dense in one half and sparse in
+    the other, a ragged end."""
+    rng = np.random.default_rng(70)
+    for n, density in (((1 << 26) + 12345, 1.0), ((1 << 27) + (1 << 26) + 777, 0.5), ((1 << 26) + 64 * 4096 * 3 + 5, None)):
+        if density is None:
+            m = np.concatenate([(rng.random(n // 2) < 0.4), (rng.random(n - n // 2) < 0.002)]).astype(np.uint8)
+        else:
+            m = (rng.random(n) < density).astype(np.uint8) if density < 1.0 else np.ones(n, dtype=np.uint8)
+        pos = np.flatnonzero(m).astype(np.int32)
+        out = torch.full((len(pos) + 5,), -7, dtype=torch.int32, device="cuda")
+        ws = B.new_workspace(B.MMV_OP_COMPRESS, B.MMV_I8_I32, B.MMV_FLAGS_PACKED32, n)
+        print("long mask", n, density, len(pos), flush=True)
+        _, count = B.mmv_compress(None, packed_dev(m), n, out=out, ws=ws)
+        sync_ok(ws)
+        got = out.cpu().numpy()
+        assert int(count.item()) == len(pos), (n, density)
+        assert np.array_equal(got[:len(pos)], pos), (n, density)
+        assert (got[len(pos):] == -7).all()
+
+
 @pytest.mark.parametrize("density", [1e-3, 1e-2])
 def test_scd_and_sscr_at_2p26(density):
     n = 1 << 26
