@@ -95,7 +95,7 @@ __device__ __forceinline__ void seg_tile(const Params &P, const uint32_t *__rest
     // flags in Algorithm "Revert Speculative Prefix Sums", taken per element).  16-bit inputs do not need it: their
     // row prefixes are exact in fp32 unless the exponents of a row differ widely.
     constexpr bool kExactStarts = MMV_EXACT_STARTS != 0 && kOp == kScan && sizeof(In) == 4;
-    constexpr int kEarlyMode = !kScanLike ? 0 : (sizeof(In) == 1 ? MMV_EARLY_I8 : (sizeof(In) == 2 ? MMV_EARLY_F16 : (kOp == kPlainScan ? MMV_EARLY_F32_SCAN : MMV_EARLY_F32)));
+    constexpr int kEarlyMode = !kScanLike ? 0 : (sizeof(In) == 1 ? MMV_EARLY_I8 : (sizeof(In) == 2 ? MMV_EARLY_F16 : (kOp == kPlainScan ? MMV_EARLY_F32_SCAN : (kMfma ? MMV_EARLY_F32 : MMV_EARLY_F32_SHUFFLE))));
     constexpr bool kEarly = kEarlyMode != 0;
     constexpr bool kEarlyLookback = kEarlyMode == 2;
     // mode 3: that wave asks for the descriptors of the tiles before at the end of its phase A and looks at them after

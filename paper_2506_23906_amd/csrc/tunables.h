@@ -78,8 +78,9 @@ namespace {
 // 1 = the plain sum is published as soon as the tile's loads have landed; 2 = and the wave that publishes it looks
 // back for the carry at once; 3 = that wave asks for the descriptors of the tiles before when its phase A is done and
 // looks at them after the barrier (the look-back takes 3 to 4 us whoever has published what, so it pays to have the
-// poll under way early; 2 makes the wave late for the barrier).  Per input width (measured best on MI355X; 32-bit inputs:
-// 3 makes the vector without flags 5 % faster and every vector with flags 2 % slower).
+// poll under way early; 2 makes the wave late for the barrier).  Per input width (measured best on MI355X; 32-bit inputs
+// on the matrix cores: 3 makes the vector without flags 5 % faster and every vector with flags 2 % slower; without the
+// matrix cores it costs the vectors with flags nothing: MMV_EARLY_F32_SHUFFLE).
 #ifndef MMV_EARLY_I8
 #define MMV_EARLY_I8 3
 #endif
@@ -88,6 +89,10 @@ namespace {
 #endif
 #ifndef MMV_EARLY_F32
 #define MMV_EARLY_F32 0
+#endif
+#ifndef MMV_EARLY_F32_SHUFFLE
+#define MMV_EARLY_F32_SHUFFLE 3   // 32-bit inputs without the matrix cores: one segment of 2^28 values 57 -> 64 % of peak, and
+                                  // nothing lost with flags (every flag set 78 -> 79.5 %, lengths U{1..64} 72 %): 2^30 stress 73 -> 75.3 %
 #endif
 #ifndef MMV_EARLY_F32_SCAN
 #define MMV_EARLY_F32_SCAN 3   // mmv_scan of 32-bit inputs: no tile has a flag, so nothing is there to lose
