@@ -32,18 +32,23 @@ constexpr uint64_t kCountSumTiles = 768;
 // CSR SpMV: one wave per tile adds up (959 tiles: the loop 1.4 us of the kernel, the prefix kernel 3 us of the call)
 constexpr uint64_t kCountSumTilesCsr = 2048;
 inline bool is_spmv(mmv_op op) { return op == MMV_OP_SPMV_COO || op == MMV_OP_SPMV_CSR; }
-// Most chunks per wave of the tile body that carries its pair from row to row (seg_tile).
+// Most chunks per wave of the tile body that carries its pair from row to row (seg_tile): what the kernel
+// instantiation for this operation, type and variant is built with.
+template <typename TT> inline int row_form_cpw_of(mmv_op op, bool mfma) {
+    switch (op) {
+        case MMV_OP_SCAN: return mfma ? chunks_per_wave<TT, kPlainScan, true>() : chunks_per_wave<TT, kPlainScan, false>();
+        case MMV_OP_SEGSUM: return mfma ? chunks_per_wave<TT, kSum, true>() : chunks_per_wave<TT, kSum, false>();
+        default: return mfma ? chunks_per_wave<TT, kScan, true>() : chunks_per_wave<TT, kScan, false>();
+    }
+}
 inline int row_form_cpw(mmv_op op, mmv_dtype dt, bool mfma) {
     if (is_spmv(op)) return TSpmv::kMaxCpw;
-    const bool plain = op == MMV_OP_SCAN;
     switch (dt) {
-        case MMV_F32_F32: return plain ? chunks_per_wave<TF32, kPlainScan, true>() : op == MMV_OP_SEGSUM ? (mfma ? chunks_per_wave<TF32, kSum, true>() : chunks_per_wave<TF32, kSum, false>()) : TF32::kMaxCpw;
-        case MMV_F16_F32: return plain ? chunks_per_wave<TF16, kPlainScan, true>() : TF16::kMaxCpw;
-        case MMV_BF16_F32: return plain ? chunks_per_wave<TBF16, kPlainScan, true>() : TBF16::kMaxCpw;
-        case MMV_I8_I32: return plain ? chunks_per_wave<TI8, kPlainScan, true>() : TI8::kMaxCpw;
-        case MMV_U8_XOR:
-            if (plain) return mfma ? chunks_per_wave<TX8, kPlainScan, true>() : chunks_per_wave<TX8, kPlainScan, false>();
-            return mfma ? chunks_per_wave<TX8, kScan, true>() : chunks_per_wave<TX8, kScan, false>();
+        case MMV_F32_F32: return row_form_cpw_of<TF32>(op, mfma);
+        case MMV_F16_F32: return row_form_cpw_of<TF16>(op, mfma);
+        case MMV_BF16_F32: return row_form_cpw_of<TBF16>(op, mfma);
+        case MMV_I8_I32: return row_form_cpw_of<TI8>(op, mfma);
+        case MMV_U8_XOR: return row_form_cpw_of<TX8>(op, mfma);
         default: break;
     }
     return 1;

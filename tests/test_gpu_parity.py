@@ -303,6 +303,21 @@ def test_bf16_2p24_uniform_len(variant):
     check_sum(out, nseg, x32, f, tol=1e-2)
 
 
+@pytest.mark.parametrize("density", [2e-5, 1e-3, 0.05])
+def test_bf16_sums_longer_than_one_round_of_workgroups(density):
+    """The kernel that streams through long spans, bf16 instantiation (see test_sums_longer_than_one_round_of_workgroups
+    for the margin: speculation over chunks of 2048 values; bf16 inputs carry 8 significant bits, their sums are
+    rounded like those of any other fp32 values)."""
+    rng = np.random.default_rng(25)
+    full = B.mmv_tile_elems(B.MMV_OP_SEGSUM, B.MMV_BF16_F32, 1 << 40)
+    n = 513 * full + 4321
+    xt, x32 = _bf16_values(rng, n)
+    f = W.uniform_density_flags(n, density, seed=n % 1000)
+    print("long bf16 sum", density, n, flush=True)
+    out, nseg = run_segsum(x32, f, "mfma", xt=xt)
+    check_sum(out, nseg, x32, f, tol=1e-2, margin=1e-4)
+
+
 # ---- the benchmark workloads: scaled twins, then full size ------------------------------------------
 
 @pytest.mark.parametrize("variant", VARIANTS)
