@@ -453,6 +453,11 @@ def write_report(args, events: HipEvents) -> None:
     for variant in ("mfma", "shuffle"):
         run("4 spmv coo 2^20 x 2^20 nnz=%d zipf(1.5) %s" % (nnz, variant), nnz, nnz * 12 + 2 * nr * 4,
             lambda: B.mmv_spmv_coo(nr, nr, rt, ct, vt, xvt, y=yt, variant=variant, ws=ws), ws)
+    # the same product in two steps: the flags made once (mmv_spmv_coo_prepare), every timed call the product alone
+    B.mmv_spmv_coo_prepare(nr, nr, rt, ct, ws=ws)
+    ms = call_ms(lambda: B.mmv_spmv_coo_run(nr, nr, rt, ct, vt, xvt, ws, y=yt))
+    emit(workload="4 spmv coo, prepared matrix (mmv_spmv_coo_run, whole call)", nnz=nnz, ms=ms, gnnz_s=nnz / ms / 1e6,
+         algo_bytes=nnz * 8 + nnz // 8 + 2 * nr * 4, gb_s=(nnz * 8 + nnz // 8 + 2 * nr * 4) / ms / 1e6)
     # what the random accesses to x cost on their own (val and col streamed, x[col] gathered, nothing else)
     part = torch.empty(B.GATHER_REFERENCE_PARTIALS, dtype=torch.float32, device="cuda")
     ms = call_ms(lambda: B.mmv_gather_reference(vt, ct, xvt, part))
@@ -554,6 +559,10 @@ def write_report(args, events: HipEvents) -> None:
     ms = call_ms(lambda: B.mmv_spmv_csr(nr, nr, rpt, ct, vt, xvt, y=yt, ws=wsv))
     emit(workload="4 spmv csr 2^20 x 2^20 nnz=%d zipf(1.5)" % nnz, nnz=nnz, ms=ms, gnnz_s=nnz / ms / 1e6,
          algo_bytes=nnz * 8 + 3 * nr * 4, gb_s=(nnz * 8 + 3 * nr * 4) / ms / 1e6)
+    B.mmv_spmv_csr_prepare(nr, nr, rpt, ct, ws=wsv)
+    ms = call_ms(lambda: B.mmv_spmv_csr_run(nr, nr, rpt, ct, vt, xvt, wsv, y=yt))
+    emit(workload="4 spmv csr, prepared matrix (mmv_spmv_csr_run, whole call)", nnz=nnz, ms=ms, gnnz_s=nnz / ms / 1e6,
+         algo_bytes=nnz * 8 + nnz // 8 + 2 * nr * 4, gb_s=(nnz * 8 + nnz // 8 + 2 * nr * 4) / ms / 1e6)
     del rpt, ct, vt, xvt, wsv
     na = 1 << 16
     for block in (2, 4, 16, 64):
@@ -567,6 +576,10 @@ def write_report(args, events: HipEvents) -> None:
             emit(workload="spmv csr sparse attention 65536^2 b-%d_r-%d" % (block, n_random), nnz=nz, ms=ms,
                  gnnz_s=nz / ms / 1e6, algo_bytes=nz * 8 + 3 * na * 4, gb_s=(nz * 8 + 3 * na * 4) / ms / 1e6)
             if n_random == 8:
+                B.mmv_spmv_csr_prepare(na, na, rpt, ct, ws=wsv)
+                ms = call_ms(lambda: B.mmv_spmv_csr_run(na, na, rpt, ct, vt, xat, wsv, y=ya))
+                emit(workload="spmv csr sparse attention 65536^2 b-%d_r-%d, prepared matrix" % (block, n_random), nnz=nz, ms=ms,
+                     gnnz_s=nz / ms / 1e6, algo_bytes=nz * 8 + nz // 8 + 2 * na * 4, gb_s=(nz * 8 + nz // 8 + 2 * na * 4) / ms / 1e6)
                 part = torch.empty(B.GATHER_REFERENCE_PARTIALS, dtype=torch.float32, device="cuda")
                 ms = call_ms(lambda: B.mmv_gather_reference(vt, ct, xat, part))
                 emit(workload="gather reference sparse attention 65536^2 b-%d_r-%d" % (block, n_random), nnz=nz, ms=ms,

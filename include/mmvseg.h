@@ -203,6 +203,34 @@ mmv_status mmv_spmv_csr(uint64_t n_rows, uint64_t n_cols, uint64_t nnz,
                         const float *d_x, float *d_y, mmv_variant v,
                         void *d_ws, size_t ws_bytes, void *hip_stream);
 
+/* SpMV in two steps, for a matrix that is multiplied more than once (an iterative solver, an attention mask): what
+ * depends on the matrix alone (Sec. 4.3: the segment-start flags from the row indices or row pointers; for CSR also the
+ * number of segment starts per tile and the list of rows that have entries) is made once by the `_prepare` call and
+ * stays in the workspace; every `_run` call then resets the tile descriptors, zeroes y and runs the product kernel
+ * alone.  Arguments as for mmv_spmv_coo / mmv_spmv_csr; the results are theirs (the same kernel on the same flags;
+ * as with every floating-point result of this library, the carries of rows that cross tile borders may be added in
+ * another order from one run to the next, so the last bits can differ between any two calls).
+ *   workspace  the same size as for the one-step call; it belongs to this matrix from `_prepare` on: any other call
+ *              that uses it as its workspace destroys the plan.  `_run` calls on one workspace must not overlap in time.
+ *   errors     `_run` with a workspace that `_prepare` has not prepared for a matrix of this n_rows and nnz (the
+ *              library keeps a mark of both in the workspace; it cannot tell two matrices of the same shape apart)
+ *              writes zeros to y and sets the status word to 2 (mmv_workspace_status); nothing is read out of bounds.
+ *              The index arrays passed to `_run` must be the ones that were prepared (not checked). */
+mmv_status mmv_spmv_coo_prepare(uint64_t n_rows, uint64_t n_cols, uint64_t nnz,
+                                const int32_t *d_row, const int32_t *d_col,
+                                void *d_ws, size_t ws_bytes, void *hip_stream);
+mmv_status mmv_spmv_coo_run(uint64_t n_rows, uint64_t n_cols, uint64_t nnz,
+                            const int32_t *d_row, const int32_t *d_col, const float *d_val,
+                            const float *d_x, float *d_y, mmv_variant v,
+                            void *d_ws, size_t ws_bytes, void *hip_stream);
+mmv_status mmv_spmv_csr_prepare(uint64_t n_rows, uint64_t n_cols, uint64_t nnz,
+                                const int32_t *d_rowptr, const int32_t *d_col,
+                                void *d_ws, size_t ws_bytes, void *hip_stream);
+mmv_status mmv_spmv_csr_run(uint64_t n_rows, uint64_t n_cols, uint64_t nnz,
+                            const int32_t *d_rowptr, const int32_t *d_col, const float *d_val,
+                            const float *d_x, float *d_y, mmv_variant v,
+                            void *d_ws, size_t ws_bytes, void *hip_stream);
+
 /* ---- The parallel primitives of Sec. 4.1, one call each, and the paper's
  * ---- un-fused compositions of them (for comparison with the fused calls above).
 
@@ -260,8 +288,9 @@ mmv_status mmv_segscan_sscr(const void *d_x, const void *d_flags, uint64_t n, vo
                             void *d_ws, size_t ws_bytes, void *hip_stream);
 
 /* Reads the status word the last call on this workspace left behind: 0 = fine,
- * non-zero = a workgroup gave up waiting for a predecessor tile's carry (should
- * never happen; the result of that call is then invalid).  Synchronises
+ * 1 = a workgroup gave up waiting for a predecessor tile's carry (should
+ * never happen; the result of that call is then invalid), 2 = mmv_spmv_*_run on a
+ * workspace that was not prepared for this matrix (y holds zeros).  Synchronises
  * `hip_stream`.  *h_status is HOST memory. */
 mmv_status mmv_workspace_status(const void *d_ws, void *hip_stream, uint32_t *h_status);
 

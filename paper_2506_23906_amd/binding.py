@@ -29,6 +29,7 @@ EXPORTS = [
     "mmv_stream_copy", "mmv_gather_reference", "mmv_status_string", "mmv_tile_elems", "mmv_set_kernel_events",
     "mmv_spmv_csr_workspace_bytes", "mmv_spmv_csr", "mmv_scan", "mmv_compress", "mmv_diff", "mmv_revert",
     "mmv_segsum_scd", "mmv_segscan_sscr", "mmv_segscan_static",
+    "mmv_spmv_coo_prepare", "mmv_spmv_coo_run", "mmv_spmv_csr_prepare", "mmv_spmv_csr_run",
 ]
 STATIC_SCRATCH_BYTES = 1 << 20   # MMV_STATIC_SCRATCH_BYTES
 
@@ -81,6 +82,12 @@ def load() -> ctypes.CDLL:
     lib.mmv_spmv_csr_workspace_bytes.restype = sz
     lib.mmv_spmv_csr.argtypes = [u64, u64, u64, vp, vp, vp, vp, vp, i32, vp, sz, vp]
     lib.mmv_spmv_csr.restype = i32
+    for name in ("mmv_spmv_coo_prepare", "mmv_spmv_csr_prepare"):
+        getattr(lib, name).argtypes = [u64, u64, u64, vp, vp, vp, sz, vp]
+        getattr(lib, name).restype = i32
+    for name in ("mmv_spmv_coo_run", "mmv_spmv_csr_run"):
+        getattr(lib, name).argtypes = [u64, u64, u64, vp, vp, vp, vp, vp, i32, vp, sz, vp]
+        getattr(lib, name).restype = i32
     lib.mmv_scan.argtypes = [vp, u64, vp, i32, i32, vp, sz, vp]
     lib.mmv_scan.restype = i32
     lib.mmv_compress.argtypes = [vp, vp, u64, vp, u64, vp, i32, vp, sz, vp]
@@ -198,6 +205,56 @@ def mmv_spmv_coo(n_rows: int, n_cols: int, row: torch.Tensor, col: torch.Tensor,
     st = lib.mmv_spmv_coo(n_rows, n_cols, nnz, _dev(row, "row"), _dev(col, "col"), _dev(val, "val"), _dev(x, "x"),
                           _dev(y, "y"), _VARIANTS[variant], _dev(ws, "ws"), ws.numel(), _stream_ptr(stream))
     _check(st, "mmv_spmv_coo")
+    return y
+
+
+def mmv_spmv_coo_prepare(n_rows: int, n_cols: int, row: torch.Tensor, col: torch.Tensor,
+                         ws: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+    """First step of the two-step COO SpMV: returns the workspace that holds the plan for this matrix."""
+    nnz = row.numel()
+    if ws is None:
+        ws = new_workspace(MMV_OP_SPMV_COO, MMV_F32_F32, MMV_FLAGS_PACKED32, nnz, row.device)
+    st = load().mmv_spmv_coo_prepare(n_rows, n_cols, nnz, _dev(row, "row"), _dev(col, "col"), _dev(ws, "ws"), ws.numel(),
+                                     _stream_ptr(stream))
+    _check(st, "mmv_spmv_coo_prepare")
+    return ws
+
+
+def mmv_spmv_coo_run(n_rows: int, n_cols: int, row: torch.Tensor, col: torch.Tensor, val: torch.Tensor,
+                     x: torch.Tensor, ws: torch.Tensor, y: torch.Tensor | None = None, variant: str = "mfma",
+                     stream=None) -> torch.Tensor:
+    """Second step: y = A x with the plan that mmv_spmv_coo_prepare left in ws."""
+    if y is None:
+        y = torch.empty(n_rows, dtype=torch.float32, device=val.device)
+    st = load().mmv_spmv_coo_run(n_rows, n_cols, val.numel(), _dev(row, "row"), _dev(col, "col"), _dev(val, "val"),
+                                 _dev(x, "x"), _dev(y, "y"), _VARIANTS[variant], _dev(ws, "ws"), ws.numel(),
+                                 _stream_ptr(stream))
+    _check(st, "mmv_spmv_coo_run")
+    return y
+
+
+def mmv_spmv_csr_prepare(n_rows: int, n_cols: int, rowptr: torch.Tensor, col: torch.Tensor,
+                         ws: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+    """First step of the two-step CSR SpMV: returns the workspace that holds the plan for this matrix."""
+    nnz = col.numel()
+    if ws is None:
+        ws = workspace(mmv_spmv_csr_workspace_bytes(n_rows, nnz), col.device)
+    st = load().mmv_spmv_csr_prepare(n_rows, n_cols, nnz, _dev(rowptr, "rowptr"), _dev(col, "col"), _dev(ws, "ws"),
+                                     ws.numel(), _stream_ptr(stream))
+    _check(st, "mmv_spmv_csr_prepare")
+    return ws
+
+
+def mmv_spmv_csr_run(n_rows: int, n_cols: int, rowptr: torch.Tensor, col: torch.Tensor, val: torch.Tensor,
+                     x: torch.Tensor, ws: torch.Tensor, y: torch.Tensor | None = None, variant: str = "mfma",
+                     stream=None) -> torch.Tensor:
+    """Second step: y = A x with the plan that mmv_spmv_csr_prepare left in ws."""
+    if y is None:
+        y = torch.empty(n_rows, dtype=torch.float32, device=val.device)
+    st = load().mmv_spmv_csr_run(n_rows, n_cols, val.numel(), _dev(rowptr, "rowptr"), _dev(col, "col"), _dev(val, "val"),
+                                 _dev(x, "x"), _dev(y, "y"), _VARIANTS[variant], _dev(ws, "ws"), ws.numel(),
+                                 _stream_ptr(stream))
+    _check(st, "mmv_spmv_csr_run")
     return y
 
 

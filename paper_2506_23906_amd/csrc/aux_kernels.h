@@ -14,6 +14,23 @@ __global__ __launch_bounds__(256) void fill_zero_kernel(uint32_t *a, uint64_t na
     for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < nb; i += stride) b[i] = 0;
 }
 
+// SpMV in two steps, second step: the words of the main kernel's header (but for the hints and the mark of the
+// preparing call, words kHdrHints .. 63) and its descriptors are zeroed, and y; a mark that is not the expected one
+// is reported through the status word (the main kernel then leaves at once).
+__global__ __launch_bounds__(256) void reset_prepared_kernel(uint32_t *ws, uint64_t ws_words, uint32_t *y, uint64_t n_rows,
+                                                             uint32_t expected) {
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    const uint64_t i0 = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const bool stale = ws[kHdrPrepared] != expected;   // (the word is not written here)
+    for (uint64_t i = i0; i < ws_words; i += stride)
+        if (i < kHdrHints || i >= 64) ws[i] = (i == kHdrError && stale) ? kErrNotPrepared : 0u;
+    for (uint64_t i = i0; i < n_rows; i += stride) y[i] = 0;
+}
+// SpMV in two steps, first step, last launch: the mark that the second step looks for.
+__global__ void mark_prepared_kernel(uint32_t *hdr, uint32_t mark) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) hdr[kHdrPrepared] = mark;
+}
+
 // Segmented sum, step "scan of the end markers" of COMPRESS (proof of the SCD / SSCR theorem)
 // at tile granularity: workgroup b counts the segment starts inside tile b (position 0 is not
 // counted: it opens segment 0 whatever its flag says; bits at or beyond n are not counted), and, if asked

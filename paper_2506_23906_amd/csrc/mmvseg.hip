@@ -208,6 +208,71 @@ mmv_status mmv_spmv_coo(uint64_t n_rows, uint64_t n_cols, uint64_t nnz, const in
     return launch_seg<TSpmv, kSpmv>(P, v, s) == hipSuccess ? MMV_OK : MMV_ERR_HIP;
 }
 
+// SpMV in two steps: the mark that the first step leaves in the header for this matrix shape (never 0).
+static uint32_t prepared_mark(mmv_op op, uint64_t n_rows, uint64_t nnz) {
+    uint64_t h = (nnz + 0x9E3779B97F4A7C15ull) * 0xD6E8FEB86659FD93ull + n_rows * 0xCA5A826395121157ull + (uint64_t)op;
+    h ^= h >> 32;
+    return (uint32_t)h | 1u;
+}
+
+mmv_status mmv_spmv_coo_prepare(uint64_t n_rows, uint64_t n_cols, uint64_t nnz, const int32_t *d_row,
+                                const int32_t *d_col, void *d_ws, size_t ws_bytes, void *hip_stream) {
+    if (n_rows >= (1ull << 31) || n_cols >= (1ull << 31) || nnz > kMaxN) return MMV_ERR_INVALID_ARG;
+    if (n_rows == 0 || nnz == 0) return MMV_OK;
+    if (!d_row || !d_col || !d_ws) return MMV_ERR_NULL;
+    if (!aligned16(d_row) || !aligned16(d_col)) return MMV_ERR_INVALID_ARG;
+    const WsLayout L = ws_layout(MMV_OP_SPMV_COO, MMV_F32_F32, MMV_FLAGS_PACKED32, nnz);
+    if (((uintptr_t)d_ws & 255u) != 0 || ws_bytes < L.total) return MMV_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)hip_stream;
+    char *ws = (char *)d_ws;
+    const uint64_t zero_words = L.packed / 4;
+    uint64_t flag_blocks = (nnz + 8191) / 8192;
+    if (flag_blocks > 0x7fffffffull) return MMV_ERR_INVALID_ARG;
+    const uint64_t fill_blocks = (uint64_t)grid_for(zero_words);
+    if (flag_blocks < fill_blocks) flag_blocks = fill_blocks;
+    row_flags_kernel<<<(unsigned)flag_blocks, 256, 0, s>>>(d_row, nnz, (uint32_t *)(ws + L.packed), d_col, (uint32_t *)ws,
+                                                           zero_words, nullptr, 0);
+    if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
+    mark_prepared_kernel<<<1, 64, 0, s>>>((uint32_t *)ws, prepared_mark(MMV_OP_SPMV_COO, n_rows, nnz));
+    return hipGetLastError() == hipSuccess ? MMV_OK : MMV_ERR_HIP;
+}
+
+mmv_status mmv_spmv_coo_run(uint64_t n_rows, uint64_t n_cols, uint64_t nnz, const int32_t *d_row, const int32_t *d_col,
+                            const float *d_val, const float *d_x, float *d_y, mmv_variant v, void *d_ws, size_t ws_bytes,
+                            void *hip_stream) {
+    if (!valid_variant(v) || n_rows >= (1ull << 31) || n_cols >= (1ull << 31) || nnz > kMaxN) return MMV_ERR_INVALID_ARG;
+    if (n_rows == 0) return MMV_OK;
+    if (!d_y) return MMV_ERR_NULL;
+    if (!aligned16(d_y)) return MMV_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)hip_stream;
+    if (nnz == 0) {
+        fill_zero_kernel<<<grid_for(n_rows), 256, 0, s>>>((uint32_t *)d_y, n_rows, nullptr, 0);
+        return hipGetLastError() == hipSuccess ? MMV_OK : MMV_ERR_HIP;
+    }
+    if (!d_row || !d_col || !d_val || !d_x || !d_ws) return MMV_ERR_NULL;
+    if (!aligned16(d_row) || !aligned16(d_col) || !aligned16(d_val) || !aligned16(d_x)) return MMV_ERR_INVALID_ARG;
+    const WsLayout L = ws_layout(MMV_OP_SPMV_COO, MMV_F32_F32, MMV_FLAGS_PACKED32, nnz);
+    if (((uintptr_t)d_ws & 255u) != 0 || ws_bytes < L.total) return MMV_ERR_WORKSPACE;
+    char *ws = (char *)d_ws;
+    Params P = {};
+    P.x = d_val;
+    P.n = nnz;
+    P.row = d_row;
+    P.col = d_col;
+    P.xv = d_x;
+    P.y = d_y;
+    P.hdr = (uint32_t *)ws;
+    P.desc_v = (uint64_t *)(ws + L.desc_v);
+    P.num_tiles = (uint32_t)tiles_for(nnz, MMV_OP_SPMV_COO, MMV_F32_F32);
+    P.fw = (const uint32_t *)(ws + L.packed);
+    P.prepared = prepared_mark(MMV_OP_SPMV_COO, n_rows, nnz);
+    const uint64_t zero_words = L.packed / 4;   // header and descriptors; the flag words behind them stay
+    reset_prepared_kernel<<<grid_for(zero_words > n_rows ? zero_words : n_rows), 256, 0, s>>>(
+        (uint32_t *)ws, zero_words, (uint32_t *)d_y, n_rows, P.prepared);
+    if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
+    return launch_seg<TSpmv, kSpmv>(P, v, s) == hipSuccess ? MMV_OK : MMV_ERR_HIP;
+}
+
 mmv_status mmv_scan(const void *d_x, uint64_t n, void *d_z, mmv_dtype dt, mmv_variant v, void *d_ws, size_t ws_bytes,
                     void *hip_stream) {
     if (!valid_dtype(dt) || !valid_variant(v) || n > kMaxN) return MMV_ERR_INVALID_ARG;
@@ -394,6 +459,86 @@ mmv_status mmv_spmv_csr(uint64_t n_rows, uint64_t n_cols, uint64_t nnz, const in
         if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
     }
     P.tile_count = tile_count;
+    return launch_seg<TSpmv, kSpmvCsr>(P, v, s) == hipSuccess ? MMV_OK : MMV_ERR_HIP;
+}
+
+mmv_status mmv_spmv_csr_prepare(uint64_t n_rows, uint64_t n_cols, uint64_t nnz, const int32_t *d_rowptr,
+                                const int32_t *d_col, void *d_ws, size_t ws_bytes, void *hip_stream) {
+    if (n_rows >= (1ull << 31) || n_cols >= (1ull << 31) || nnz >= (1ull << 31)) return MMV_ERR_INVALID_ARG;
+    if (n_rows == 0 || nnz == 0) return MMV_OK;
+    if (!d_rowptr || !d_col || !d_ws) return MMV_ERR_NULL;
+    if (!aligned16(d_rowptr) || !aligned16(d_col)) return MMV_ERR_INVALID_ARG;
+    const CsrLayout C = csr_layout(n_rows, nnz);
+    if (((uintptr_t)d_ws & 255u) != 0 || ws_bytes < C.total) return MMV_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)hip_stream;
+    char *ws = (char *)d_ws;
+    const WsLayout L = ws_layout(MMV_OP_SPMV_CSR, MMV_F32_F32, MMV_FLAGS_PACKED32, nnz);
+    const uint64_t zero_words = (C.compress_ws + compress_layout(MMV_FLAGS_PACKED32, n_rows).packed) / 4;
+    fill_zero_kernel<<<grid_for(zero_words), 256, 0, s>>>((uint32_t *)ws, zero_words, nullptr, 0);
+    if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
+    const TilePlan plan = tile_plan(MMV_OP_SPMV_CSR, MMV_F32_F32, nnz);
+    uint32_t *fw = (uint32_t *)(ws + C.main_ws + L.packed);
+    uint32_t *tile_count = (uint32_t *)(ws + C.main_ws + L.desc_c);
+    const uint64_t row_blocks = (n_rows + 255) / 256;
+    csr_flags_kernel<<<(unsigned)row_blocks, 256, 0, s>>>(d_rowptr, n_rows, fw, (uint32_t *)(ws + C.rowmask),
+                                                          (uint32_t *)(ws + C.main_ws), plan.reg, plan.unit,
+                                                          tile_count, d_col, nnz);
+    if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
+    {
+        EventsOff quiet;
+        const mmv_status st = compress_impl(nullptr, ws + C.rowmask, n_rows, ws + C.rowmap, n_rows,
+                                            (uint64_t *)(ws + C.rowcount), MMV_FLAGS_PACKED32, ws + C.compress_ws,
+                                            C.rowmask - C.compress_ws, s, true,
+                                            (const uint32_t *)(ws + C.main_ws) + kHdrEmptyRows);
+        if (st != MMV_OK) return st;
+    }
+    if (plan.tiles > kCountSumTilesCsr) {
+        scan_counts_kernel<<<1, 1024, 0, s>>>(tile_count, (uint32_t)plan.tiles, (uint64_t *)(ws + C.rowcount));
+        if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
+    }
+    mark_prepared_kernel<<<1, 64, 0, s>>>((uint32_t *)(ws + C.main_ws), prepared_mark(MMV_OP_SPMV_CSR, n_rows, nnz));
+    return hipGetLastError() == hipSuccess ? MMV_OK : MMV_ERR_HIP;
+}
+
+mmv_status mmv_spmv_csr_run(uint64_t n_rows, uint64_t n_cols, uint64_t nnz, const int32_t *d_rowptr, const int32_t *d_col,
+                            const float *d_val, const float *d_x, float *d_y, mmv_variant v, void *d_ws, size_t ws_bytes,
+                            void *hip_stream) {
+    if (!valid_variant(v) || n_rows >= (1ull << 31) || n_cols >= (1ull << 31) || nnz >= (1ull << 31))
+        return MMV_ERR_INVALID_ARG;
+    if (n_rows == 0) return MMV_OK;
+    if (!d_y) return MMV_ERR_NULL;
+    if (!aligned16(d_y)) return MMV_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)hip_stream;
+    if (nnz == 0) {
+        fill_zero_kernel<<<grid_for(n_rows), 256, 0, s>>>((uint32_t *)d_y, n_rows, nullptr, 0);
+        return hipGetLastError() == hipSuccess ? MMV_OK : MMV_ERR_HIP;
+    }
+    if (!d_rowptr || !d_col || !d_val || !d_x || !d_ws) return MMV_ERR_NULL;
+    if (!aligned16(d_rowptr) || !aligned16(d_col) || !aligned16(d_val) || !aligned16(d_x)) return MMV_ERR_INVALID_ARG;
+    const CsrLayout C = csr_layout(n_rows, nnz);
+    if (((uintptr_t)d_ws & 255u) != 0 || ws_bytes < C.total) return MMV_ERR_WORKSPACE;
+    char *ws = (char *)d_ws;
+    const WsLayout L = ws_layout(MMV_OP_SPMV_CSR, MMV_F32_F32, MMV_FLAGS_PACKED32, nnz);
+    const TilePlan plan = tile_plan(MMV_OP_SPMV_CSR, MMV_F32_F32, nnz);
+    Params P = {};
+    P.x = d_val;
+    P.n = nnz;
+    P.col = d_col;
+    P.xv = d_x;
+    P.y = d_y;
+    P.rowmap = (const uint32_t *)(ws + C.rowmap);
+    P.out_cap = n_rows;
+    P.hdr = (uint32_t *)(ws + C.main_ws);
+    P.desc_v = (uint64_t *)(ws + C.main_ws + L.desc_v);
+    P.fw = (const uint32_t *)(ws + C.main_ws + L.packed);
+    P.count_is_prefix = plan.tiles > kCountSumTilesCsr ? 1u : 0u;
+    P.tile_count = (const uint32_t *)(ws + C.main_ws + L.desc_c);
+    P.prepared = prepared_mark(MMV_OP_SPMV_CSR, n_rows, nnz);
+    // header and value descriptors of the main kernel; the counts, flag words, row mask and row map behind them stay
+    const uint64_t zero_words = L.desc_c / 4;
+    reset_prepared_kernel<<<grid_for(zero_words > n_rows ? zero_words : n_rows), 256, 0, s>>>(
+        (uint32_t *)(ws + C.main_ws), zero_words, (uint32_t *)d_y, n_rows, P.prepared);
+    if (hipGetLastError() != hipSuccess) return MMV_ERR_HIP;
     return launch_seg<TSpmv, kSpmvCsr>(P, v, s) == hipSuccess ? MMV_OK : MMV_ERR_HIP;
 }
 

@@ -46,7 +46,12 @@ __global__ __launch_bounds__(TT::kWaves * 64, MMV_MIN_WAVES_PER_SIMD) void seg_k
     // gathers are the limit and values loaded that late only add to their burst (4-8 % slower).
     // Uniform words, written by the kernel that makes the flags.
     bool late_val = false;
-    if constexpr (kProduct) late_val = hints[kHdrColumnRuns - kHdrHints] != 0;
+    if constexpr (kProduct) {
+        // SpMV in two steps: without the mark of the preparing call for this matrix the flags, counts and row map of
+        // the workspace are not to be trusted (the reset launch has put that into the status word)
+        if (P.prepared && hints[kHdrPrepared - kHdrHints] != P.prepared) return;
+        late_val = hints[kHdrColumnRuns - kHdrHints] != 0;
+    }
     const uint32_t tile = take_tile(P, sm);
     if (kProduct && late_val)
         seg_tile<TT, kOp, kMfma, kProduct>(P, hints, sm, tile);

@@ -142,10 +142,12 @@ constexpr int kRowData = 4;
 
 constexpr uint32_t kHdrTicket = 0;              // workspace header words
 constexpr uint32_t kHdrError = 1;
+constexpr uint32_t kErrLookback = 1, kErrNotPrepared = 2;   // values of the status word
 constexpr uint32_t kHdrHints = 32;              // first of the words the SpMV kernels read as hints (a cache line of
                                                 // their own: the line of the ticket is busy with atomics):
 constexpr uint32_t kHdrEmptyRows = 32;          // CSR SpMV: set when some row of the matrix has no entries
 constexpr uint32_t kHdrColumnRuns = 33;         // SpMV: set when neighbouring entries mostly have consecutive columns
+constexpr uint32_t kHdrPrepared = 34;         // SpMV in two steps: what the preparing call left for this matrix (0: nothing)
 constexpr size_t kHdrBytes = 256;
 
 constexpr uint64_t kStatusInvalid = 0;          // descriptor not written yet
@@ -237,6 +239,7 @@ struct Params {
     const uint32_t *span_count;  // sum of 8- and 16-bit inputs: segment starts per wave span (kWaves of them per tile)
     uint32_t num_tiles;
     TileRegions reg;        // which elements a tile covers
+    uint32_t prepared;      // SpMV in two steps: the mark the preparing call must have left in the header (0: not asked for)
     uint32_t first_round;   // workgroups [0, first_round) are resident together from the start and take the tile
                             // of their own index; the others take tickets
     uint32_t stagger_wgs;   // workgroups [0, stagger_wgs) start after a delay of up to ...

@@ -120,6 +120,24 @@ def test_argument_errors_are_caught_on_the_host(libmmvseg_path):
     assert lib.mmv_spmv_csr(4, 4, 4, None, a16, a16, a16, a16, 0, a16 << 4, 1 << 20, None) == NULL
     assert lib.mmv_spmv_csr(4, 4, 1 << 31, a16, a16, a16, a16, a16, 0, a16 << 4, 1 << 20, None) == INVALID
     assert lib.mmv_spmv_csr(4, 4, 4, a16, a16, a16, a16, a16, 0, a16 << 4, 16, None) == WORKSPACE
+    # SpMV in two steps: the same checks in both steps
+    assert lib.mmv_spmv_coo_prepare(0, 0, 0, None, None, None, 0, None) == OK
+    assert lib.mmv_spmv_coo_prepare(4, 4, 4, a16, None, a16 << 4, 4096, None) == NULL
+    assert lib.mmv_spmv_coo_prepare(4, 4, 4, a16 + 4, a16, a16 << 4, 4096, None) == INVALID       # alignment
+    assert lib.mmv_spmv_coo_prepare(1 << 31, 4, 4, a16, a16, a16 << 4, 4096, None) == INVALID
+    assert lib.mmv_spmv_coo_prepare(4, 4, 4, a16, a16, a16 << 4, 16, None) == WORKSPACE
+    assert lib.mmv_spmv_coo_run(0, 0, 0, None, None, None, None, None, 0, None, 0, None) == OK
+    assert lib.mmv_spmv_coo_run(4, 4, 4, a16, a16, None, a16, a16, 0, a16 << 4, 4096, None) == NULL
+    assert lib.mmv_spmv_coo_run(4, 4, 4, a16, a16, a16, a16, a16, 7, a16 << 4, 4096, None) == INVALID   # variant
+    assert lib.mmv_spmv_coo_run(4, 4, 4, a16, a16, a16, a16, a16, 0, a16 << 4, 16, None) == WORKSPACE
+    assert lib.mmv_spmv_csr_prepare(0, 0, 0, None, None, None, 0, None) == OK
+    assert lib.mmv_spmv_csr_prepare(4, 4, 4, None, a16, a16 << 4, 1 << 20, None) == NULL
+    assert lib.mmv_spmv_csr_prepare(4, 4, 1 << 31, a16, a16, a16 << 4, 1 << 20, None) == INVALID
+    assert lib.mmv_spmv_csr_prepare(4, 4, 4, a16, a16, a16 << 4, 16, None) == WORKSPACE
+    assert lib.mmv_spmv_csr_run(0, 0, 0, None, None, None, None, None, 0, None, 0, None) == OK
+    assert lib.mmv_spmv_csr_run(4, 4, 4, a16, a16, a16, None, a16, 0, a16 << 4, 1 << 20, None) == NULL
+    assert lib.mmv_spmv_csr_run(4, 4, 4, a16, a16, a16, a16, a16, 0, (a16 << 4) + 16, 1 << 20, None) == WORKSPACE  # alignment of d_ws
+    assert lib.mmv_spmv_csr_run(4, 4, 4, a16, a16, a16, a16, a16, 0, a16 << 4, 16, None) == WORKSPACE
     assert lib.mmv_stream_copy(a16, 24, a16, 32, None) == INVALID
     assert lib.mmv_workspace_status(None, None, None) == NULL
     assert lib.mmv_gather_reference(0, None, None, 0, None, None, None) == OK
