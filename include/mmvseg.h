@@ -18,8 +18,9 @@
  *  - `d_ws` is scratch of at least mmv_workspace_bytes(...) bytes, 256-byte
  *    aligned.  The library resets what it needs on every call (inside the
  *    stream, by a small fill kernel); contents are undefined afterwards, except
- *    for the status word read by mmv_workspace_status().  Two calls that share
- *    a workspace must not overlap in time.
+ *    for the status word read by mmv_workspace_status() and for the plan that
+ *    mmv_spmv_coo_prepare / mmv_spmv_csr_prepare leave for their _run calls.
+ *    Two calls that share a workspace must not overlap in time.
  *  - Value, flag, index and output pointers must be 16-byte aligned.  Inputs are read
  *    in aligned 16-byte blocks: the block that holds the last element is read whole
  *    (up to 15 bytes beyond the last element, never beyond that block) and the
