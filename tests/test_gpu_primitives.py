@@ -45,6 +45,24 @@ def test_scan_sizes(dtype, variant):
             assert (np.abs(got.astype(np.float64) - ref) <= TOL[np.dtype(dtype)] * np.maximum(A, 1.0)).all(), (n, variant)
 
 
+@pytest.mark.parametrize("dtype", [np.float16, np.float32])
+def test_scan_at_the_border_between_one_round_of_workgroups_and_several(dtype):
+    """mmv_scan of 16- and 32-bit inputs has tiles of its own length (3 and 2 chunks per wave): exactly one round of
+    512 full tiles (equal tiles, every workgroup its own index), one element more (graded tiles, tickets), one less."""
+    rng = np.random.default_rng(65)
+    dt = B._DTYPES[dev(np.zeros(1, dtype)).dtype]
+    full = B.mmv_tile_elems(B.MMV_OP_SCAN, dt, 1 << 40)
+    assert full == (3 if dtype == np.float16 else 2) * 16384
+    for n in (512 * full - 1, 512 * full, 512 * full + 1):
+        x = random_values(rng, n, dtype)
+        for variant in ("mfma", "shuffle"):
+            z = B.mmv_scan(dev(x), n=n, variant=variant)
+            torch.cuda.synchronize()
+            got, ref = z.cpu().numpy(), oracle.scan(x)
+            A = oracle.scan(np.abs(x.astype(np.float64)))
+            assert (np.abs(got.astype(np.float64) - ref) <= TOL[np.dtype(dtype)] * np.maximum(A, 1.0)).all(), (n, variant)
+
+
 def test_scan_wraps_and_is_segscan_without_flags():
     n = 20_000_000
     x = np.full(n, 127, dtype=np.int8)
