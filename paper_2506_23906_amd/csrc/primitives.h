@@ -122,16 +122,28 @@ __global__ __launch_bounds__(kCompressWaves * 64, 8) void compress_kernel(
     if (wave_cnt <= 4u * kWords * kGroups) {
         // few selected entries in my wave's positions: every lane walks the set bits of its own
         // words (a handful of independent loads per lane) instead of the wave visiting every word
+        // Four entries of a word at a time, their loads all under way before the first store: one memory round trip
+        // per four entries instead of one per entry.
 #pragma unroll
         for (int g = 0; g < kGroups; ++g) {
             const uint64_t p0 = span + (uint64_t)g * kGroupSpan + 64u * lane;
             uint64_t mm = m[g], k = wave_base + before[g];
             while (mm) {
-                const uint64_t p = p0 + (uint32_t)__builtin_ctzll((unsigned long long)mm);
-                mm &= mm - 1;
-                const uint32_t v = x ? __builtin_nontemporal_load(x + p) : (uint32_t)p;
-                if (k < out_cap) out[k] = v;
-                ++k;
+                uint64_t p[4];
+                uint32_t v[4];
+                bool on[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    on[i] = mm != 0;
+                    p[i] = p0 + (on[i] ? (uint32_t)__builtin_ctzll((unsigned long long)mm) : 0u);
+                    mm &= mm - 1;   // (0 stays 0)
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i) v[i] = !on[i] ? 0u : (x ? __builtin_nontemporal_load(x + p[i]) : (uint32_t)p[i]);
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (on[i] && k + i < out_cap) out[k + i] = v[i];
+                k += 4;
             }
         }
         return;
