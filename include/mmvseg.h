@@ -160,15 +160,16 @@ mmv_status mmv_segscan_static(const void *d_x, const void *d_flags, uint64_t n, 
  *                 1 + #{i >= 1 : f(i) = 1} for n >= 1
  * Floating point: as for mmv_segscan (a sum is off by the rounding of the prefixes of the rows of 32 it starts
  * and ends in; a non-finite value can reach the sums of the segments that share its row of 32).  16-bit inputs
- * with MMV_VARIANT_MFMA on vectors longer than one round of workgroups speculate over chunks of 2048 elements
+ * on vectors longer than one round of workgroups (either variant) speculate over chunks of 2048 elements
  * (2048-aligned): there a sum is the difference of two prefixes of its chunk and is off by their rounding
  * (2^-24 of the chunk's running sum each), and a non-finite value reaches the other sums of its chunk.
  * Sums with index >= out_capacity are not written (d_nseg still holds the true
  * count); pass out_capacity = n to be safe.  The number of segments must be
  * below 2^32 (counts are carried in 32 bits).
- * Speed on long vectors (n = 2^28, % of the HBM peak): 8- and 16-bit inputs are fastest with
- * MMV_VARIANT_MFMA (58 % against 30 %), fp32 inputs with MMV_VARIANT_SHUFFLE (74 % against 51 %: its tiles
- * are twice as long, which the registers of the matrix-core variant do not allow). */
+ * Speed on long vectors (n = 2^28, 0.1 % of the flags set, % of the HBM peak): 8- and 16-bit inputs are fastest
+ * with MMV_VARIANT_MFMA (bytes 59 % against 53 %, fp16 68 % against 61 %: the same kernel, its 32x32 tiles scanned
+ * by the matrix cores or by vector instructions), fp32 inputs with MMV_VARIANT_SHUFFLE (74 % against 51 %: its
+ * tiles are twice as long, which the registers of the matrix-core variant do not allow). */
 mmv_status mmv_segsum(const void *d_x, const void *d_flags, uint64_t n,
                       void *d_out, uint64_t out_capacity, uint64_t *d_nseg,
                       mmv_dtype dt, mmv_flag_fmt ff, mmv_variant v,
@@ -328,8 +329,9 @@ const char *mmv_status_string(mmv_status s);
  * smaller for short inputs so that every compute unit gets one).  For tests that want
  * to straddle tile borders and for sizing: the workspace holds one 8-byte descriptor
  * per tile (the segmented sum 40 more bytes of counts per tile).  The value is that
- * of the matrix-core variant, whose segmented sum of 8- and 16-bit inputs has longer
- * tiles than the scan; mmv_scan of 16-bit inputs has longer tiles than mmv_segscan.
+ * of the matrix-core variant (the other one differs for fp32 sums and for bytes under exclusive or).
+ * The segmented sum of 8- and 16-bit inputs has longer tiles than the scan; mmv_scan of 16- and
+ * 32-bit inputs has longer tiles than mmv_segscan.
  * 0 for invalid arguments. */
 uint32_t mmv_tile_elems(mmv_op op, mmv_dtype dt, uint64_t n);
 

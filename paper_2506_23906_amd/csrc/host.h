@@ -56,7 +56,8 @@ inline int row_form_cpw(mmv_op op, mmv_dtype dt, bool mfma) {
 // Most chunks per wave of the segmented sum that speculates over whole chunks and streams through its spans
 // (sum_tile; 0: this operation, type or variant has no such form).
 inline int chunk_form_cpw(mmv_op op, mmv_dtype dt, bool mfma) {
-    if (op != MMV_OP_SEGSUM || !mfma) return 0;
+    (void)mfma;   // both variants have it
+    if (op != MMV_OP_SEGSUM) return 0;
     if (dt == MMV_I8_I32 && chunk_sum_kernel<TI8, kSum, true>()) return sum_cpw<TI8>();
     if (dt == MMV_U8_XOR && chunk_sum_kernel<TX8, kSum, true>()) return sum_cpw<TX8>();
     if (dt == MMV_F16_F32 && chunk_sum_kernel<TF16, kSum, true>()) return sum_cpw<TF16>();
@@ -287,7 +288,7 @@ template <typename TT, int kOp, bool kMfma> hipError_t launch_variant(Params P, 
     static std::atomic<uint32_t> occupancy[2][kMaxDevices];
     void (*kernel)(Params, const uint32_t *) = seg_kernel<TT, kOp, kMfma>;
     if constexpr (chunk_sum_kernel<TT, kOp, kMfma>()) {
-        if (chunk_form) kernel = sum_kernel<TT>;
+        if (chunk_form) kernel = sum_kernel<TT, kMfma>;
     }
     const uint32_t resident = resident_workgroups((const void *)kernel, TT::kWaves * 64, occupancy[chunk_form ? 1 : 0]);
     P.first_round = P.num_tiles < resident ? P.num_tiles : resident;

@@ -32,6 +32,7 @@
 
 #include <atomic>
 #include <mutex>
+#include <type_traits>
 
 #include "mmvseg.h"
 

@@ -61,14 +61,14 @@ __global__ __launch_bounds__(TT::kWaves * 64, MMV_MIN_WAVES_PER_SIMD) void seg_k
 
 // The segmented sum of 8- and 16-bit inputs (speculation over whole chunks): its waves keep less in LDS and in
 // registers than those of the scan, so more workgroups share a compute unit.
-template <typename TT>
+template <typename TT, bool kMfma>
 __global__ __launch_bounds__(TT::kWaves * 64, sum_waves_per_simd<TT>()) void sum_kernel(Params P, const uint32_t *__restrict__) {
     __shared__ SumShared<TT> sm;
 #if MMV_LOAD_PRIO
     __builtin_amdgcn_s_setprio(MMV_LOAD_PRIO);
 #endif
     const uint32_t tile = take_tile(P, sm);
-    sum_tile<TT>(P, sm, tile);
+    sum_tile<TT, kMfma>(P, sm, tile);
 }
 
 }  // namespace

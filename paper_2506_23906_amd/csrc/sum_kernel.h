@@ -1,5 +1,6 @@
 // libmmvseg, part of the one translation unit mmvseg.hip (included there, in order).
-// The tile body of the segmented sum for 8- and 16-bit inputs in the matrix-core variant.
+// The tile body of the segmented sum for 8- and 16-bit inputs on long vectors (both variants: the 32x32 tiles that
+// hold segment ends are scanned by the matrix cores, SpecMfma, or by vector instructions, SpecVector).
 #pragma once
 
 namespace {
@@ -13,7 +14,8 @@ namespace {
 //     [T(r) + x-bar_r(p)] - [T(r') + x-bar_r'(s - 1)],        T = exclusive scan of the row totals,
 // the difference of two speculative prefixes of the chunk, exactly as Algorithm SCD takes the difference of two
 // prefixes of the whole vector; if no flag of the chunk precedes p, it is carry + T(r) + x-bar_r(p).  The row
-// scans x-bar come from the matrix cores and are made only for 32x32 tiles that the ends of the chunk need.
+// scans x-bar come from the matrix cores (vector instructions in the ablation variant) and are made only for
+// 32x32 tiles that the ends of the chunk need.
 // Between chunks, waves and tiles the segmented pair (value after the last flag, any flag) is carried as in the
 // scan; the one row of a chunk whose last flag matters there is known to the whole wave, so its masked dot
 // product uses masks made on the scalar unit.
@@ -61,6 +63,101 @@ template <bool kBf16> struct TilePartHalf {
 };
 template <> struct TilePart<TF16> : TilePartHalf<false> {};
 template <> struct TilePart<TBF16> : TilePartHalf<true> {};
+
+// The row scans of one 32x32 tile without the matrix cores, for the ablation variant of this kernel: same input
+// (operand layout: lane (c, h) holds one half of row c) and same output layout as SpecMfma (lane (c, h) gets
+// positions 8 q + 4 h .. + 3 of row c in acc[4 q .. 4 q + 3]).  One v_permlane32_swap per register gives both
+// lanes of a row all of it; each then scans the row with vector instructions and keeps its sixteen positions.
+template <typename TT> struct SpecVector;
+// (a register of the half-wave that holds the lower half-rows / the upper half-rows, in every lane)
+__device__ __forceinline__ void both_halves(uint32_t mine, uint32_t &lower, uint32_t &upper) {
+    const auto sw = __builtin_amdgcn_permlane32_swap(mine, mine, false, false);
+    lower = (uint32_t)sw[0];
+    upper = (uint32_t)sw[1];
+}
+template <> struct SpecVector<TI8> {
+    static __device__ __forceinline__ void run(const v4u *raw, int lane, uint32_t (&acc)[16]) {
+        const bool h = lane >= 32;
+        // words of the row in position order: w[2 q] = positions 8 q .. + 3, w[2 q + 1] = 8 q + 4 .. + 7
+        uint32_t w[8];
+#pragma unroll
+        for (int d = 0; d < 4; ++d) both_halves(raw[0][d], w[d], w[4 + d]);
+        int before = 0;   // sum of the words before the one at hand
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int s0 = __builtin_amdgcn_sdot4((int)w[2 * q], 0x01010101, before, false);   // ... up to and with word 2 q
+            const uint32_t word = h ? w[2 * q + 1] : w[2 * q];
+            const int base = h ? s0 : before;
+            acc[4 * q + 0] = (uint32_t)__builtin_amdgcn_sdot4((int)word, 0x00000001, base, false);
+            acc[4 * q + 1] = (uint32_t)__builtin_amdgcn_sdot4((int)word, 0x00000101, base, false);
+            acc[4 * q + 2] = (uint32_t)__builtin_amdgcn_sdot4((int)word, 0x00010101, base, false);
+            acc[4 * q + 3] = (uint32_t)__builtin_amdgcn_sdot4((int)word, 0x01010101, base, false);
+            before = __builtin_amdgcn_sdot4((int)w[2 * q + 1], 0x01010101, s0, false);
+        }
+    }
+};
+template <> struct SpecVector<TX8> {
+    static __device__ __forceinline__ uint32_t fold(uint32_t x) {   // xor of the four bytes, in the low byte
+        x ^= x >> 16;
+        x ^= x >> 8;
+        return x & 0xFFu;
+    }
+    static __device__ __forceinline__ void run(const v4u *raw, int lane, XorWord (&acc)[16]) {
+        const bool h = lane >= 32;
+        uint32_t w[8];
+#pragma unroll
+        for (int d = 0; d < 4; ++d) both_halves(raw[0][d], w[d], w[4 + d]);
+        uint32_t before = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const uint32_t s0 = before ^ fold(w[2 * q]);
+            const uint32_t word = h ? w[2 * q + 1] : w[2 * q];
+            const uint32_t base = h ? s0 : before;
+            // byte j of `run` = xor of bytes 0 .. j of the word
+            uint32_t run = word ^ (word << 8);
+            run ^= run << 16;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[4 * q + j] = XorWord(((run >> (8 * j)) & 0xFFu) ^ base);
+            before = s0 ^ fold(w[2 * q + 1]);
+        }
+    }
+};
+template <bool kBf16> struct SpecVectorHalf {
+    static __device__ __forceinline__ float lo(uint32_t pair) {
+        return kBf16 ? from_bits<float>(pair << 16) : (float)__builtin_bit_cast(_Float16, (uint16_t)(pair & 0xFFFFu));
+    }
+    static __device__ __forceinline__ float hi(uint32_t pair) {
+        return kBf16 ? from_bits<float>(pair & 0xFFFF0000u) : (float)__builtin_bit_cast(_Float16, (uint16_t)(pair >> 16));
+    }
+    static __device__ __forceinline__ void run(const v4u *raw, int lane, float (&acc)[16]) {
+        const bool h = lane >= 32;
+        // run q of eight positions (8 q .. 8 q + 7) is word ks = q / 2 of the half-wave q % 2: four pairs each
+        uint32_t r[4][4];
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int d = 0; d < 4; ++d) both_halves(raw[ks][d], r[2 * ks][d], r[2 * ks + 1][d]);
+        float before = 0.0f;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            // my four positions of this run: pairs 2 h and 2 h + 1; the pairs before them belong to the other lane
+            const float first = (lo(r[q][0]) + hi(r[q][0])) + (lo(r[q][1]) + hi(r[q][1]));   // positions 8 q .. + 3
+            const uint32_t p0 = h ? r[q][2] : r[q][0], p1 = h ? r[q][3] : r[q][1];
+            float s = h ? before + first : before;
+            s += lo(p0);
+            acc[4 * q + 0] = s;
+            s += hi(p0);
+            acc[4 * q + 1] = s;
+            s += lo(p1);
+            acc[4 * q + 2] = s;
+            s += hi(p1);
+            acc[4 * q + 3] = s;
+            before = (before + first) + ((lo(r[q][2]) + hi(r[q][2])) + (lo(r[q][3]) + hi(r[q][3])));
+        }
+    }
+};
+template <> struct SpecVector<TF16> : SpecVectorHalf<false> {};
+template <> struct SpecVector<TBF16> : SpecVectorHalf<true> {};
 
 // Sum of the elements a lane holds of one 32x32 tile that lie at positions below p of their row (p is the same
 // for all lanes, so the masks of both half-waves are made on the scalar unit and a lane picks its own).
@@ -153,7 +250,7 @@ template <> struct ScanPair<TI8> {
 // tile spread over more elements).
 template <typename TT> constexpr int sum_cpw() { return sizeof(typename TT::in_t) == 1 ? MMV_SUM_CPW_I8 : MMV_SUM_CPW_F16; }
 template <typename TT, int kOp, bool kMfma> constexpr bool chunk_sum_kernel() {
-    return MMV_CHUNK_SUM != 0 && kOp == kSum && kMfma && sizeof(typename TT::in_t) <= 2;
+    return MMV_CHUNK_SUM != 0 && kOp == kSum && sizeof(typename TT::in_t) <= 2;
 }
 
 // The LDS rows of one wave: the row scans x-bar of the chunk at hand.  Row scans of 32 bytes fit 16 bits
@@ -226,9 +323,10 @@ __device__ __forceinline__ void sum_load_slot(const Params &P, uint64_t chunk_ba
 // end comes a flag; kept in LDS and written at the end, when the carry is known).  The index of an output is the
 // number of segment starts before its segment; the starts before a wave's span come from the counting kernel.
 // So a tile can be long (few tickets, barriers and look-backs per element) without holding more in registers.
-template <typename TT>
+template <typename TT, bool kMfma>
 __device__ __forceinline__ void sum_tile(const Params &P, SumShared<TT> &sm, const uint32_t tile) {
     typedef SumRows<TT> Rows;
+    typedef typename std::conditional<kMfma, SpecMfma<TT>, SpecVector<TT>>::type Spec;   // how a 32x32 tile is scanned
     typedef typename TT::acc_t A;
     constexpr int kWaves = TT::kWaves;
     constexpr int kDepth = sum_load_depth<TT>();
@@ -328,12 +426,12 @@ __device__ __forceinline__ void sum_tile(const Params &P, SumShared<TT> &sm, con
                     const bool need0 = (uint32_t)rows_with_ends != 0 || (need1 && (uint32_t)rows_flagged != 0);
                     if (need0) {
                         A acc[16];
-                        SpecMfma<TT>::run(raw, lane, acc);
+                        Spec::run(raw, lane, acc);
                         Rows::store(rows, 0, lane, acc);
                     }
                     if (need1) {
                         A acc[16];
-                        SpecMfma<TT>::run(raw + K, lane, acc);
+                        Spec::run(raw + K, lane, acc);
                         Rows::store(rows, 1, lane, acc);
                     }
                     // a segment that ends in my row and has no flag there starts at the last flag of the last flagged

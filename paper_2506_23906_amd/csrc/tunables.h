@@ -104,7 +104,7 @@ namespace {
 #define MMV_POLL_WINDOWS 1   // windows of 64 tile descriptors that a look-back started ahead of time asks for at once (2 and 4: 3 to 5 % slower, the descriptor loads compete with the streams)
 #endif
 #ifndef MMV_CHUNK_SUM
-#define MMV_CHUNK_SUM 1   // 1: the segmented sum of 8- and 16-bit inputs (matrix-core variant) speculates over whole chunks
+#define MMV_CHUNK_SUM 1   // 1: the segmented sum of 8- and 16-bit inputs on long vectors speculates over whole chunks
 #endif
 #ifndef MMV_SHORT_SUMS_ROW_FORM
 #define MMV_SHORT_SUMS_ROW_FORM 1   // 1: sums that fit one round of workgroups use the scan's tile body (see tile_plan)

@@ -46,9 +46,10 @@ def test_host_only_entry_points(libmmvseg_path):
     # one 8-byte descriptor per tile: at least n / (largest tile), and the end of the vector is cut finer
     assert 256 + (n // tile) * 8 <= scan <= 256 + 4 * (n // tile) * 8 and scan % 256 == 0
     ssum = B.mmv_workspace_bytes(B.MMV_OP_SEGSUM, B.MMV_I8_I32, B.MMV_FLAGS_PACKED32, n)
-    # descriptors, 8 bytes of counts per tile, 4 bytes of counts per wave span (8 waves to a tile)
-    # (each of the three arrays rounded to 256 bytes)
-    assert abs(ssum - (256 + 6 * (scan - 256))) <= 3 * 256 and ssum % 256 == 0
+    # descriptors, 8 bytes of counts per tile, 4 bytes of counts per wave span (8 waves to a tile): 48 bytes per tile
+    # (each of the three arrays rounded to 256 bytes); the sum of bytes has longer tiles than the scan, cut finer at both ends
+    tsum = B.mmv_tile_elems(B.MMV_OP_SEGSUM, B.MMV_I8_I32, n)
+    assert tsum >= tile and 256 + (n // tsum) * 48 <= ssum <= 256 + 4 * (n // tsum) * 48 + 3 * 256 and ssum % 256 == 0
     assert B.mmv_workspace_bytes(B.MMV_OP_SEGSCAN, B.MMV_I8_I32, B.MMV_FLAGS_U8, n) == scan + n // 8
     assert B.mmv_workspace_bytes(B.MMV_OP_SEGSCAN, 7, B.MMV_FLAGS_U8, n) == 0      # bad dtype
     assert B.mmv_workspace_bytes(99, B.MMV_I8_I32, B.MMV_FLAGS_U8, n) == 0         # bad op

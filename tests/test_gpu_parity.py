@@ -303,8 +303,9 @@ def test_bf16_2p24_uniform_len(variant):
     check_sum(out, nseg, x32, f, tol=1e-2)
 
 
+@pytest.mark.parametrize("variant", VARIANTS)
 @pytest.mark.parametrize("density", [2e-5, 1e-3, 0.05])
-def test_bf16_sums_longer_than_one_round_of_workgroups(density):
+def test_bf16_sums_longer_than_one_round_of_workgroups(density, variant):
     """The kernel that streams through long spans, bf16 instantiation (see test_sums_longer_than_one_round_of_workgroups
     for the margin: speculation over chunks of 2048 values; bf16 inputs carry 8 significant bits, their sums are
     rounded like those of any other fp32 values)."""
@@ -314,7 +315,7 @@ def test_bf16_sums_longer_than_one_round_of_workgroups(density):
     xt, x32 = _bf16_values(rng, n)
     f = W.uniform_density_flags(n, density, seed=n % 1000)
     print("long bf16 sum", density, n, flush=True)
-    out, nseg = run_segsum(x32, f, "mfma", xt=xt)
+    out, nseg = run_segsum(x32, f, variant, xt=xt)
     check_sum(out, nseg, x32, f, tol=1e-2, margin=1e-4)
 
 
@@ -339,12 +340,13 @@ def test_workload2_f16_geometric(log2n, variant):
         check_scan(run_segscan(x, f, variant), x, f)
 
 
+@pytest.mark.parametrize("variant", VARIANTS)
 @pytest.mark.parametrize("density", [0.0, 1e-7, 2e-5, 1e-3, 0.05])
 @pytest.mark.parametrize("dtype", [np.int8, np.float16])
-def test_sums_longer_than_one_round_of_workgroups(dtype, density):
+def test_sums_longer_than_one_round_of_workgroups(dtype, density, variant):
     """The segmented sum of 8- and 16-bit inputs has a kernel and tiles of its own on vectors longer than one round of
     workgroups (longer tiles: a wave streams through its span), with short tiles at both ends and full ones between
-    them.  Densities from no flag at all (one segment: every tile hands on a plain sum, the one output waits for the
+    them; in the ablation variant the same kernel scans its 32x32 tiles with vector instructions.  Densities from no flag at all (one segment: every tile hands on a plain sum, the one output waits for the
     carry of all tiles) over a handful of flags (most tiles without one) to a flag in every row."""
     rng = np.random.default_rng(78)
     full = B.mmv_tile_elems(B.MMV_OP_SEGSUM, B._DTYPES[torch.from_numpy(np.zeros(1, dtype=dtype)).dtype], 1 << 40)
@@ -353,8 +355,8 @@ def test_sums_longer_than_one_round_of_workgroups(dtype, density):
     for n in sizes:
         x = random_values(rng, n, dtype)
         f = W.uniform_density_flags(n, density, seed=n % 1000)
-        print("long sum", dtype.__name__, density, n, int(f.sum()), flush=True)
-        out, nseg = run_segsum(x, f, "mfma")
+        print("long sum", dtype.__name__, density, variant, n, int(f.sum()), flush=True)
+        out, nseg = run_segsum(x, f, variant)
         # This kernel speculates over whole chunks of 2048 values, not rows of 32: a sum is the difference of two
         # prefixes of its chunk, each rounded to fp32 at the size the prefix has there.  Over 2048 values from N(0,1)
         # a prefix stays below 512 (11 sigma), where one rounding is 2^-15 = 3e-5: the margin against max(A, 1) is
