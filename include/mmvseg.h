@@ -167,7 +167,7 @@ mmv_status mmv_segscan_static(const void *d_x, const void *d_flags, uint64_t n, 
  * count); pass out_capacity = n to be safe.  The number of segments must be
  * below 2^32 (counts are carried in 32 bits).
  * Speed on long vectors (n = 2^28, 0.1 % of the flags set, % of the HBM peak): 8- and 16-bit inputs are fastest
- * with MMV_VARIANT_MFMA (bytes 59 % against 53 %, fp16 68 % against 61 %: the same kernel, its 32x32 tiles scanned
+ * with MMV_VARIANT_MFMA (bytes 59 % against 52 %, fp16 69 % against 60 %: the same kernel, its 32x32 tiles scanned
  * by the matrix cores or by vector instructions), fp32 inputs with MMV_VARIANT_SHUFFLE (74 % against 51 %: its
  * tiles are twice as long, which the registers of the matrix-core variant do not allow). */
 mmv_status mmv_segsum(const void *d_x, const void *d_flags, uint64_t n,
